@@ -1,0 +1,219 @@
+/*
+ * Definition oracle for the two operators of "Blockbuster, Part 1" that this
+ * repository implements on the GPU:
+ *
+ *   - RMSNorm -> FFN-SwiGLU   (paper: Example 3, original array program and
+ *                              its initial block program)
+ *   - LayerNorm -> matmul     (paper: Example 2, original array program,
+ *                              the sigma formula of Example 2)
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  Only the tests, the smoke
+ * check and the bench's cpu_baseline leg may load it.  It shares no source,
+ * header, table or helper with the HIP library.
+ *
+ * The fused kernels the paper derives are obtained by logic-preserving
+ * rewrites (Section 3), so what they compute is exactly the plain unfused
+ * definition.  The oracle is that definition written out in fp64, one row at
+ * a time, with no blocking, fusion or reordering: every sum runs over its
+ * index in increasing order.
+ *
+ * Inputs are bf16 bit patterns (uint16_t) widened exactly to double, so a
+ * comparison with the GPU measures the kernel's arithmetic and not the
+ * quantisation of the inputs.  All pointers are HOST pointers, dense
+ * row-major.  Output is double.
+ *
+ * Where the paper is silent the following readings apply (they are the
+ * operator statement this build was given):
+ *   - the paper's listing for RMSNorm uses 1/sqrt(sum x^2) with no 1/D and no
+ *     eps (Example 3, initial block program); here the root MEAN square is
+ *     used and eps is added to the mean inside the square root;
+ *   - a per-column gain g (resp. gamma, beta for LayerNorm) multiplies the
+ *     normalised row before the matmuls; the paper has none;
+ *   - Swish/SiLU x/(1+exp(-x)) is applied to the product with W1 (the paper's
+ *     W), the product with W3 (the paper's V) is the linear gate, W2 is the
+ *     paper's U;
+ *   - LayerNorm uses the biased variance, as the paper's sigma formula
+ *     sqrt(s2/k - (s1/k)^2) does; it is evaluated here in the two-pass form
+ *     sum((x-mu)^2)/k, which is the same number in exact arithmetic.
+ *
+ * Parity pins: tests/test_oracle_pins.py (brute force with exact rationals,
+ * closed forms, invariants, a torch fp64 composition, the paper's Rule 4 and
+ * Rule 5 identities through oracle/listing_oracle.py).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static inline double bf16_to_double(uint16_t h) {
+    uint32_t u = ((uint32_t)h) << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+int bb_oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void bb_oracle_set_num_threads(int n) {
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/*
+ * Y[i,:] = ( SiLU(xh W1) * (xh W3) ) W2,  xh = g * x / sqrt(mean(x^2) + eps)
+ *
+ * X [M,D], g [D], W1 [D,F], W3 [D,F], W2 [F,D] : bf16 bit patterns.
+ * rows: optional list of nrows row indices of X to evaluate (NULL = rows
+ *       0..nrows-1, and then nrows must be <= M).
+ * Y [nrows, D] double, row k of Y belongs to row rows[k] of X.
+ * Returns 0, or -1 on a bad argument / allocation failure.
+ */
+int bb_oracle_rmsnorm_swiglu_ffn(const uint16_t* X, const uint16_t* g,
+                                 const uint16_t* W1, const uint16_t* W3,
+                                 const uint16_t* W2, double* Y,
+                                 int64_t M, int64_t D, int64_t F, double eps,
+                                 const int64_t* rows, int64_t nrows) {
+    if (M < 0 || D <= 0 || F <= 0 || nrows < 0) return -1;
+    if (!rows && nrows > M) return -1;
+    if (nrows == 0) return 0;
+    if (!X || !g || !W1 || !W3 || !W2 || !Y) return -1;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double* xh = (double*)malloc(sizeof(double) * (size_t)D);
+        double* a = (double*)malloc(sizeof(double) * (size_t)F);
+        double* b = (double*)malloc(sizeof(double) * (size_t)F);
+        if (!xh || !a || !b) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp barrier
+        int bad;
+#pragma omp atomic read
+        bad = fail;
+        if (!bad) {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t k = 0; k < nrows; ++k) {
+                const int64_t i = rows ? rows[k] : k;
+                if (i < 0 || i >= M) {
+#pragma omp atomic write
+                    fail = 1;
+                    continue;
+                }
+                const uint16_t* x = X + (size_t)i * (size_t)D;
+                /* row statistic: mean of squares */
+                double s = 0.0;
+                for (int64_t d = 0; d < D; ++d) {
+                    const double v = bf16_to_double(x[d]);
+                    s += v * v;
+                }
+                const double r = 1.0 / sqrt(s / (double)D + eps);
+                /* normalised, gained row */
+                for (int64_t d = 0; d < D; ++d)
+                    xh[d] = bf16_to_double(g[d]) * bf16_to_double(x[d]) * r;
+                /* the two up-projections */
+                for (int64_t f = 0; f < F; ++f) { a[f] = 0.0; b[f] = 0.0; }
+                for (int64_t d = 0; d < D; ++d) {
+                    const double xv = xh[d];
+                    const uint16_t* w1 = W1 + (size_t)d * (size_t)F;
+                    const uint16_t* w3 = W3 + (size_t)d * (size_t)F;
+                    for (int64_t f = 0; f < F; ++f) {
+                        a[f] += xv * bf16_to_double(w1[f]);
+                        b[f] += xv * bf16_to_double(w3[f]);
+                    }
+                }
+                /* Swish on the W1 branch, Hadamard product with the gate */
+                for (int64_t f = 0; f < F; ++f)
+                    a[f] = a[f] / (1.0 + exp(-a[f])) * b[f];
+                /* down-projection */
+                double* y = Y + (size_t)k * (size_t)D;
+                for (int64_t n = 0; n < D; ++n) y[n] = 0.0;
+                for (int64_t f = 0; f < F; ++f) {
+                    const double hv = a[f];
+                    const uint16_t* w2 = W2 + (size_t)f * (size_t)D;
+                    for (int64_t n = 0; n < D; ++n)
+                        y[n] += hv * bf16_to_double(w2[n]);
+                }
+            }
+        }
+        free(xh); free(a); free(b);
+    }
+    return fail ? -1 : 0;
+}
+
+/*
+ * Y[i,:] = LN(x) W,  LN(x) = gamma * (x - mu) / sqrt(var + eps) + beta,
+ * mu = mean(x), var = mean((x-mu)^2)  (biased).
+ *
+ * X [M,D], gamma [D], beta [D], W [D,N] : bf16 bit patterns.
+ * rows / nrows as above.  Y [nrows, N] double.
+ */
+int bb_oracle_layernorm_matmul(const uint16_t* X, const uint16_t* gamma,
+                               const uint16_t* beta, const uint16_t* W,
+                               double* Y, int64_t M, int64_t D, int64_t N,
+                               double eps, const int64_t* rows, int64_t nrows) {
+    if (M < 0 || D <= 0 || N <= 0 || nrows < 0) return -1;
+    if (!rows && nrows > M) return -1;
+    if (nrows == 0) return 0;
+    if (!X || !gamma || !beta || !W || !Y) return -1;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double* z = (double*)malloc(sizeof(double) * (size_t)D);
+        if (!z) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp barrier
+        int bad;
+#pragma omp atomic read
+        bad = fail;
+        if (!bad) {
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t k = 0; k < nrows; ++k) {
+                const int64_t i = rows ? rows[k] : k;
+                if (i < 0 || i >= M) {
+#pragma omp atomic write
+                    fail = 1;
+                    continue;
+                }
+                const uint16_t* x = X + (size_t)i * (size_t)D;
+                double s1 = 0.0;
+                for (int64_t d = 0; d < D; ++d) s1 += bf16_to_double(x[d]);
+                const double mu = s1 / (double)D;
+                double s2 = 0.0;
+                for (int64_t d = 0; d < D; ++d) {
+                    const double c = bf16_to_double(x[d]) - mu;
+                    s2 += c * c;
+                }
+                const double r = 1.0 / sqrt(s2 / (double)D + eps);
+                for (int64_t d = 0; d < D; ++d)
+                    z[d] = bf16_to_double(gamma[d]) * (bf16_to_double(x[d]) - mu) * r
+                           + bf16_to_double(beta[d]);
+                double* y = Y + (size_t)k * (size_t)N;
+                for (int64_t n = 0; n < N; ++n) y[n] = 0.0;
+                for (int64_t d = 0; d < D; ++d) {
+                    const double zv = z[d];
+                    const uint16_t* w = W + (size_t)d * (size_t)N;
+                    for (int64_t n = 0; n < N; ++n)
+                        y[n] += zv * bf16_to_double(w[n]);
+                }
+            }
+        }
+        free(z);
+    }
+    return fail ? -1 : 0;
+}
