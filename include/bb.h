@@ -1,0 +1,192 @@
+/*
+ * bb -- fused RMSNorm -> FFN-SwiGLU and LayerNorm -> matmul for AMD MI355X
+ * (gfx950), the two fused operators derived in "Blockbuster, Part 1:
+ * Block-level AI Operator Fusion" (Example 3, Flash-RMSNorm+FFN-SwiGLU, and
+ * Example 2, Flash-LayerNorm+Matmul).
+ *
+ * C ABI.  Every tensor pointer is a DEVICE pointer to bf16 elements (raw
+ * 16-bit patterns), dense row-major with no strides, unless a parameter says
+ * otherwise.  The caller owns every buffer; the library keeps no user pointer
+ * after a call returns.  Inputs are only read, the output is only written and
+ * must not overlap any input.  Calls enqueue work on `stream` (a hipStream_t
+ * passed as void*, NULL = the default stream) and return without
+ * synchronising; no host<->device copy is made.  No exception crosses the
+ * boundary and nothing is printed unless the environment variable BB_LOG is
+ * set.  Only gfx950 devices are supported.
+ *
+ * Every function returning int returns BB_OK (0) or a negative bb_status.
+ * Argument checks happen before anything is launched, so a failed call has
+ * no effect on the output buffer.
+ */
+#ifndef BB_H_
+#define BB_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BB_VERSION 100 /* major*10000 + minor*100 + patch */
+
+typedef enum bb_status {
+    BB_OK = 0,
+    BB_ERR_NULL = -1,      /* a pointer is NULL while its extent is > 0           */
+    BB_ERR_SHAPE = -2,     /* M < 0, D/F/N <= 0, D/F/N not a multiple of 8, or a
+                              size beyond the supported range (2^31-1 elements
+                              per row-major dimension product per tile index)   */
+    BB_ERR_ALIGN = -3,     /* a pointer is not 16-byte aligned                    */
+    BB_ERR_EPS = -4,       /* eps negative, NaN or infinite                       */
+    BB_ERR_ALIAS = -5,     /* the output overlaps an input                        */
+    BB_ERR_ARCH = -6,      /* the current device is not gfx950                    */
+    BB_ERR_WORKSPACE = -7, /* workspace missing, too small or misaligned          */
+    BB_ERR_HIP = -8,       /* a HIP call failed; see bb_last_hip_error()          */
+    BB_ERR_VARIANT = -9    /* unknown variant, or one that cannot run this shape  */
+} bb_status;
+
+/* Which fused block program of Example 3 a call of bb_rmsnorm_swiglu_ffn runs.
+ * Both are the first snapshot the fusion algorithm returns (taken before any
+ * map extension, so no work is replicated): row statistics, the K-map that
+ * produces the hidden blocks, the N-map that reduces over them.
+ *
+ * BB_VARIANT_SNAPSHOT1 compute-bound form for many rows.  A norm-prologue dual
+ *                      GEMM (sum x^2 and both products from one pass over X,
+ *                      inverse norm after the dots, Swish*gate epilogue)
+ *                      writes the hidden once as bf16 to the workspace; a
+ *                      second GEMM contracts it with W2.  Two launches.
+ * BB_VARIANT_STREAM    bandwidth-bound form for M <= 16 rows.  One persistent
+ *                      cooperative kernel streams W1, W3 and then W2 exactly
+ *                      once; both reductions (over the model dimension and
+ *                      over the hidden dimension) run in parallel over all
+ *                      workgroups with fp32 atomic accumulation (Rule 3's
+ *                      atomic form; Example 3's epilogue proposes it for the
+ *                      K-map).  The pre-activations (2 x 16 x F floats) pass
+ *                      through a cache-resident scratch between the phases.
+ * BB_VARIANT_AUTO      STREAM for M <= 16, SNAPSHOT1 otherwise.
+ */
+typedef enum bb_variant {
+    BB_VARIANT_AUTO = 0,
+    BB_VARIANT_STREAM = 1,
+    BB_VARIANT_SNAPSHOT1 = 2
+} bb_variant;
+
+typedef enum bb_op {
+    BB_OP_RMSNORM_SWIGLU_FFN = 0,
+    BB_OP_LAYERNORM_MATMUL = 1,
+    BB_OP_RMSNORM_SWIGLU_FFN_UNFUSED = 2,
+    BB_OP_LAYERNORM_MATMUL_UNFUSED = 3
+} bb_op;
+
+/* ------------------------------------------------------------------------
+ * Y = ( SiLU(Xh W1) (.) (Xh W3) ) W2,   Xh[i,:] = g (.) X[i,:] / sqrt(mean(X[i,:]^2) + eps)
+ *
+ * The array program of Example 3 ("RMSNorm and FeedForward-SwiGLU") with the
+ * root MEAN square, eps inside the root and a per-column gain g; SiLU(x) =
+ * x/(1+exp(-x)) acts on the W1 product.  W1, W3, W2 are the paper's W, V, U.
+ *
+ *   X  [M, D]  in      g  [D]  in
+ *   W1 [D, F]  in      W3 [D, F]  in      W2 [F, D]  in
+ *   Y  [M, D]  out (bf16, every element written)
+ *
+ * Arithmetic: bf16 operands, fp32 accumulation and statistics, the gained row
+ * bf16(x*g) and the hidden are rounded to bf16 before they enter a matrix
+ * instruction, the inverse norm is applied after the first contraction
+ * (Rule 4).  M may be any value >= 0 (M == 0 returns BB_OK and launches
+ * nothing); D and F must be positive multiples of 8.
+ * Needs a workspace of bb_workspace_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F)
+ * bytes: taken from bb_set_workspace() if one is set, otherwise allocated by
+ * the library on first use (that call may synchronise the device) and cached.
+ * Two calls that share the workspace must not overlap in time.
+ */
+int bb_rmsnorm_swiglu_ffn(const void* X, const void* g, const void* W1,
+                          const void* W3, const void* W2, void* Y,
+                          int64_t M, int64_t D, int64_t F, float eps,
+                          void* stream);
+
+/* ------------------------------------------------------------------------
+ * Y = LN(X) W,  LN(x) = gamma (.) (x - mean(x)) / sqrt(var(x) + eps) + beta
+ *
+ * The array program of Example 2 ("LayerNorm and Matmul") with the biased
+ * variance of its sigma formula, plus gamma, beta and eps.  Computed in the
+ * fused form the paper ends with: one pass over X per output tile that
+ * accumulates sum x, sum x^2 and (X diag(gamma)) W together; the mean is
+ * removed after the contraction through the column vector gamma^T W (Rule 5)
+ * and rows are scaled by the inverse standard deviation afterwards (Rule 4).
+ *
+ *   X [M, D] in   gamma [D] in   beta [D] in   W [D, N] in   Y [M, N] out
+ *
+ * D and N positive multiples of 8, M >= 0.  The one-pass variance
+ * sum(x^2)/D - mean^2 is evaluated in fp32: rows whose |mean|/std exceeds a
+ * few hundred lose accuracy.  Workspace: bb_workspace_bytes(
+ * BB_OP_LAYERNORM_MATMUL, M, D, N) (two fp32 vectors of length N).
+ */
+int bb_layernorm_matmul(const void* X, const void* gamma, const void* beta,
+                        const void* W, void* Y, int64_t M, int64_t D,
+                        int64_t N, float eps, void* stream);
+
+/* ------------------------------------------------------------------------
+ * The UNFUSED block programs (Example 3 / Example 2, initial block programs):
+ * one kernel per array operator, every intermediate materialised in global
+ * memory.  Built from the same tile primitives; exported so that the cost of
+ * not fusing can be timed.  Same arguments and results as the fused calls.
+ * FFN: rmsnorm rows -> Xh (bf16) ; P = Xh W1 ; Q = Xh W3 ; H = SiLU(P)*Q ;
+ * Y = H W2  (5 launches).  LN: layernorm rows -> Z ; Y = Z W (2 launches).
+ * Workspace: bb_workspace_bytes(BB_OP_*_UNFUSED, ...).
+ */
+int bb_rmsnorm_swiglu_ffn_unfused(const void* X, const void* g, const void* W1,
+                                  const void* W3, const void* W2, void* Y,
+                                  int64_t M, int64_t D, int64_t F, float eps,
+                                  void* stream);
+int bb_layernorm_matmul_unfused(const void* X, const void* gamma,
+                                const void* beta, const void* W, void* Y,
+                                int64_t M, int64_t D, int64_t N, float eps,
+                                void* stream);
+
+/* ------------------------------------------------------------------------
+ * Workspace and variant control.
+ *
+ * bb_workspace_bytes: bytes of device scratch `op` needs for the given sizes
+ *   (third size is F for the FFN ops, N for the LN ops); the maximum over the
+ *   variants that AUTO may choose.  Returns 0 for invalid sizes.
+ * bb_set_workspace: hand the library a device buffer (256-byte aligned) to use
+ *   instead of its own allocation; (NULL, 0) returns to the internal one.  The
+ *   buffer must be ZERO-FILLED when it is handed over (the streaming variant
+ *   keeps all-zero accumulators between calls) and stays owned by the caller.
+ * bb_set_variant / bb_get_variant: process-wide choice for
+ *   bb_rmsnorm_swiglu_ffn (default BB_VARIANT_AUTO, or the BB_VARIANT
+ *   environment variable: "auto", "stream", "snapshot1").
+ * bb_shutdown: frees the library's own workspace (synchronises the device).
+ */
+size_t bb_workspace_bytes(int op, int64_t M, int64_t D, int64_t F_or_N);
+int bb_set_workspace(void* dptr, size_t bytes);
+int bb_set_variant(int variant);
+int bb_get_variant(void);
+int bb_shutdown(void);
+
+/* ------------------------------------------------------------------------
+ * Diagnostics.
+ */
+const char* bb_status_string(int status);
+int bb_version(void);
+int bb_last_hip_error(void); /* raw hipError_t of the last BB_ERR_HIP, else 0 */
+
+/* ------------------------------------------------------------------------
+ * Calibration kernels for roofline denominators (not part of the operators).
+ * bb_calib_copy:  dst[i] = src[i] for `bytes` bytes (multiple of 16), a plain
+ *                 grid-stride copy; known traffic = bytes read + bytes written.
+ * bb_calib_read:  streams `bytes` bytes (multiple of 16) and writes one float
+ *                 per workgroup to `sink` (>= 4096 floats).
+ * bb_calib_mfma:  each wave issues `iters` x 16 independent bf16
+ *                 32x32x16 matrix instructions on register operands; `sink`
+ *                 (>= 64 floats) is only there to keep the work alive.  Flops
+ *                 issued = workgroups * 4 waves * iters * 16 * 32768.
+ */
+int bb_calib_copy(const void* src, void* dst, size_t bytes, void* stream);
+int bb_calib_read(const void* src, size_t bytes, void* sink, void* stream);
+int bb_calib_mfma(int workgroups, int iters, void* sink, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BB_H_ */

@@ -1,0 +1,170 @@
+"""Thin ctypes binding of libbb.so: argument marshalling only.
+
+Functions mirror include/bb.h.  Tensor arguments are torch tensors on the GPU
+(bf16, contiguous); torch is used for device memory and the current stream,
+every step of the computation runs inside the library's HIP kernels.  There is
+no fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libbb.so")
+
+BB_OK = 0
+VARIANT_AUTO, VARIANT_STREAM, VARIANT_SNAPSHOT1 = 0, 1, 2
+OP_FFN, OP_LN, OP_FFN_UNFUSED, OP_LN_UNFUSED = 0, 1, 2, 3
+
+EXPORTS = [
+    "bb_rmsnorm_swiglu_ffn", "bb_layernorm_matmul",
+    "bb_rmsnorm_swiglu_ffn_unfused", "bb_layernorm_matmul_unfused",
+    "bb_workspace_bytes", "bb_set_workspace", "bb_set_variant", "bb_get_variant",
+    "bb_shutdown", "bb_status_string", "bb_version", "bb_last_hip_error",
+    "bb_calib_copy", "bb_calib_read", "bb_calib_mfma",
+]
+
+_lib = None
+
+
+class BBError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} (status {status})")
+
+
+def load() -> ctypes.CDLL:
+    """Loads libbb.so; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2505_07829_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, f32, sz, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t, ctypes.c_int
+    lib.bb_rmsnorm_swiglu_ffn.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
+    lib.bb_rmsnorm_swiglu_ffn_unfused.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
+    lib.bb_layernorm_matmul.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
+    lib.bb_layernorm_matmul_unfused.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
+    lib.bb_workspace_bytes.argtypes = [ci, i64, i64, i64]
+    lib.bb_workspace_bytes.restype = sz
+    lib.bb_set_workspace.argtypes = [vp, sz]
+    lib.bb_set_variant.argtypes = [ci]
+    lib.bb_status_string.argtypes = [ci]
+    lib.bb_status_string.restype = ctypes.c_char_p
+    lib.bb_calib_copy.argtypes = [vp, vp, sz, vp]
+    lib.bb_calib_read.argtypes = [vp, sz, vp, vp]
+    lib.bb_calib_mfma.argtypes = [ci, ci, vp, vp]
+    for name in EXPORTS:
+        fn = getattr(lib, name)
+        if name not in ("bb_workspace_bytes", "bb_status_string"):
+            fn.restype = ci
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().bb_status_string(int(status)).decode()
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != BB_OK:
+        raise BBError(rc, what)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream() -> int:
+    import torch
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _require(t, shape, name):
+    import torch
+    if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous CUDA bfloat16 tensor")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+
+
+def bb_rmsnorm_swiglu_ffn(X, g, W1, W3, W2, eps: float, Y=None, unfused: bool = False):
+    """Y = (SiLU(Xh W1) * (Xh W3)) W2 with Xh = g * X / sqrt(mean(X^2) + eps).  Returns Y."""
+    import torch
+    lib = load()
+    M, D = X.shape
+    F = W1.shape[1]
+    _require(X, (M, D), "X"); _require(g, (D,), "g")
+    _require(W1, (D, F), "W1"); _require(W3, (D, F), "W3"); _require(W2, (F, D), "W2")
+    if Y is None:
+        Y = torch.empty((M, D), dtype=torch.bfloat16, device=X.device)
+    _require(Y, (M, D), "Y")
+    fn = lib.bb_rmsnorm_swiglu_ffn_unfused if unfused else lib.bb_rmsnorm_swiglu_ffn
+    _check(fn(_ptr(X), _ptr(g), _ptr(W1), _ptr(W3), _ptr(W2), _ptr(Y), M, D, F, float(eps), _stream()),
+           "bb_rmsnorm_swiglu_ffn" + ("_unfused" if unfused else ""))
+    return Y
+
+
+def bb_layernorm_matmul(X, gamma, beta, W, eps: float, Y=None, unfused: bool = False):
+    """Y = LN(X; gamma, beta, eps) W.  Returns Y."""
+    import torch
+    lib = load()
+    M, D = X.shape
+    N = W.shape[1]
+    _require(X, (M, D), "X"); _require(gamma, (D,), "gamma"); _require(beta, (D,), "beta")
+    _require(W, (D, N), "W")
+    if Y is None:
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device)
+    _require(Y, (M, N), "Y")
+    fn = lib.bb_layernorm_matmul_unfused if unfused else lib.bb_layernorm_matmul
+    _check(fn(_ptr(X), _ptr(gamma), _ptr(beta), _ptr(W), _ptr(Y), M, D, N, float(eps), _stream()),
+           "bb_layernorm_matmul" + ("_unfused" if unfused else ""))
+    return Y
+
+
+def bb_workspace_bytes(op: int, M: int, D: int, F_or_N: int) -> int:
+    return int(load().bb_workspace_bytes(op, M, D, F_or_N))
+
+
+def bb_set_workspace(t) -> None:
+    """t: zero-filled CUDA tensor (any dtype) or None to return to the internal buffer."""
+    if t is None:
+        _check(load().bb_set_workspace(None, 0), "bb_set_workspace")
+    else:
+        _check(load().bb_set_workspace(_ptr(t), t.numel() * t.element_size()), "bb_set_workspace")
+
+
+def bb_set_variant(v: int) -> None:
+    _check(load().bb_set_variant(int(v)), "bb_set_variant")
+
+
+def bb_get_variant() -> int:
+    return int(load().bb_get_variant())
+
+
+def bb_shutdown() -> None:
+    _check(load().bb_shutdown(), "bb_shutdown")
+
+
+def bb_version() -> int:
+    return int(load().bb_version())
+
+
+def bb_last_hip_error() -> int:
+    return int(load().bb_last_hip_error())
+
+
+def bb_calib_copy(src, dst) -> None:
+    _check(load().bb_calib_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream()), "bb_calib_copy")
+
+
+def bb_calib_read(src, sink) -> None:
+    _check(load().bb_calib_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream()), "bb_calib_read")
+
+
+def bb_calib_mfma(workgroups: int, iters: int, sink) -> None:
+    _check(load().bb_calib_mfma(int(workgroups), int(iters), _ptr(sink), _stream()), "bb_calib_mfma")

@@ -1,0 +1,475 @@
+// C ABI of the bb library: argument validation, workspace management, variant
+// selection and kernel launches.  See include/bb.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+
+#include "../../include/bb.h"
+#include "bb_gemm.h"
+#include "bb_misc.h"
+#include "bb_stream.h"
+
+namespace {
+
+using namespace bb;
+
+constexpr int64_t kStreamMaxM = 16;   // rows the weight-streaming kernel handles
+constexpr size_t kAlign = 256;
+
+std::mutex g_mu;
+int g_variant = -1;                    // -1: not yet read from the environment
+int g_last_hip = 0;
+int g_log = -1;
+
+struct Workspace {
+    void* ptr = nullptr;
+    size_t bytes = 0;
+    bool user = false;
+    size_t clean = 0;                  // leading bytes known to be zero
+    int64_t stream_D = -1, stream_F = -1;
+    int parity = 0;                    // pre-activation buffer the next stream call uses
+    int device = -1;
+} g_ws;
+
+struct DeviceInfo {
+    bool known = false;
+    bool gfx950 = false;
+    int cus = 0;
+} g_dev[64];
+
+bool log_on() {
+    if (g_log < 0) g_log = std::getenv("BB_LOG") ? 1 : 0;
+    return g_log == 1;
+}
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+int hip_fail(hipError_t e) {
+    g_last_hip = (int)e;
+    (void)hipGetLastError();
+    return BB_ERR_HIP;
+}
+
+#define BB_HIP(expr)                                   \
+    do {                                               \
+        hipError_t e_ = (expr);                        \
+        if (e_ != hipSuccess) return hip_fail(e_);     \
+    } while (0)
+
+int current_device_info(const DeviceInfo** out) {
+    int dev = 0;
+    BB_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return BB_ERR_ARCH;
+    DeviceInfo& d = g_dev[dev];
+    if (!d.known) {
+        hipDeviceProp_t prop;
+        BB_HIP(hipGetDeviceProperties(&prop, dev));
+        d.gfx950 = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0;
+        d.cus = prop.multiProcessorCount;
+        d.known = true;
+    }
+    *out = &d;
+    return d.gfx950 ? BB_OK : BB_ERR_ARCH;
+}
+
+int read_variant() {
+    if (g_variant < 0) {
+        g_variant = BB_VARIANT_AUTO;
+        if (const char* e = std::getenv("BB_VARIANT")) {
+            if (!std::strcmp(e, "stream")) g_variant = BB_VARIANT_STREAM;
+            else if (!std::strcmp(e, "snapshot1")) g_variant = BB_VARIANT_SNAPSHOT1;
+        }
+    }
+    return g_variant;
+}
+
+// ---------------------------------------------------------------- validation
+bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+int check_dims(int64_t M, int64_t D, int64_t F) {
+    if (M < 0 || D <= 0 || F <= 0) return BB_ERR_SHAPE;
+    if ((D & 7) || (F & 7)) return BB_ERR_SHAPE;
+    // int32 indexing inside tiles: leading dimensions and tile counts must fit
+    if (D > (1 << 24) || F > (1 << 24) || M > (1 << 24)) return BB_ERR_SHAPE;
+    return BB_OK;
+}
+int check_eps(float eps) { return (std::isfinite(eps) && eps >= 0.f) ? BB_OK : BB_ERR_EPS; }
+
+int validate_ffn(const void* X, const void* g, const void* W1, const void* W3, const void* W2, void* Y,
+                 int64_t M, int64_t D, int64_t F, float eps) {
+    if (int rc = check_dims(M, D, F)) return rc;
+    if (int rc = check_eps(eps)) return rc;
+    if (M == 0) return BB_OK;
+    if (!X || !g || !W1 || !W3 || !W2 || !Y) return BB_ERR_NULL;
+    if (misaligned(X) || misaligned(g) || misaligned(W1) || misaligned(W3) || misaligned(W2) || misaligned(Y))
+        return BB_ERR_ALIGN;
+    const size_t ny = (size_t)M * D * 2, nw = (size_t)D * F * 2;
+    if (overlaps(Y, ny, X, ny) || overlaps(Y, ny, g, (size_t)D * 2) || overlaps(Y, ny, W1, nw) ||
+        overlaps(Y, ny, W3, nw) || overlaps(Y, ny, W2, nw))
+        return BB_ERR_ALIAS;
+    return BB_OK;
+}
+
+int validate_ln(const void* X, const void* gamma, const void* beta, const void* W, void* Y, int64_t M,
+                int64_t D, int64_t N, float eps) {
+    if (int rc = check_dims(M, D, N)) return rc;
+    if (int rc = check_eps(eps)) return rc;
+    if (M == 0) return BB_OK;
+    if (!X || !gamma || !beta || !W || !Y) return BB_ERR_NULL;
+    if (misaligned(X) || misaligned(gamma) || misaligned(beta) || misaligned(W) || misaligned(Y))
+        return BB_ERR_ALIGN;
+    const size_t ny = (size_t)M * N * 2;
+    if (overlaps(Y, ny, X, (size_t)M * D * 2) || overlaps(Y, ny, gamma, (size_t)D * 2) ||
+        overlaps(Y, ny, beta, (size_t)D * 2) || overlaps(Y, ny, W, (size_t)D * N * 2))
+        return BB_ERR_ALIAS;
+    return BB_OK;
+}
+
+// ------------------------------------------------------------ workspace plan
+struct StreamPlan {
+    size_t yacc_off, cnt_off, pq_off[2], pq_bytes, zone_bytes;
+    int Fp, nnb;
+};
+
+StreamPlan stream_plan(int64_t D, int64_t F) {
+    StreamPlan s;
+    s.Fp = (int)((F + 127) / 128 * 128);
+    s.nnb = (int)((D + 127) / 128);
+    s.yacc_off = 0;
+    s.cnt_off = align_up((size_t)kStreamMaxM * D * 4);
+    s.pq_bytes = align_up(((size_t)2 * 16 * s.Fp + 64) * 4);
+    s.pq_off[0] = s.cnt_off + align_up((size_t)s.nnb * 4);
+    s.pq_off[1] = s.pq_off[0] + s.pq_bytes;
+    s.zone_bytes = s.pq_off[1] + s.pq_bytes;
+    return s;
+}
+
+size_t zone_bytes(int op, int64_t M, int64_t D, int64_t F) {
+    if (op == BB_OP_RMSNORM_SWIGLU_FFN && M <= kStreamMaxM) return stream_plan(D, F).zone_bytes;
+    return 0;
+}
+
+size_t scratch_bytes(int op, int64_t M, int64_t D, int64_t F) {
+    switch (op) {
+        case BB_OP_RMSNORM_SWIGLU_FFN: return align_up((size_t)M * F * 2);
+        case BB_OP_LAYERNORM_MATMUL: return 2 * align_up((size_t)F * 4);
+        case BB_OP_RMSNORM_SWIGLU_FFN_UNFUSED: return align_up((size_t)M * D * 2) + 3 * align_up((size_t)M * F * 2);
+        case BB_OP_LAYERNORM_MATMUL_UNFUSED: return align_up((size_t)M * D * 2);
+        default: return 0;
+    }
+}
+
+// Makes sure a workspace of `need` bytes exists on the current device.
+int ensure_workspace(size_t need) {
+    int dev = 0;
+    BB_HIP(hipGetDevice(&dev));
+    if (g_ws.user) return (g_ws.bytes >= need) ? BB_OK : BB_ERR_WORKSPACE;
+    if (g_ws.ptr && g_ws.device == dev && g_ws.bytes >= need) return BB_OK;
+    if (g_ws.ptr) {
+        BB_HIP(hipDeviceSynchronize());
+        BB_HIP(hipFree(g_ws.ptr));
+        g_ws = Workspace();
+    }
+    void* p = nullptr;
+    BB_HIP(hipMalloc(&p, need));
+    g_ws.ptr = p;
+    g_ws.bytes = need;
+    g_ws.user = false;
+    g_ws.clean = 0;
+    g_ws.device = dev;
+    if (log_on()) std::fprintf(stderr, "[bb] workspace %zu bytes allocated\n", need);
+    return BB_OK;
+}
+
+int fill_zero(void* p, size_t bytes, hipStream_t st) {
+    const size_t n16 = bytes / 16;
+    const int grid = (int)std::min<size_t>((n16 + 255) / 256, 2048);
+    if (grid == 0) return BB_OK;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(grid), dim3(256), 0, st, (u32x4*)p, n16);
+    BB_HIP(hipGetLastError());
+    return BB_OK;
+}
+
+// scratch region [off, off+len) is about to be written: it is no longer zero
+void mark_dirty(size_t off) {
+    if (off < g_ws.clean) g_ws.clean = off;
+}
+
+// ------------------------------------------------------------------- launches
+template <int MODE>
+int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u16* C, int ldc,
+                const u16* gain, const float* colc, const float* colb, int M, int N, int K, float eps,
+                int cus, hipStream_t st) {
+    GemmArgs a;
+    a.A = A; a.B0 = B0; a.B1 = B1; a.C = C; a.gain = gain; a.colc = colc; a.colb = colb;
+    a.M = M; a.N = N; a.K = K; a.lda = lda; a.ldb = ldb; a.ldc = ldc; a.eps = eps;
+    const int ncol = (MODE == MODE_GATEUP) ? 128 : 256;
+    a.tiles_n = (N + ncol - 1) / ncol;
+    const int tiles256 = ((M + 255) / 256) * a.tiles_n;
+    const bool big = tiles256 >= cus;
+    const int BM = big ? 256 : 128;
+    a.tiles_m = (M + BM - 1) / BM;
+    const int tiles = a.tiles_m * a.tiles_n;
+    a.tiles_per_xcd = (tiles + 7) / 8;
+    const dim3 grid(8 * a.tiles_per_xcd), block(GEMM_THREADS);
+    if (log_on())
+        std::fprintf(stderr, "[bb] gemm mode %d BM %d M %d N %d K %d tiles %dx%d\n", MODE, BM, M, N, K,
+                     a.tiles_m, a.tiles_n);
+    if (big) hipLaunchKernelGGL((gemm_kernel<MODE, 256>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((gemm_kernel<MODE, 128>), grid, block, 0, st, a);
+    BB_HIP(hipGetLastError());
+    return BB_OK;
+}
+
+int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u16* W2, u16* Y, int M,
+               int D, int F, float eps, int cus, hipStream_t st) {
+    const StreamPlan sp = stream_plan(D, F);
+    char* base = (char*)g_ws.ptr;
+    if (g_ws.clean < sp.zone_bytes || g_ws.stream_D != D || g_ws.stream_F != F) {
+        if (int rc = fill_zero(base, sp.zone_bytes, st)) return rc;
+        g_ws.clean = sp.zone_bytes;
+        g_ws.stream_D = D;
+        g_ws.stream_F = F;
+        g_ws.parity = 0;
+    }
+    StreamArgs a;
+    a.X = X; a.g = g; a.W1 = W1; a.W3 = W3; a.W2 = W2; a.Y = Y;
+    const int par = g_ws.parity;
+    a.pq = (float*)(base + sp.pq_off[par]);
+    a.ssq = a.pq + (size_t)2 * 16 * sp.Fp;
+    a.zero_ptr = (float*)(base + sp.pq_off[1 - par]);
+    a.zero_count4 = (int)(sp.pq_bytes / 16);
+    a.yacc = (float*)(base + sp.yacc_off);
+    a.cnt = (unsigned*)(base + sp.cnt_off);
+    a.M = M; a.D = D; a.F = F; a.Fp = sp.Fp; a.eps = eps;
+    const int G = cus;
+    a.nkb1 = (D + 31) / 32;
+    a.items1 = a.nkb1 * ((F + 127) / 128);
+    a.per1 = (a.items1 + G - 1) / G;
+    a.nkb2 = (F + 31) / 32;
+    a.items2 = a.nkb2 * sp.nnb;
+    a.per2 = (a.items2 + G - 1) / G;
+    if (log_on())
+        std::fprintf(stderr, "[bb] stream M %d D %d F %d items %d/%d per wg %d/%d parity %d\n", M, D, F,
+                     a.items1, a.items2, a.per1, a.per2, par);
+    void* params[] = {(void*)&a};
+    BB_HIP(hipLaunchCooperativeKernel((const void*)ffn_stream_kernel, dim3(G), dim3(STREAM_THREADS), params, 0, st));
+    g_ws.parity = 1 - par;
+    return BB_OK;
+}
+
+hipStream_t as_stream(void* s) { return (hipStream_t)s; }
+
+}  // namespace
+
+// ============================================================== exported API
+extern "C" {
+
+int bb_version(void) { return BB_VERSION; }
+int bb_last_hip_error(void) { return g_last_hip; }
+
+const char* bb_status_string(int s) {
+    switch (s) {
+        case BB_OK: return "ok";
+        case BB_ERR_NULL: return "null pointer";
+        case BB_ERR_SHAPE: return "bad shape";
+        case BB_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case BB_ERR_EPS: return "bad eps";
+        case BB_ERR_ALIAS: return "output overlaps an input";
+        case BB_ERR_ARCH: return "device is not gfx950";
+        case BB_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
+        case BB_ERR_HIP: return "HIP call failed";
+        case BB_ERR_VARIANT: return "bad variant";
+        default: return "unknown status";
+    }
+}
+
+int bb_set_variant(int v) {
+    if (v != BB_VARIANT_AUTO && v != BB_VARIANT_STREAM && v != BB_VARIANT_SNAPSHOT1) return BB_ERR_VARIANT;
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_variant = v;
+    return BB_OK;
+}
+
+int bb_get_variant(void) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    return read_variant();
+}
+
+size_t bb_workspace_bytes(int op, int64_t M, int64_t D, int64_t F) {
+    if (op < BB_OP_RMSNORM_SWIGLU_FFN || op > BB_OP_LAYERNORM_MATMUL_UNFUSED) return 0;
+    if (check_dims(M, D, F) != BB_OK) return 0;
+    return zone_bytes(op, M, D, F) + scratch_bytes(op, M, D, F);
+}
+
+int bb_set_workspace(void* dptr, size_t bytes) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    if ((dptr == nullptr) != (bytes == 0)) return BB_ERR_WORKSPACE;
+    if ((uintptr_t)dptr & (kAlign - 1)) return BB_ERR_WORKSPACE;
+    if (g_ws.ptr && !g_ws.user) {
+        BB_HIP(hipDeviceSynchronize());
+        BB_HIP(hipFree(g_ws.ptr));
+    }
+    g_ws = Workspace();
+    if (dptr) {
+        g_ws.ptr = dptr;
+        g_ws.bytes = bytes;
+        g_ws.user = true;
+        g_ws.clean = bytes;    // handed over zero-filled (contract)
+    }
+    return BB_OK;
+}
+
+int bb_shutdown(void) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (g_ws.ptr && !g_ws.user) {
+        BB_HIP(hipDeviceSynchronize());
+        BB_HIP(hipFree(g_ws.ptr));
+    }
+    g_ws = Workspace();
+    return BB_OK;
+}
+
+int bb_rmsnorm_swiglu_ffn(const void* X, const void* g, const void* W1, const void* W3, const void* W2,
+                          void* Y, int64_t M, int64_t D, int64_t F, float eps, void* stream) {
+    if (int rc = validate_ffn(X, g, W1, W3, W2, Y, M, D, F, eps)) return rc;
+    if (M == 0) return BB_OK;
+    std::lock_guard<std::mutex> lk(g_mu);
+    int variant = read_variant();
+    if (variant == BB_VARIANT_STREAM && M > kStreamMaxM) return BB_ERR_VARIANT;
+    if (variant == BB_VARIANT_AUTO) variant = (M <= kStreamMaxM) ? BB_VARIANT_STREAM : BB_VARIANT_SNAPSHOT1;
+    const DeviceInfo* dev = nullptr;
+    if (int rc = current_device_info(&dev)) return rc;
+    const size_t zone = zone_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F);
+    if (int rc = ensure_workspace(zone + scratch_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F))) return rc;
+    hipStream_t st = as_stream(stream);
+    const u16 *x = (const u16*)X, *gg = (const u16*)g, *w1 = (const u16*)W1, *w3 = (const u16*)W3,
+              *w2 = (const u16*)W2;
+    if (variant == BB_VARIANT_STREAM)
+        return run_stream(x, gg, w1, w3, w2, (u16*)Y, (int)M, (int)D, (int)F, eps, dev->cus, st);
+    // first snapshot: hidden written once (bf16), then contracted with W2
+    u16* H = (u16*)((char*)g_ws.ptr + zone);
+    mark_dirty(zone);
+    if (int rc = launch_gemm<MODE_GATEUP>(x, (int)D, w1, w3, (int)F, H, (int)F, gg, nullptr, nullptr, (int)M,
+                                          (int)F, (int)D, eps, dev->cus, st))
+        return rc;
+    return launch_gemm<MODE_PLAIN>(H, (int)F, w2, nullptr, (int)D, (u16*)Y, (int)D, nullptr, nullptr, nullptr,
+                                   (int)M, (int)D, (int)F, 0.f, dev->cus, st);
+}
+
+int bb_layernorm_matmul(const void* X, const void* gamma, const void* beta, const void* W, void* Y,
+                        int64_t M, int64_t D, int64_t N, float eps, void* stream) {
+    if (int rc = validate_ln(X, gamma, beta, W, Y, M, D, N, eps)) return rc;
+    if (M == 0) return BB_OK;
+    std::lock_guard<std::mutex> lk(g_mu);
+    const DeviceInfo* dev = nullptr;
+    if (int rc = current_device_info(&dev)) return rc;
+    if (int rc = ensure_workspace(scratch_bytes(BB_OP_LAYERNORM_MATMUL, M, D, N))) return rc;
+    hipStream_t st = as_stream(stream);
+    mark_dirty(0);
+    float* colc = (float*)g_ws.ptr;
+    float* colb = (float*)((char*)g_ws.ptr + align_up((size_t)N * 4));
+    hipLaunchKernelGGL(colvec_kernel, dim3((unsigned)((N + 63) / 64)), dim3(256), 0, st, (const u16*)W,
+                       (const u16*)gamma, (const u16*)beta, colc, colb, (int)D, (int)N);
+    BB_HIP(hipGetLastError());
+    return launch_gemm<MODE_LN>((const u16*)X, (int)D, (const u16*)W, nullptr, (int)N, (u16*)Y, (int)N,
+                                (const u16*)gamma, colc, colb, (int)M, (int)N, (int)D, eps, dev->cus, st);
+}
+
+int bb_rmsnorm_swiglu_ffn_unfused(const void* X, const void* g, const void* W1, const void* W3,
+                                  const void* W2, void* Y, int64_t M, int64_t D, int64_t F, float eps,
+                                  void* stream) {
+    if (int rc = validate_ffn(X, g, W1, W3, W2, Y, M, D, F, eps)) return rc;
+    if (M == 0) return BB_OK;
+    std::lock_guard<std::mutex> lk(g_mu);
+    const DeviceInfo* dev = nullptr;
+    if (int rc = current_device_info(&dev)) return rc;
+    if (int rc = ensure_workspace(scratch_bytes(BB_OP_RMSNORM_SWIGLU_FFN_UNFUSED, M, D, F))) return rc;
+    hipStream_t st = as_stream(stream);
+    mark_dirty(0);
+    char* base = (char*)g_ws.ptr;
+    const size_t nMF = align_up((size_t)M * F * 2);
+    u16* Xh = (u16*)base;
+    u16* P = (u16*)(base + align_up((size_t)M * D * 2));
+    u16* Q = (u16*)((char*)P + nMF);
+    u16* H = (u16*)((char*)Q + nMF);
+    hipLaunchKernelGGL(rmsnorm_rows_kernel, dim3((unsigned)M), dim3(256), 0, st, (const u16*)X, (const u16*)g,
+                       Xh, (int)D, eps);
+    BB_HIP(hipGetLastError());
+    if (int rc = launch_gemm<MODE_PLAIN>(Xh, (int)D, (const u16*)W1, nullptr, (int)F, P, (int)F, nullptr,
+                                         nullptr, nullptr, (int)M, (int)F, (int)D, 0.f, dev->cus, st))
+        return rc;
+    if (int rc = launch_gemm<MODE_PLAIN>(Xh, (int)D, (const u16*)W3, nullptr, (int)F, Q, (int)F, nullptr,
+                                         nullptr, nullptr, (int)M, (int)F, (int)D, 0.f, dev->cus, st))
+        return rc;
+    const size_t n8 = (size_t)M * F / 8;
+    hipLaunchKernelGGL(silu_mul_kernel, dim3((unsigned)std::min<size_t>((n8 + 255) / 256, 4096)), dim3(256), 0,
+                       st, P, Q, H, n8);
+    BB_HIP(hipGetLastError());
+    return launch_gemm<MODE_PLAIN>(H, (int)F, (const u16*)W2, nullptr, (int)D, (u16*)Y, (int)D, nullptr,
+                                   nullptr, nullptr, (int)M, (int)D, (int)F, 0.f, dev->cus, st);
+}
+
+int bb_layernorm_matmul_unfused(const void* X, const void* gamma, const void* beta, const void* W, void* Y,
+                                int64_t M, int64_t D, int64_t N, float eps, void* stream) {
+    if (int rc = validate_ln(X, gamma, beta, W, Y, M, D, N, eps)) return rc;
+    if (M == 0) return BB_OK;
+    std::lock_guard<std::mutex> lk(g_mu);
+    const DeviceInfo* dev = nullptr;
+    if (int rc = current_device_info(&dev)) return rc;
+    if (int rc = ensure_workspace(scratch_bytes(BB_OP_LAYERNORM_MATMUL_UNFUSED, M, D, N))) return rc;
+    hipStream_t st = as_stream(stream);
+    mark_dirty(0);
+    u16* Z = (u16*)g_ws.ptr;
+    hipLaunchKernelGGL(layernorm_rows_kernel, dim3((unsigned)M), dim3(256), 0, st, (const u16*)X,
+                       (const u16*)gamma, (const u16*)beta, Z, (int)D, eps);
+    BB_HIP(hipGetLastError());
+    return launch_gemm<MODE_PLAIN>(Z, (int)D, (const u16*)W, nullptr, (int)N, (u16*)Y, (int)N, nullptr, nullptr,
+                                   nullptr, (int)M, (int)N, (int)D, 0.f, dev->cus, st);
+}
+
+// ------------------------------------------------------------- calibration
+int bb_calib_copy(const void* src, void* dst, size_t bytes, void* stream) {
+    if (!src || !dst) return BB_ERR_NULL;
+    if ((bytes & 15) || misaligned(src) || misaligned(dst)) return BB_ERR_ALIGN;
+    if (overlaps(src, bytes, dst, bytes)) return BB_ERR_ALIAS;
+    if (bytes == 0) return BB_OK;
+    const DeviceInfo* dev = nullptr;
+    if (int rc = current_device_info(&dev)) return rc;
+    hipLaunchKernelGGL(calib_copy_kernel, dim3(dev->cus * 8), dim3(256), 0, as_stream(stream),
+                       (const u32x4*)src, (u32x4*)dst, bytes / 16);
+    BB_HIP(hipGetLastError());
+    return BB_OK;
+}
+
+int bb_calib_read(const void* src, size_t bytes, void* sink, void* stream) {
+    if (!src || !sink) return BB_ERR_NULL;
+    if ((bytes & 15) || misaligned(src) || misaligned(sink)) return BB_ERR_ALIGN;
+    if (bytes == 0) return BB_OK;
+    const DeviceInfo* dev = nullptr;
+    if (int rc = current_device_info(&dev)) return rc;
+    hipLaunchKernelGGL(calib_read_kernel, dim3(dev->cus), dim3(256), 0, as_stream(stream), (const u32x4*)src,
+                       bytes / 16, (float*)sink);
+    BB_HIP(hipGetLastError());
+    return BB_OK;
+}
+
+int bb_calib_mfma(int workgroups, int iters, void* sink, void* stream) {
+    if (!sink) return BB_ERR_NULL;
+    if (workgroups <= 0 || iters <= 0 || workgroups > 65536 || iters > (1 << 22)) return BB_ERR_SHAPE;
+    const DeviceInfo* dev = nullptr;
+    if (int rc = current_device_info(&dev)) return rc;
+    hipLaunchKernelGGL(calib_mfma_kernel, dim3(workgroups), dim3(256), 0, as_stream(stream), (float*)sink, iters);
+    BB_HIP(hipGetLastError());
+    return BB_OK;
+}
+
+}  // extern "C"

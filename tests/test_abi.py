@@ -1,0 +1,116 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol include/bb.h declares, and rejects bad arguments before touching
+the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2505_07829_amd as bb
+from paper_2505_07829_amd import build as bb_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    bb_build.build(force=False)
+    return bb.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "bb.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bb_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert "bb_rmsnorm_swiglu_ffn" in names and "bb_layernorm_matmul" in names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(bb.binding.EXPORTS) == names
+
+
+def test_version_and_strings(lib):
+    assert bb.bb_version() == 100
+    assert bb.status_string(0) == "ok"
+    for s in range(-9, 0):
+        assert bb.status_string(s) not in ("ok", "unknown status")
+    assert bb.status_string(-99) == "unknown status"
+
+
+A = 0x10000   # fake, aligned, non-overlapping "device addresses": never dereferenced
+
+
+def ffn(lib, X=A, g=2 * A, W1=3 * A, W3=4 * A, W2=5 * A, Y=6 * A, M=4, D=64, F=128, eps=1e-6, fn=None):
+    fn = fn or lib.bb_rmsnorm_swiglu_ffn
+    return fn(X, g, W1, W3, W2, Y, M, D, F, eps, None)
+
+
+def ln(lib, X=A, ga=2 * A, be=3 * A, W=4 * A, Y=6 * A, M=4, D=64, N=128, eps=1e-6, fn=None):
+    fn = fn or lib.bb_layernorm_matmul
+    return fn(X, ga, be, W, Y, M, D, N, eps, None)
+
+
+@pytest.mark.parametrize("unfused", [False, True])
+def test_ffn_argument_errors(lib, unfused):
+    fn = lib.bb_rmsnorm_swiglu_ffn_unfused if unfused else lib.bb_rmsnorm_swiglu_ffn
+    assert ffn(lib, fn=fn, M=0) == 0                       # empty input: nothing to do
+    assert ffn(lib, fn=fn, M=0, X=None, Y=None) == 0
+    assert ffn(lib, fn=fn, M=-1) == -2
+    assert ffn(lib, fn=fn, D=0) == -2
+    assert ffn(lib, fn=fn, D=60) == -2                     # not a multiple of 8
+    assert ffn(lib, fn=fn, F=130) == -2
+    assert ffn(lib, fn=fn, D=(1 << 24) + 8) == -2
+    for k in ("X", "g", "W1", "W3", "W2", "Y"):
+        assert ffn(lib, fn=fn, **{k: None}) == -1
+        assert ffn(lib, fn=fn, **{k: A * 7 + 2}) == -3     # misaligned
+    assert ffn(lib, fn=fn, eps=-1.0) == -4
+    assert ffn(lib, fn=fn, eps=float("nan")) == -4
+    assert ffn(lib, fn=fn, eps=float("inf")) == -4
+    assert ffn(lib, fn=fn, Y=A) == -5                      # in place
+    assert ffn(lib, fn=fn, Y=A + 16) == -5                 # partial overlap with X
+    assert ffn(lib, fn=fn, Y=5 * A + 64) == -5             # overlap with W2
+
+
+@pytest.mark.parametrize("unfused", [False, True])
+def test_ln_argument_errors(lib, unfused):
+    fn = lib.bb_layernorm_matmul_unfused if unfused else lib.bb_layernorm_matmul
+    assert ln(lib, fn=fn, M=0) == 0
+    assert ln(lib, fn=fn, M=-3) == -2
+    assert ln(lib, fn=fn, N=12) == -2
+    for k in ("X", "ga", "be", "W", "Y"):
+        assert ln(lib, fn=fn, **{k: None}) == -1
+        assert ln(lib, fn=fn, **{k: A * 9 + 4}) == -3
+    assert ln(lib, fn=fn, eps=-1e-9) == -4
+    assert ln(lib, fn=fn, Y=4 * A) == -5
+
+
+def test_variant_and_workspace_queries(lib):
+    assert bb.bb_get_variant() in (0, 1, 2)
+    old = bb.bb_get_variant()
+    with pytest.raises(bb.BBError):
+        bb.bb_set_variant(7)
+    bb.bb_set_variant(bb.VARIANT_SNAPSHOT1)
+    assert bb.bb_get_variant() == bb.VARIANT_SNAPSHOT1
+    bb.bb_set_variant(old)
+    # hidden (M*F bf16) must fit; invalid sizes give 0
+    assert bb.bb_workspace_bytes(bb.OP_FFN, 2048, 4096, 11008) >= 2048 * 11008 * 2
+    assert bb.bb_workspace_bytes(bb.OP_FFN, 16, 4096, 11008) >= 16 * 4096 * 4 + 2 * 2 * 16 * 11008 * 4
+    assert bb.bb_workspace_bytes(bb.OP_LN, 8192, 4096, 16384) >= 2 * 16384 * 4
+    assert bb.bb_workspace_bytes(bb.OP_FFN_UNFUSED, 64, 256, 704) >= 64 * 256 * 2 + 3 * 64 * 704 * 2
+    assert bb.bb_workspace_bytes(bb.OP_FFN, 4, 7, 8) == 0
+    assert bb.bb_workspace_bytes(99, 4, 8, 8) == 0
+    assert lib.bb_set_workspace(ctypes.c_void_p(A + 8), 1024) == -7     # misaligned
+    assert lib.bb_set_workspace(None, 1024) == -7
+    assert lib.bb_set_workspace(None, 0) == 0
+
+
+def test_calibration_argument_errors(lib):
+    assert lib.bb_calib_copy(None, A, 1024, None) == -1
+    assert lib.bb_calib_copy(A, 2 * A, 1000, None) == -3
+    assert lib.bb_calib_copy(A, A + 512, 1024, None) == -5
+    assert lib.bb_calib_read(A, 1024, None, None) == -1
+    assert lib.bb_calib_mfma(0, 10, A, None) == -2

@@ -1,0 +1,205 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 oracle on
+the same seeded inputs.  Gate (both operators):
+
+    max_i || Ygpu[i,:] - Yref[i,:] ||_2 / || Yref[i,:] ||_2  <=  2e-2
+
+bf16 operands, fp32 accumulation; the oracle sees the same bf16-rounded inputs.
+"""
+import numpy as np
+import pytest
+import torch
+
+import bb_inputs
+import paper_2505_07829_amd as bb
+from oracle import oracle as orc
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+def dev(ts):
+    return [t.cuda() for t in ts]
+
+
+def row_rel_err(Y_gpu, Y_ref):
+    y = Y_gpu.float().cpu().numpy().astype(np.float64)
+    num = np.linalg.norm(y - Y_ref, axis=1)
+    den = np.linalg.norm(Y_ref, axis=1)
+    assert np.all(np.isfinite(y))
+    assert np.all(den > 0)
+    return float((num / den).max())
+
+
+def sample_rows(M, tile=256, extra=6, seed=0):
+    """first/last row of every row tile plus a few random rows"""
+    rows = set()
+    for t0 in range(0, M, tile):
+        rows.add(t0); rows.add(min(M, t0 + tile) - 1)
+    rng = np.random.default_rng(seed)
+    rows.update(int(r) for r in rng.integers(0, M, size=extra))
+    return sorted(rows)
+
+
+def ffn_case(cpu, eps, rows=None, variant=bb.VARIANT_AUTO, unfused=False):
+    X, g, W1, W3, W2 = cpu
+    bb.bb_set_variant(variant)
+    try:
+        Y = bb.bb_rmsnorm_swiglu_ffn(*dev(cpu), eps, unfused=unfused)
+        torch.cuda.synchronize()
+    finally:
+        bb.bb_set_variant(bb.VARIANT_AUTO)
+    ref = orc.rmsnorm_swiglu_ffn(X, g, W1, W3, W2, eps, rows=rows)
+    got = Y if rows is None else Y[rows]
+    return row_rel_err(got, ref)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    bb.load()
+    yield
+    bb.bb_shutdown()
+
+
+# ---------------------------------------------------------------- small shapes
+@pytest.mark.parametrize("variant", [bb.VARIANT_SNAPSHOT1, bb.VARIANT_AUTO])
+def test_c1_full(variant):
+    c = bb_inputs.CONFIGS["c1"]
+    err = ffn_case(bb_inputs.make_config("c1"), c.eps, variant=variant)
+    print("c1 rel err", err)
+    assert err <= TOL
+
+
+@pytest.mark.parametrize("M,D,F", [(1, 64, 64), (5, 264, 712), (16, 256, 704), (17, 72, 136),
+                                   (130, 264, 712), (300, 520, 1032), (257, 128, 256)])
+def test_ragged_shapes_snapshot1(M, D, F):
+    err = ffn_case(bb_inputs.make_ffn(M, D, F, seed=M + D), 1e-6, variant=bb.VARIANT_SNAPSHOT1)
+    assert err <= TOL
+
+
+@pytest.mark.parametrize("M,D,F", [(1, 64, 64), (5, 264, 712), (16, 256, 704), (9, 72, 136), (16, 520, 1032)])
+def test_ragged_shapes_stream(M, D, F):
+    err = ffn_case(bb_inputs.make_ffn(M, D, F, seed=M + F), 1e-6, variant=bb.VARIANT_STREAM)
+    assert err <= TOL
+
+
+def test_stream_repeated_calls_keep_scratch_clean():
+    cpu = bb_inputs.make_ffn(16, 256, 704, seed=3)
+    X, g, W1, W3, W2 = cpu
+    ref = orc.rmsnorm_swiglu_ffn(X, g, W1, W3, W2, 1e-6)
+    d = dev(cpu)
+    bb.bb_set_variant(bb.VARIANT_STREAM)
+    try:
+        outs = []
+        for _ in range(5):
+            outs.append(bb.bb_rmsnorm_swiglu_ffn(*d, 1e-6))
+        # a different shape in between forces a new scratch layout
+        other = bb_inputs.make_ffn(7, 128, 384, seed=4)
+        Yo = bb.bb_rmsnorm_swiglu_ffn(*dev(other), 1e-6)
+        outs.append(bb.bb_rmsnorm_swiglu_ffn(*d, 1e-6))
+        torch.cuda.synchronize()
+    finally:
+        bb.bb_set_variant(bb.VARIANT_AUTO)
+    for Y in outs:
+        assert row_rel_err(Y, ref) <= TOL
+    refo = orc.rmsnorm_swiglu_ffn(*other, 1e-6)
+    assert row_rel_err(Yo, refo) <= TOL
+
+
+def test_variant_switching_shares_workspace():
+    cpu = bb_inputs.make_ffn(16, 256, 704, seed=5)
+    ref = orc.rmsnorm_swiglu_ffn(*cpu, 1e-6)
+    d = dev(cpu)
+    for v in (bb.VARIANT_STREAM, bb.VARIANT_SNAPSHOT1, bb.VARIANT_STREAM, bb.VARIANT_STREAM):
+        bb.bb_set_variant(v)
+        Y = bb.bb_rmsnorm_swiglu_ffn(*d, 1e-6)
+        torch.cuda.synchronize()
+        bb.bb_set_variant(bb.VARIANT_AUTO)
+        assert row_rel_err(Y, ref) <= TOL
+
+
+@pytest.mark.parametrize("which", [1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [bb.VARIANT_STREAM, bb.VARIANT_SNAPSHOT1])
+def test_zero_operand_gives_exact_zero(which, variant):
+    cpu = list(bb_inputs.make_ffn(16, 128, 256, seed=6))
+    cpu[which] = torch.zeros_like(cpu[which])           # g, W1, W3 or W2
+    bb.bb_set_variant(variant)
+    try:
+        Y = bb.bb_rmsnorm_swiglu_ffn(*dev(cpu), 1e-6)
+        torch.cuda.synchronize()
+    finally:
+        bb.bb_set_variant(bb.VARIANT_AUTO)
+    assert torch.all(Y.float() == 0)
+
+
+def test_eps_matters_when_rows_are_tiny():
+    # mean(x^2) ~ eps: the output must follow the oracle, which a kernel that
+    # drops eps or puts it outside the root would miss by tens of percent
+    cpu = list(bb_inputs.make_ffn(16, 256, 512, seed=8))
+    cpu[0] = (cpu[0].float() * 1e-3).to(torch.bfloat16)
+    for v in (bb.VARIANT_STREAM, bb.VARIANT_SNAPSHOT1):
+        assert ffn_case(cpu, 1e-6, variant=v) <= TOL
+
+
+def test_unfused_small():
+    assert ffn_case(bb_inputs.make_config("c1"), 1e-6, unfused=True) <= TOL
+    assert ffn_case(bb_inputs.make_ffn(130, 264, 712, seed=1), 1e-6, unfused=True) <= TOL
+
+
+@pytest.mark.parametrize("M,D,N", [(1, 64, 64), (64, 256, 512), (130, 264, 712), (300, 520, 1032)])
+@pytest.mark.parametrize("unfused", [False, True])
+def test_ln_small(M, D, N, unfused):
+    cpu = bb_inputs.make_ln(M, D, N, seed=M)
+    Y = bb.bb_layernorm_matmul(*dev(cpu), 1e-5, unfused=unfused)
+    torch.cuda.synchronize()
+    ref = orc.layernorm_matmul(*cpu, 1e-5)
+    assert row_rel_err(Y, ref) <= TOL
+
+
+def test_ln_gamma_zero_gives_bias_row():
+    X, ga, be, W = bb_inputs.make_ln(40, 128, 256, seed=2)
+    ga = torch.zeros_like(ga)
+    Y = bb.bb_layernorm_matmul(*dev((X, ga, be, W)), 1e-5)
+    torch.cuda.synchronize()
+    ref = orc.layernorm_matmul(X, ga, be, W, 1e-5)
+    assert row_rel_err(Y, ref) <= TOL
+    assert torch.all(Y == Y[0:1])                        # every row identical
+
+
+# ------------------------------------------------------------ full-size configs
+def test_c2_decode_full():
+    c = bb_inputs.CONFIGS["c2"]
+    cpu = bb_inputs.make_config("c2")
+    for v in (bb.VARIANT_AUTO, bb.VARIANT_SNAPSHOT1):
+        err = ffn_case(cpu, c.eps, variant=v)
+        print("c2 variant", v, "rel err", err)
+        assert err <= TOL
+
+
+def test_c3_prefill_sampled_rows():
+    c = bb_inputs.CONFIGS["c3"]
+    cpu = bb_inputs.make_config("c3")
+    rows = sample_rows(c.M)
+    err = ffn_case(cpu, c.eps, rows=rows)
+    print("c3 rel err", err, "rows", len(rows))
+    assert err <= TOL
+
+
+def test_c4_large_sampled_rows():
+    c = bb_inputs.CONFIGS["c4"]
+    cpu = bb_inputs.make_config("c4")
+    rows = sample_rows(c.M, tile=1024, extra=2)
+    err = ffn_case(cpu, c.eps, rows=rows)
+    print("c4 rel err", err, "rows", len(rows))
+    assert err <= TOL
+
+
+def test_c5_ln_sampled_rows():
+    c = bb_inputs.CONFIGS["c5"]
+    cpu = bb_inputs.make_config("c5")
+    rows = sample_rows(c.M, tile=1024, extra=4)
+    Y = bb.bb_layernorm_matmul(*dev(cpu), c.eps)
+    torch.cuda.synchronize()
+    ref = orc.layernorm_matmul(*cpu, c.eps, rows=rows)
+    err = row_rel_err(Y[rows], ref)
+    print("c5 rel err", err, "rows", len(rows))
+    assert err <= TOL
