@@ -1,0 +1,250 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused RMSNorm -> FFN-SwiGLU hot path on ONE MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--no-cpu]
+
+A "step" is one pass of the whole hot path over one batch of synthetic input
+(`bb_rmsnorm_swiglu_ffn`, or `bb_layernorm_matmul` for c5) with every input
+already resident in HBM.  Prints ONE JSON line.  The primary workload is the
+prefill shape c3 (M=2048, D=4096, F=11008; TFLOP/s against the bf16 matrix-core
+peak); the decode shape c2 (M=16; GB/s against the HBM peak) is measured in the
+same run and reported in the "decode" object with its own roofline.  The fp64
+oracle is timed on the host cores on a bounded sample ("cpu_baseline") and the
+same sample gives the parity figure.  The unfused kernel sequence is timed
+beside the fused one.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
+
+
+def flops_of(cfg):
+    return (6.0 if cfg.op == "ffn" else 2.0) * cfg.M * cfg.D * cfg.F
+
+
+def bytes_of(cfg):
+    if cfg.op == "ffn":
+        return 2.0 * (3 * cfg.D * cfg.F + 2 * cfg.M * cfg.D + cfg.D)
+    return 2.0 * (cfg.M * cfg.D + cfg.D * cfg.F + cfg.M * cfg.F + 2 * cfg.D)
+
+
+def dominant_kernel(cfg, variant_stream):
+    """name in the library's per-kernel profile, algorithmic work of one launch, bound"""
+    if cfg.op == "ln":
+        return "gemm_ln", 2.0 * cfg.M * cfg.D * cfg.F, "mfma"
+    if variant_stream:
+        return "ffn_stream", bytes_of(cfg), "hbm"
+    return "gemm_gateup", 4.0 * cfg.M * cfg.D * cfg.F, "mfma"
+
+
+def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
+    cfg = bb_inputs.CONFIGS[name]
+    cpu = bb_inputs.make_config(name)
+    stream_variant = cfg.op == "ffn" and cfg.M <= 16
+    # decode: rotate weight sets so that the 256 MB memory-side cache cannot hold them
+    nsets = 3 if stream_variant else 1
+    dev_sets = []
+    for s in range(nsets):
+        src = cpu if s == 0 else bb_inputs.make_config(name, seed=s)
+        d = [t.cuda() for t in src]
+        if s > 0:                      # same activations, different weights
+            d[0], d[1] = dev_sets[0][0], dev_sets[0][1]
+        dev_sets.append(d)
+    out = torch.empty((cfg.M, cfg.D if cfg.op == "ffn" else cfg.F), dtype=torch.bfloat16, device="cuda")
+
+    def step(i, unfused=False):
+        d = dev_sets[i % nsets]
+        if cfg.op == "ffn":
+            bb.bb_rmsnorm_swiglu_ffn(*d, cfg.eps, Y=out, unfused=unfused)
+        else:
+            bb.bb_layernorm_matmul(*d, cfg.eps, Y=out, unfused=unfused)
+
+    def timed(unfused=False):
+        for i in range(warmup):
+            step(i, unfused)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for i in range(steps):
+            step(i, unfused)
+        e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3
+        return max(wall, e0.elapsed_time(e1)) / steps, e0.elapsed_time(e1) / steps
+
+    ms_step, ms_step_events = timed(False)
+    # result of the fused path on weight set 0, kept for the parity figure
+    step(0, False)
+    torch.cuda.synchronize()
+    y_fused = out.clone()
+
+    # per-kernel durations (HIP events recorded by the library on the launch stream)
+    bb.bb_profile_enable(True)
+    per = {}
+    for i in range(steps):
+        step(i, False)
+        for kname, ms in bb.bb_profile_last():
+            per.setdefault(kname, []).append(ms)
+    bb.bb_profile_enable(False)
+    kernels_ms = {k: float(np.mean(v)) for k, v in per.items()}
+
+    ms_unfused, _ = timed(True)
+
+    dom, work, bound = dominant_kernel(cfg, stream_variant)
+    dom_ms = kernels_ms[dom]
+    if bound == "mfma":
+        achieved, peak, unit = work / (dom_ms * 1e-3) / 1e12, PEAK_BF16_TFLOPS, "TFLOP/s"
+    else:
+        achieved, peak, unit = work / (dom_ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
+    res = {
+        "workload": name, "op": cfg.op, "M": cfg.M, "D": cfg.D, "F_or_N": cfg.F,
+        "variant": "stream" if stream_variant else ("snapshot1" if cfg.op == "ffn" else "fused_ln"),
+        "ms_per_step": ms_step, "ms_per_step_events": ms_step_events,
+        "tflops": flops_of(cfg) / (ms_step * 1e-3) / 1e12,
+        "gbs": bytes_of(cfg) / (ms_step * 1e-3) / 1e9,
+        "kernels_ms": kernels_ms,
+        "unfused_ms_per_step": ms_unfused,
+        "roofline": {"kernel": dom, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+                     "frac": achieved / peak, "traffic": None},
+    }
+
+    if with_cpu:
+        # bounded oracle sample: first a few rows to size the sample, then ~15 s of work
+        rows_all = list(range(cfg.M))
+        probe = rows_all[:: max(1, cfg.M // 16)][:16]
+        t0 = time.perf_counter()
+        _oracle(orc, cfg, cpu, probe)
+        per_row = (time.perf_counter() - t0) / len(probe)
+        n = int(min(cfg.M, max(16, 15.0 / max(per_row, 1e-9))))
+        rng = np.random.default_rng(0)
+        rows = sorted(set(rng.choice(cfg.M, size=n, replace=False).tolist()) | {0, cfg.M - 1})
+        reps, t_total, ref = 0, 0.0, None
+        while t_total < 10.0 and reps < 64:       # small configs: repeat to reach ~10 s
+            t0 = time.perf_counter()
+            ref = _oracle(orc, cfg, cpu, rows)
+            t_total += time.perf_counter() - t0
+            reps += 1
+        sec_per_row = t_total / (reps * len(rows))
+        row_work = flops_of(cfg) / cfg.M
+        y = y_fused[rows].float().cpu().numpy().astype(np.float64)
+        err = float((np.linalg.norm(y - ref, axis=1) / np.linalg.norm(ref, axis=1)).max())
+        res["parity"] = {"max_row_rel_err": err, "rows_checked": len(rows), "tolerance": 2e-2}
+        cpu_tflops = row_work / sec_per_row / 1e12
+        res["cpu_baseline"] = {
+            "value": cpu_tflops if bound == "mfma" else bytes_of(cfg) / (sec_per_row * cfg.M) / 1e9,
+            "unit": "TFLOP/s" if bound == "mfma" else "GB/s",
+            "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"{len(rows)} of {cfg.M} rows of {name}, all output columns, x{reps} repeats, "
+                      f"{t_total:.1f} s; whole-workload time extrapolated as seconds_per_row * M",
+            "seconds_full_workload_extrapolated": sec_per_row * cfg.M,
+        }
+    del dev_sets
+    torch.cuda.empty_cache()
+    return res
+
+
+def _oracle(orc, cfg, cpu, rows):
+    if cfg.op == "ffn":
+        return orc.rmsnorm_swiglu_ffn(*cpu, cfg.eps, rows=rows)
+    return orc.layernorm_matmul(*cpu, cfg.eps, rows=rows)
+
+
+def calibrate(torch, bb):
+    """measured streaming-read and matrix-core peaks (context for the spec-sheet denominators)"""
+    buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    buf.fill_(1)
+    sink = torch.zeros(4096, dtype=torch.float32, device="cuda")
+    def t(fn, n):
+        fn(); torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+    ms_r = t(lambda: bb.bb_calib_read(buf, sink), 10)
+    iters, wgs = 4000, 1024
+    ms_m = t(lambda: bb.bb_calib_mfma(wgs, iters, sink), 3)
+    return {"read_gbs": buf.numel() / (ms_r * 1e-3) / 1e9,
+            "mfma_bf16_tflops": wgs * 4 * iters * 16 * 32768.0 / (ms_m * 1e-3) / 1e12}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--also", default="c2", help="comma list of further workloads reported in 'others' "
+                    "(the decode shape c2 is reported as 'decode')")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing / parity sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import bb_inputs
+    import paper_2505_07829_amd as bb
+    from oracle import oracle as orc
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    bb.load()          # fails loudly if the HIP library has not been built
+
+    primary = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu, torch, bb, bb_inputs, orc, np)
+    others = {}
+    for name in [w for w in args.also.split(",") if w and w != args.workload]:
+        others[name] = run_workload(name, args.steps, args.warmup, not args.no_cpu, torch, bb, bb_inputs, orc, np)
+    peaks = calibrate(torch, bb)
+    bb.bb_shutdown()
+
+    mfma_bound = primary["roofline"]["bound"] == "mfma"
+    line = {
+        "metric": "fused RMSNorm+SwiGLU FFN TFLOP/s (% bf16 MFMA peak); decode HBM GB/s",
+        "value": primary["tflops"] if mfma_bound else primary["gbs"],
+        "unit": "TFLOP/s" if mfma_bound else "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": primary["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {primary['op']} M={primary['M']} D={primary['D']} "
+                               f"F_or_N={primary['F_or_N']} ({primary['variant']})"},
+        "roofline": primary["roofline"],
+        "cpu_baseline": primary.get("cpu_baseline"),
+        "parity": primary.get("parity"),
+        "kernels_ms": primary["kernels_ms"],
+        "unfused_ms_per_step": primary["unfused_ms_per_step"],
+        "measured_peaks": peaks,
+    }
+    if "c2" in others:
+        d = others.pop("c2")
+        line["decode"] = {
+            "workload": "c2: ffn M=16 D=4096 F=11008 (stream), 3 rotating weight sets",
+            "value": d["gbs"], "unit": "GB/s", "ms_per_step": d["ms_per_step"],
+            "roofline": d["roofline"], "cpu_baseline": d.get("cpu_baseline"), "parity": d.get("parity"),
+            "kernels_ms": d["kernels_ms"], "unfused_ms_per_step": d["unfused_ms_per_step"],
+        }
+    if others:
+        line["others"] = others
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -172,6 +172,19 @@ int bb_version(void);
 int bb_last_hip_error(void); /* raw hipError_t of the last BB_ERR_HIP, else 0 */
 
 /* ------------------------------------------------------------------------
+ * Per-kernel timing of the most recent operator call, for roofline reports.
+ * While enabled, every operator call records a HIP event on its stream before
+ * its first kernel and after each kernel (this serialises nothing but adds a
+ * few event packets, so time whole calls with profiling off).
+ * bb_profile_count: kernels recorded by the last call.
+ * bb_profile_get:   waits for kernel i of the last call and returns its
+ *                   duration in ms and a static name (host pointers).
+ */
+int bb_profile_enable(int on);
+int bb_profile_count(void);
+int bb_profile_get(int i, float* ms, const char** name);
+
+/* ------------------------------------------------------------------------
  * Calibration kernels for roofline denominators (not part of the operators).
  * bb_calib_copy:  dst[i] = src[i] for `bytes` bytes (multiple of 16), a plain
  *                 grid-stride copy; known traffic = bytes read + bytes written.

@@ -24,6 +24,7 @@ EXPORTS = [
     "bb_workspace_bytes", "bb_set_workspace", "bb_set_variant", "bb_get_variant",
     "bb_shutdown", "bb_status_string", "bb_version", "bb_last_hip_error",
     "bb_calib_copy", "bb_calib_read", "bb_calib_mfma",
+    "bb_profile_enable", "bb_profile_count", "bb_profile_get",
 ]
 
 _lib = None
@@ -58,6 +59,8 @@ def load() -> ctypes.CDLL:
     lib.bb_calib_copy.argtypes = [vp, vp, sz, vp]
     lib.bb_calib_read.argtypes = [vp, sz, vp, vp]
     lib.bb_calib_mfma.argtypes = [ci, ci, vp, vp]
+    lib.bb_profile_enable.argtypes = [ci]
+    lib.bb_profile_get.argtypes = [ci, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_char_p)]
     for name in EXPORTS:
         fn = getattr(lib, name)
         if name not in ("bb_workspace_bytes", "bb_status_string"):
@@ -168,3 +171,18 @@ def bb_calib_read(src, sink) -> None:
 
 def bb_calib_mfma(workgroups: int, iters: int, sink) -> None:
     _check(load().bb_calib_mfma(int(workgroups), int(iters), _ptr(sink), _stream()), "bb_calib_mfma")
+
+
+def bb_profile_enable(on: bool) -> None:
+    _check(load().bb_profile_enable(1 if on else 0), "bb_profile_enable")
+
+
+def bb_profile_last():
+    """[(kernel name, milliseconds)] of the most recent operator call (waits for it)."""
+    lib = load()
+    out = []
+    for i in range(int(lib.bb_profile_count())):
+        ms, name = ctypes.c_float(), ctypes.c_char_p()
+        _check(lib.bb_profile_get(i, ctypes.byref(ms), ctypes.byref(name)), "bb_profile_get")
+        out.append((name.value.decode(), float(ms.value)))
+    return out

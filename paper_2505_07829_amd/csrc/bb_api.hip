@@ -35,6 +35,16 @@ struct Workspace {
     int device = -1;
 } g_ws;
 
+// optional per-kernel timing of the most recent call (bb_profile_*)
+constexpr int kMaxProf = 8;
+struct Profile {
+    bool on = false;
+    int n = 0;                         // kernels recorded by the last call
+    hipEvent_t ev[kMaxProf + 1] = {};
+    const char* name[kMaxProf] = {};
+    bool created = false;
+} g_prof;
+
 struct DeviceInfo {
     bool known = false;
     bool gfx950 = false;
@@ -85,6 +95,18 @@ int read_variant() {
         }
     }
     return g_variant;
+}
+
+void prof_begin(hipStream_t st) {
+    if (!g_prof.on) return;
+    g_prof.n = 0;
+    (void)hipEventRecord(g_prof.ev[0], st);
+}
+void prof_mark(const char* name, hipStream_t st) {
+    if (!g_prof.on || g_prof.n >= kMaxProf) return;
+    g_prof.name[g_prof.n] = name;
+    ++g_prof.n;
+    (void)hipEventRecord(g_prof.ev[g_prof.n], st);
 }
 
 // ---------------------------------------------------------------- validation
@@ -226,6 +248,7 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
     if (big) hipLaunchKernelGGL((gemm_kernel<MODE, 256>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((gemm_kernel<MODE, 128>), grid, block, 0, st, a);
     BB_HIP(hipGetLastError());
+    prof_mark(MODE == MODE_GATEUP ? "gemm_gateup" : MODE == MODE_LN ? "gemm_ln" : "gemm_plain", st);
     return BB_OK;
 }
 
@@ -261,7 +284,9 @@ int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u
         std::fprintf(stderr, "[bb] stream M %d D %d F %d items %d/%d per wg %d/%d parity %d\n", M, D, F,
                      a.items1, a.items2, a.per1, a.per2, par);
     void* params[] = {(void*)&a};
+    prof_begin(st);   // (a scratch refill above, if any, is not part of the kernel's time)
     BB_HIP(hipLaunchCooperativeKernel((const void*)ffn_stream_kernel, dim3(G), dim3(STREAM_THREADS), params, 0, st));
+    prof_mark("ffn_stream", st);
     g_ws.parity = 1 - par;
     return BB_OK;
 }
@@ -358,6 +383,7 @@ int bb_rmsnorm_swiglu_ffn(const void* X, const void* g, const void* W1, const vo
     // first snapshot: hidden written once (bf16), then contracted with W2
     u16* H = (u16*)((char*)g_ws.ptr + zone);
     mark_dirty(zone);
+    prof_begin(st);
     if (int rc = launch_gemm<MODE_GATEUP>(x, (int)D, w1, w3, (int)F, H, (int)F, gg, nullptr, nullptr, (int)M,
                                           (int)F, (int)D, eps, dev->cus, st))
         return rc;
@@ -377,9 +403,11 @@ int bb_layernorm_matmul(const void* X, const void* gamma, const void* beta, cons
     mark_dirty(0);
     float* colc = (float*)g_ws.ptr;
     float* colb = (float*)((char*)g_ws.ptr + align_up((size_t)N * 4));
+    prof_begin(st);
     hipLaunchKernelGGL(colvec_kernel, dim3((unsigned)((N + 63) / 64)), dim3(256), 0, st, (const u16*)W,
                        (const u16*)gamma, (const u16*)beta, colc, colb, (int)D, (int)N);
     BB_HIP(hipGetLastError());
+    prof_mark("colvec", st);
     return launch_gemm<MODE_LN>((const u16*)X, (int)D, (const u16*)W, nullptr, (int)N, (u16*)Y, (int)N,
                                 (const u16*)gamma, colc, colb, (int)M, (int)N, (int)D, eps, dev->cus, st);
 }
@@ -401,9 +429,11 @@ int bb_rmsnorm_swiglu_ffn_unfused(const void* X, const void* g, const void* W1, 
     u16* P = (u16*)(base + align_up((size_t)M * D * 2));
     u16* Q = (u16*)((char*)P + nMF);
     u16* H = (u16*)((char*)Q + nMF);
+    prof_begin(st);
     hipLaunchKernelGGL(rmsnorm_rows_kernel, dim3((unsigned)M), dim3(256), 0, st, (const u16*)X, (const u16*)g,
                        Xh, (int)D, eps);
     BB_HIP(hipGetLastError());
+    prof_mark("rmsnorm_rows", st);
     if (int rc = launch_gemm<MODE_PLAIN>(Xh, (int)D, (const u16*)W1, nullptr, (int)F, P, (int)F, nullptr,
                                          nullptr, nullptr, (int)M, (int)F, (int)D, 0.f, dev->cus, st))
         return rc;
@@ -414,6 +444,7 @@ int bb_rmsnorm_swiglu_ffn_unfused(const void* X, const void* g, const void* W1, 
     hipLaunchKernelGGL(silu_mul_kernel, dim3((unsigned)std::min<size_t>((n8 + 255) / 256, 4096)), dim3(256), 0,
                        st, P, Q, H, n8);
     BB_HIP(hipGetLastError());
+    prof_mark("silu_mul", st);
     return launch_gemm<MODE_PLAIN>(H, (int)F, (const u16*)W2, nullptr, (int)D, (u16*)Y, (int)D, nullptr,
                                    nullptr, nullptr, (int)M, (int)D, (int)F, 0.f, dev->cus, st);
 }
@@ -429,11 +460,40 @@ int bb_layernorm_matmul_unfused(const void* X, const void* gamma, const void* be
     hipStream_t st = as_stream(stream);
     mark_dirty(0);
     u16* Z = (u16*)g_ws.ptr;
+    prof_begin(st);
     hipLaunchKernelGGL(layernorm_rows_kernel, dim3((unsigned)M), dim3(256), 0, st, (const u16*)X,
                        (const u16*)gamma, (const u16*)beta, Z, (int)D, eps);
     BB_HIP(hipGetLastError());
+    prof_mark("layernorm_rows", st);
     return launch_gemm<MODE_PLAIN>(Z, (int)D, (const u16*)W, nullptr, (int)N, (u16*)Y, (int)N, nullptr, nullptr,
                                    nullptr, (int)M, (int)N, (int)D, 0.f, dev->cus, st);
+}
+
+// ---------------------------------------------------------------- profiling
+int bb_profile_enable(int on) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (on && !g_prof.created) {
+        for (int i = 0; i <= kMaxProf; ++i) BB_HIP(hipEventCreate(&g_prof.ev[i]));
+        g_prof.created = true;
+    }
+    g_prof.on = on != 0;
+    g_prof.n = 0;
+    return BB_OK;
+}
+
+int bb_profile_count(void) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    return g_prof.n;
+}
+
+int bb_profile_get(int i, float* ms, const char** name) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!ms) return BB_ERR_NULL;
+    if (!g_prof.created || i < 0 || i >= g_prof.n) return BB_ERR_SHAPE;
+    BB_HIP(hipEventSynchronize(g_prof.ev[i + 1]));
+    BB_HIP(hipEventElapsedTime(ms, g_prof.ev[i], g_prof.ev[i + 1]));
+    if (name) *name = g_prof.name[i];
+    return BB_OK;
 }
 
 // ------------------------------------------------------------- calibration
