@@ -30,8 +30,7 @@ struct Workspace {
     size_t bytes = 0;
     bool user = false;
     size_t clean = 0;                  // leading bytes known to be zero
-    int64_t stream_D = -1, stream_F = -1;
-    int parity = 0;                    // pre-activation buffer the next stream call uses
+    unsigned bar_count = 0;            // grid barriers completed so far (the barrier words only increase)
     int device = -1;
 } g_ws;
 
@@ -157,25 +156,39 @@ int validate_ln(const void* X, const void* gamma, const void* beta, const void* 
 
 // ------------------------------------------------------------ workspace plan
 struct StreamPlan {
-    size_t yacc_off, cnt_off, pq_off[2], pq_bytes, zone_bytes;
-    int Fp, nnb;
+    size_t bar_off, ppart_off, spart_off, h_off, ypart_off, zone_bytes, total_bytes;
+    int Fp, nkb1, nfb, items1, per1, S1, nkb2, nnb, items2, per2, S2;
 };
 
-StreamPlan stream_plan(int64_t D, int64_t F) {
+// Layout of the streaming kernel's scratch for G workgroups.  Only the barrier
+// word (the "zone") has to be zero between calls.
+StreamPlan stream_plan(int64_t D, int64_t F, int G) {
     StreamPlan s;
     s.Fp = (int)((F + 127) / 128 * 128);
+    s.nkb1 = (int)((D + 31) / 32);
+    s.nfb = (int)((F + 127) / 128);
+    s.items1 = s.nkb1 * s.nfb;
+    s.per1 = (s.items1 + G - 1) / G;
+    s.S1 = (s.nkb1 - 1) / s.per1 + 2;
+    s.nkb2 = (int)((F + 31) / 32);
     s.nnb = (int)((D + 127) / 128);
-    s.yacc_off = 0;
-    s.cnt_off = align_up((size_t)kStreamMaxM * D * 4);
-    s.pq_bytes = align_up(((size_t)2 * 16 * s.Fp + 64) * 4);
-    s.pq_off[0] = s.cnt_off + align_up((size_t)s.nnb * 4);
-    s.pq_off[1] = s.pq_off[0] + s.pq_bytes;
-    s.zone_bytes = s.pq_off[1] + s.pq_bytes;
+    s.items2 = s.nkb2 * s.nnb;
+    s.per2 = (s.items2 + G - 1) / G;
+    s.S2 = (s.nkb2 - 1) / s.per2 + 2;
+    s.bar_off = 0;
+    s.zone_bytes = align_up((size_t)BAR_WORDS * 4);
+    s.ppart_off = s.zone_bytes;
+    s.spart_off = s.ppart_off + align_up((size_t)s.nfb * s.S1 * 4096 * 4);
+    s.h_off = s.spart_off + align_up((size_t)s.S1 * 16 * 4);
+    s.ypart_off = s.h_off + align_up((size_t)16 * s.Fp * 2);
+    s.total_bytes = s.ypart_off + align_up((size_t)s.nnb * s.S2 * 2048 * 4);
     return s;
 }
 
+constexpr int kPlanCUs = 256;   // workgroups assumed by bb_workspace_bytes (one per compute unit of an MI355X)
+
 size_t zone_bytes(int op, int64_t M, int64_t D, int64_t F) {
-    if (op == BB_OP_RMSNORM_SWIGLU_FFN && M <= kStreamMaxM) return stream_plan(D, F).zone_bytes;
+    if (op == BB_OP_RMSNORM_SWIGLU_FFN && M <= kStreamMaxM) return stream_plan(D, F, kPlanCUs).total_bytes;
     return 0;
 }
 
@@ -254,40 +267,40 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
 
 int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u16* W2, u16* Y, int M,
                int D, int F, float eps, int cus, hipStream_t st) {
-    const StreamPlan sp = stream_plan(D, F);
+    static int resident = -1;      // workgroups of the streaming kernel one compute unit can hold
+    if (resident < 0) {
+        int n = 0;
+        BB_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, ffn_stream_kernel, STREAM_THREADS, 0));
+        resident = n;
+    }
+    if (resident < 1) return BB_ERR_VARIANT;   // the grid barrier needs every workgroup resident
+    const int G = std::min(cus, kPlanCUs);
+    const StreamPlan sp = stream_plan(D, F, G);
     char* base = (char*)g_ws.ptr;
-    if (g_ws.clean < sp.zone_bytes || g_ws.stream_D != D || g_ws.stream_F != F) {
+    if (g_ws.clean < sp.zone_bytes) {
         if (int rc = fill_zero(base, sp.zone_bytes, st)) return rc;
         g_ws.clean = sp.zone_bytes;
-        g_ws.stream_D = D;
-        g_ws.stream_F = F;
-        g_ws.parity = 0;
+        g_ws.bar_count = 0;
     }
     StreamArgs a;
     a.X = X; a.g = g; a.W1 = W1; a.W3 = W3; a.W2 = W2; a.Y = Y;
-    const int par = g_ws.parity;
-    a.pq = (float*)(base + sp.pq_off[par]);
-    a.ssq = a.pq + (size_t)2 * 16 * sp.Fp;
-    a.zero_ptr = (float*)(base + sp.pq_off[1 - par]);
-    a.zero_count4 = (int)(sp.pq_bytes / 16);
-    a.yacc = (float*)(base + sp.yacc_off);
-    a.cnt = (unsigned*)(base + sp.cnt_off);
+    a.ppart = (float*)(base + sp.ppart_off);
+    a.spart = (float*)(base + sp.spart_off);
+    a.H = (u16*)(base + sp.h_off);
+    a.ypart = (float*)(base + sp.ypart_off);
+    a.bar = (unsigned*)(base + sp.bar_off);
+    a.bar_base = g_ws.bar_count;
     a.M = M; a.D = D; a.F = F; a.Fp = sp.Fp; a.eps = eps;
-    const int G = cus;
-    a.nkb1 = (D + 31) / 32;
-    a.items1 = a.nkb1 * ((F + 127) / 128);
-    a.per1 = (a.items1 + G - 1) / G;
-    a.nkb2 = (F + 31) / 32;
-    a.items2 = a.nkb2 * sp.nnb;
-    a.per2 = (a.items2 + G - 1) / G;
+    a.nkb1 = sp.nkb1; a.nfb = sp.nfb; a.items1 = sp.items1; a.per1 = sp.per1; a.S1 = sp.S1;
+    a.nkb2 = sp.nkb2; a.nnb = sp.nnb; a.items2 = sp.items2; a.per2 = sp.per2; a.S2 = sp.S2;
     if (log_on())
-        std::fprintf(stderr, "[bb] stream M %d D %d F %d items %d/%d per wg %d/%d parity %d\n", M, D, F,
-                     a.items1, a.items2, a.per1, a.per2, par);
-    void* params[] = {(void*)&a};
-    prof_begin(st);   // (a scratch refill above, if any, is not part of the kernel's time)
-    BB_HIP(hipLaunchCooperativeKernel((const void*)ffn_stream_kernel, dim3(G), dim3(STREAM_THREADS), params, 0, st));
+        std::fprintf(stderr, "[bb] stream M %d D %d F %d items %d/%d per wg %d/%d slots %d/%d\n", M, D, F,
+                     a.items1, a.items2, a.per1, a.per2, a.S1, a.S2);
+    prof_begin(st);   // (a refill of the barrier word above, if any, is not part of the kernel's time)
+    hipLaunchKernelGGL(ffn_stream_kernel, dim3(G), dim3(STREAM_THREADS), 0, st, a);
+    BB_HIP(hipGetLastError());
     prof_mark("ffn_stream", st);
-    g_ws.parity = 1 - par;
+    g_ws.bar_count += 3u;   // grid barriers per call
     return BB_OK;
 }
 

@@ -1,32 +1,42 @@
 // Weight-streaming RMSNorm -> FFN-SwiGLU kernel for few rows (decode), gfx950.
 //
 // With at most 16 rows the operator is a pure stream over the three weight
-// matrices.  One cooperative persistent kernel (one workgroup per compute
-// unit) runs the two maps of Example 3's first fused snapshot back to back:
+// matrices.  One persistent kernel (one workgroup per compute unit, all
+// resident at once) runs the maps of Example 3's first fused snapshot back to
+// back, separated by grid barriers:
 //
-//   phase 1 (K-map): work item = (block of 128 hidden units, block of 32 model
-//     channels).  Items are dealt out evenly over the workgroups, so the
-//     reduction over the model dimension is a PARALLEL reduction (Rule 3,
-//     atomic form): partial pre-activations (X diag(g)) W1, (X diag(g)) W3 are
-//     summed with fp32 atomics into a cache-resident scratch of 2 x 16 x F
-//     floats, together with sum x^2.
-//   grid barrier
-//   phase 2 (N-map): work item = (block of 128 output columns, block of 32
-//     hidden units).  The consumer applies the inverse norm after the dots
-//     (Rule 4), Swish and the gate to the pre-activations it reads back, and
-//     contracts with W2; partial outputs are again reduced with fp32 atomics.
-//     The last workgroup to finish an output block converts it to bf16.
+//   phase 1 (K-map): work item = (block of 32 model channels, block of 128
+//     hidden units).  Items are dealt out evenly over the workgroups, so the
+//     reduction over the model dimension is a PARALLEL reduction (Rule 3): a
+//     workgroup sums its consecutive items in registers and LDS and stores its
+//     partial pre-activations (X diag(g)) W1, (X diag(g)) W3 and its partial
+//     sum x^2 in a slot of its own.
+//   phase 1b: the (at most a few) partial sums per hidden unit are added, the
+//     inverse norm is applied AFTER the dots (Rule 4), then Swish and the
+//     gate; the hidden block (16 x F, bf16) is written once to a cache-
+//     resident scratch.
+//   phase 2 (N-map): work item = (block of 32 hidden units, block of 128
+//     output columns), again dealt out evenly; partial outputs go to slots.
+//   phase 2b: partial outputs are added and stored as bf16.
+//
+// The parallel reductions use per-workgroup slots instead of atomics: fp32
+// atomics run at about one per L2 channel per clock on this part and stall the
+// weight stream behind them (measured), plain stores do not.  No scratch needs
+// to be zero on entry except the barrier word.
 //
 // Every weight element is read from HBM exactly once, by exactly one
-// wavefront, with 16-byte loads that cover 256 contiguous bytes per row; the
-// 8x8 in-register transposition turns them into matrix-instruction operands
-// without touching LDS.  Scratch buffers are all-zero on entry and are
-// returned to all-zero: the output accumulator by the finishing workgroup,
-// the pre-activation buffer by the NEXT call (two buffers alternate).
+// wavefront, with 16-byte loads; the 8x8 in-register transposition turns them
+// into matrix-instruction operands without touching LDS.  The grid barrier is
+// a monotonically increasing counter in the workspace; its wait is bounded, so
+// the kernel always terminates.
 #pragma once
-#include <hip/hip_cooperative_groups.h>
-
 #include "bb_common.h"
+
+// Optional timeline hook: a debugging build may define BB_STREAM_TRACE(slot) to
+// record a timestamp per workgroup; it expands to nothing in the library.
+#ifndef BB_STREAM_TRACE
+#define BB_STREAM_TRACE(slot)
+#endif
 
 namespace bb {
 
@@ -39,29 +49,21 @@ struct StreamArgs {
     const u16* W3;     // [D, F]
     const u16* W2;     // [F, D]
     u16* Y;            // [M, D]
-    float* pq;         // [2][16][Fp] pre-activations of this call, zero on entry
-    float* ssq;        // [16] row sums of squares of this call, zero on entry
-    float* zero_ptr;   // the other call parity's pq+ssq block, zeroed here
-    int zero_count4;   // its length in float4
-    float* yacc;       // [16][D] output accumulator, zero on entry and exit
-    unsigned* cnt;     // [nnb] arrival counters, zero on entry and exit
+    float* ppart;      // [nfb][S1][2][16][128] partial pre-activations (P then Q)
+    float* spart;      // [S1][16] partial row sums of squares
+    u16* H;            // [16][Fp] hidden block, bf16
+    float* ypart;      // [nnb][S2][16][128] partial outputs
+    unsigned* bar;     // BAR_WORDS barrier words (see grid_arrive), zero before the first call
+    unsigned bar_base; // grid barriers completed before this call
     int M, D, F, Fp;
-    int nkb1, items1, per1;   // phase 1: D/32 blocks, total items, items per workgroup
-    int nkb2, items2, per2;   // phase 2: F/32 blocks
+    int nkb1, nfb, items1, per1, S1;   // phase 1: D/32 blocks, F/128 blocks, items, items per workgroup, slots
+    int nkb2, nnb, items2, per2, S2;   // phase 2: F/32 blocks, D/128 blocks, ...
     float eps;
 };
 
 struct StreamSmem {
     float red[4][2][16][128];   // per-wavefront partial tiles
-    unsigned flag;
 };
-
-__device__ __forceinline__ void atomic_add_f32(float* p, float v) {
-    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float coherent_load_f32(const float* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 // loads the 8 rows x 8 columns block of a row-major matrix this lane owns
 __device__ __forceinline__ void load_block(const u16* base, int ld, int row0, int nrows, int col,
@@ -71,220 +73,405 @@ __device__ __forceinline__ void load_block(const u16* base, int ld, int row0, in
         r[i] = (col_ok && row0 + i < nrows) ? ldg16(base + (size_t)(row0 + i) * ld + col) : zero4();
 }
 
+// acc[c][e] of a wavefront's 16 x 128 tile is row 4*(lane/16)+e, column 8*(lane%16)+c
+__device__ __forceinline__ void stash_tile(float (*dst)[128], const f32x4 (&acc)[8], int lane) {
+    const int jn = lane & 15, g4 = lane >> 4;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const f32x4 lo = {acc[0][e], acc[1][e], acc[2][e], acc[3][e]};
+        const f32x4 hi = {acc[4][e], acc[5][e], acc[6][e], acc[7][e]};
+        float* s = &dst[4 * g4 + e][8 * jn];
+        *reinterpret_cast<f32x4*>(s) = lo;
+        *reinterpret_cast<f32x4*>(s + 4) = hi;
+    }
+}
+
+// sum of the four wavefronts' tiles, 4 consecutive floats starting at flat index i4*4
+__device__ __forceinline__ f32x4 sum4(const float* red0, int stride, int i4) {
+    const f32x4 a = *reinterpret_cast<const f32x4*>(red0 + 4 * i4);
+    const f32x4 b = *reinterpret_cast<const f32x4*>(red0 + stride + 4 * i4);
+    const f32x4 c = *reinterpret_cast<const f32x4*>(red0 + 2 * stride + 4 * i4);
+    const f32x4 d = *reinterpret_cast<const f32x4*>(red0 + 3 * stride + 4 * i4);
+    return (a + b) + (c + d);
+}
+
+// Grid barrier in two halves.  All workgroups of the grid must be resident.
+// 256 simultaneous atomics and polls on ONE word serialise at its memory
+// channel (measured: > 10 us), so arrivals are counted in two levels: 16 groups
+// of workgroups (id mod 16) each own an arrival word, the last arriver of a
+// group bumps the top word, the last group's arriver publishes the barrier
+// number in 16 flag words, and a workgroup polls only its group's flag.  Every
+// word sits in its own 256-byte block.  All words only ever increase (the host
+// passes the number of barriers completed before the call), so nothing needs
+// resetting; the wait gives up after about two seconds.
+// Only thread 0 talks to the other workgroups, after the whole workgroup's
+// stores have been acknowledged.
+constexpr int BAR_GROUPS = 16;
+constexpr int BAR_STRIDE = 64;                 // words between barrier words (256 bytes)
+constexpr int BAR_WORDS = (2 * BAR_GROUPS + 2) * BAR_STRIDE;
+// word layout: group arrival g -> g, top -> 16, flag g -> 17 + g, timeout marker -> 33 (times BAR_STRIDE)
+
+// thread-level half: count this workgroup's arrival at barrier number k (>= 1)
+__device__ __forceinline__ void bar_signal(unsigned* bar, unsigned k) {
+    const unsigned G = gridDim.x, g = blockIdx.x % BAR_GROUPS;
+    const unsigned ngroups = G < BAR_GROUPS ? G : BAR_GROUPS;
+    const unsigned gsize = (G - g + BAR_GROUPS - 1) / BAR_GROUPS;
+    const unsigned old = __hip_atomic_fetch_add(bar + g * BAR_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old + 1u == gsize * k) {
+        const unsigned oldt = __hip_atomic_fetch_add(bar + BAR_GROUPS * BAR_STRIDE, 1u, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+        if (oldt + 1u == ngroups * k)
+            for (unsigned j = 0; j < ngroups; ++j)
+                __hip_atomic_store(bar + (BAR_GROUPS + 1 + j) * BAR_STRIDE, k, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+// thread-level half: wait until barrier number k has been published (bounded)
+__device__ __forceinline__ void bar_poll(unsigned* bar, unsigned k) {
+    const unsigned* flag = bar + (BAR_GROUPS + 1 + blockIdx.x % BAR_GROUPS) * BAR_STRIDE;
+    unsigned spins = 0;
+    while ((int)(__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - k) < 0) {
+        if (++spins > 8000000u) {
+            __hip_atomic_store(bar + (2 * BAR_GROUPS + 1) * BAR_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            break;
+        }
+        __builtin_amdgcn_s_sleep(2);
+    }
+}
+// whole workgroup: all its stores are complete, then thread 0 signals
+__device__ __forceinline__ void grid_arrive(unsigned* bar, unsigned k) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);                       // every store of this wavefront has been acknowledged
+    __syncthreads();
+    if (threadIdx.x == 0) bar_signal(bar, k);
+}
+
+// Data exchanged between workgroups inside the kernel is written with
+// agent-scope stores (written through, complete when acknowledged) and read
+// with agent-scope loads (never a stale cached copy).  So neither side needs a
+// cache write-back or invalidation around the barrier, and nothing waits on
+// the weight loads that are in flight.
+__device__ __forceinline__ void cstore8(void* p, u32 lo, u32 hi) {
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), ((unsigned long long)hi << 32) | lo,
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void cstore16f(float* p, const f32x4 v) {
+    cstore8(p, __float_as_uint(v[0]), __float_as_uint(v[1]));
+    cstore8(p + 2, __float_as_uint(v[2]), __float_as_uint(v[3]));
+}
+__device__ __forceinline__ u32x2 cload8(const void* p) {
+    const unsigned long long v =
+        __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    u32x2 r = {(u32)v, (u32)(v >> 32)};
+    return r;
+}
+__device__ __forceinline__ f32x4 cload16f(const float* p) {
+    const u32x2 a = cload8(p), b = cload8(p + 2);
+    f32x4 r = {__uint_as_float(a[0]), __uint_as_float(a[1]), __uint_as_float(b[0]), __uint_as_float(b[1])};
+    return r;
+}
+__device__ __forceinline__ float cload4f(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+constexpr int STREAM_NP1 = 2;   // phase 1 items (16 KiB each) a wavefront keeps in flight
+constexpr int STREAM_NP2 = 6;   // phase 2 items (8 KiB each) a wavefront keeps in flight
+
+struct StreamItem1 {
+    u32x4 r1[8], r3[8], rx, rg;
+};
+
 __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const StreamArgs p) {
     __shared__ StreamSmem sm;
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
     const int jn = lane & 15, g4 = lane >> 4;
     const int G = gridDim.x, b = blockIdx.x;
+    constexpr int RS = 2 * 16 * 128;               // floats per wavefront in sm.red
 
-    // ---- return the other parity's scratch to zero (nobody uses it now)
-    {
-        f32x4* z = reinterpret_cast<f32x4*>(p.zero_ptr);
-        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-        for (int i = b * STREAM_THREADS + t; i < p.zero_count4; i += G * STREAM_THREADS) z[i] = zero;
-    }
-
-    // =====================  phase 1: pre-activations  =====================
+    BB_STREAM_TRACE(0);
+    // =====================  phase 1: partial pre-activations  =====================
     {
         int i = b * p.per1;
         const int iend = min(i + p.per1, p.items1);
-        while (i < iend) {                         // one segment = one hidden block
+        while (i < iend) {                         // one segment = one block of 128 hidden units
             const int fb = i / p.nkb1, kb0 = i % p.nkb1;
             const int kb1 = min(p.nkb1, kb0 + (iend - i));
+            const int slot = b - (fb * p.nkb1) / p.per1;
             const int col = 128 * fb + 8 * jn;
             const bool col_ok = col < p.F;
             f32x4 accP[8], accQ[8];
 #pragma unroll
             for (int c = 0; c < 8; ++c) { accP[c] = f32x4{0, 0, 0, 0}; accQ[c] = f32x4{0, 0, 0, 0}; }
             float ssq = 0.f;
-
-            u32x4 r1[8], r3[8], rx, rg;
-            auto issue = [&](int kb) {
+            StreamItem1 it[STREAM_NP1];
+            auto issue = [&](int kb, StreamItem1& r) {          // nothing is loaded past the segment
+                const bool live = kb < kb1;
                 const int d0 = 32 * kb + 8 * g4;
-                load_block(p.W1, p.F, d0, p.D, col, col_ok, r1);
-                load_block(p.W3, p.F, d0, p.D, col, col_ok, r3);
-                const bool ok = d0 < p.D;
-                rx = (ok && jn < p.M) ? ldg16(p.X + (size_t)jn * p.D + d0) : zero4();
-                rg = ok ? ldg16(p.g + d0) : zero4();
+                load_block(p.W1, p.F, d0, p.D, col, col_ok && live, r.r1);
+                load_block(p.W3, p.F, d0, p.D, col, col_ok && live, r.r3);
+                const bool ok = live && d0 < p.D;
+                r.rx = (ok && jn < p.M) ? ldg16(p.X + (size_t)jn * p.D + d0) : zero4();
+                r.rg = ok ? ldg16(p.g + d0) : zero4();
             };
-            int kb = kb0 + w;
-            if (kb < kb1) issue(kb);
-            while (kb < kb1) {
-                // consume the registers of item kb, then refill them for kb + 4
-                Chunk xa;
+            // the wavefronts take the items round robin: kb0 + w, kb0 + w + 4, ...
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float x0 = bf_lo(rx[q]), x1 = bf_hi(rx[q]);
-                    ssq = fmaf(x0, x0, ssq);
-                    ssq = fmaf(x1, x1, ssq);
-                    xa.u[q] = pack_bf16(x0 * bf_lo(rg[q]), x1 * bf_hi(rg[q]));
-                }
-                u32x4 t1[8], t3[8];
-                transpose8x8(r1, t1);
-                transpose8x8(r3, t3);
-                kb += 4;
-                if (kb < kb1) issue(kb);
+            for (int u = 0; u < STREAM_NP1; ++u) issue(kb0 + w + 4 * u, it[u]);
+            for (int kbb = kb0 + w; kbb < kb1; kbb += 4 * STREAM_NP1) {
 #pragma unroll
-                for (int c = 0; c < 8; ++c) {
-                    Chunk b1, b3;
-                    b1.u = t1[c];
-                    b3.u = t3[c];
-                    accP[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa.v, b1.v, accP[c], 0, 0, 0);
-                    accQ[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa.v, b3.v, accQ[c], 0, 0, 0);
+                for (int u = 0; u < STREAM_NP1; ++u) {
+                    const int kb = kbb + 4 * u;
+                    if (kb < kb1) {
+                        // consume the registers of item kb, then refill them
+                        Chunk xa;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const float x0 = bf_lo(it[u].rx[q]), x1 = bf_hi(it[u].rx[q]);
+                            ssq = fmaf(x0, x0, ssq);
+                            ssq = fmaf(x1, x1, ssq);
+                            xa.u[q] = pack_bf16(x0 * bf_lo(it[u].rg[q]), x1 * bf_hi(it[u].rg[q]));
+                        }
+                        u32x4 t1[8], t3[8];
+                        transpose8x8(it[u].r1, t1);
+                        transpose8x8(it[u].r3, t3);
+                        issue(kb + 4 * STREAM_NP1, it[u]);
+#pragma unroll
+                        for (int c = 0; c < 8; ++c) {
+                            Chunk b1, b3;
+                            b1.u = t1[c];
+                            b3.u = t3[c];
+                            accP[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa.v, b1.v, accP[c], 0, 0, 0);
+                            accQ[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa.v, b3.v, accQ[c], 0, 0, 0);
+                        }
+                    }
                 }
             }
-            // ---- reduce the 4 wavefronts in LDS, then one atomic per element.
-            // accX[c][e] is row (token) 4*g4+e, column 8*jn+c of the block.
+            BB_STREAM_TRACE(1);
+            // ---- add the 4 wavefronts in LDS and store the workgroup's partial tile in its slot
+            stash_tile(sm.red[w][0], accP, lane);
+            stash_tile(sm.red[w][1], accQ, lane);
+            __syncthreads();
+            float* dst = p.ppart + (size_t)(fb * p.S1 + slot) * RS;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const f32x4 p0 = {accP[0][e], accP[1][e], accP[2][e], accP[3][e]};
-                const f32x4 p1 = {accP[4][e], accP[5][e], accP[6][e], accP[7][e]};
-                const f32x4 q0 = {accQ[0][e], accQ[1][e], accQ[2][e], accQ[3][e]};
-                const f32x4 q1 = {accQ[4][e], accQ[5][e], accQ[6][e], accQ[7][e]};
-                float* rp = &sm.red[w][0][4 * g4 + e][8 * jn];
-                float* rq = &sm.red[w][1][4 * g4 + e][8 * jn];
-                *reinterpret_cast<f32x4*>(rp) = p0;
-                *reinterpret_cast<f32x4*>(rp + 4) = p1;
-                *reinterpret_cast<f32x4*>(rq) = q0;
-                *reinterpret_cast<f32x4*>(rq + 4) = q1;
+            for (int j = 0; j < 4; ++j) {
+                const int i4 = t + STREAM_THREADS * j;        // float4 index in [2][16][128]
+                cstore16f(dst + 4 * i4, sum4(&sm.red[0][0][0][0], RS, i4));
             }
-            if (fb == 0) {   // sum x^2 is counted once: by the items of hidden block 0
+            if (fb == 0) {   // sum x^2 is counted once per model channel: by the items of hidden block 0
                 ssq += __shfl_xor(ssq, 16);
                 ssq += __shfl_xor(ssq, 32);
-                if (lane < 16 && ssq != 0.f) atomic_add_f32(p.ssq + lane, ssq);
-            }
-            __syncthreads();
-#pragma unroll 4
-            for (int j = 0; j < 16; ++j) {
-                const int idx = t + STREAM_THREADS * j;       // [pq][token][col]
-                const int cc = idx & 127, tok = (idx >> 7) & 15, sel = idx >> 11;
-                const float v = sm.red[0][sel][tok][cc] + sm.red[1][sel][tok][cc] +
-                                sm.red[2][sel][tok][cc] + sm.red[3][sel][tok][cc];
-                if (v != 0.f) atomic_add_f32(p.pq + (size_t)(sel * 16 + tok) * p.Fp + 128 * fb + cc, v);
+                __syncthreads();
+                if (lane < 16) sm.red[w][0][0][lane] = ssq;
+                __syncthreads();
+                if (t < 16)
+                    __hip_atomic_store(p.spart + slot * 16 + t,
+                                       sm.red[0][0][0][t] + sm.red[1][0][0][t] + sm.red[2][0][0][t] + sm.red[3][0][0][t],
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             __syncthreads();
             i += kb1 - kb0;
         }
     }
 
-    // ---- phase 2 work of this workgroup; the first weight blocks are
-    // requested BEFORE the grid barrier so that HBM stays busy across it.
-    int i2 = b * p.per2;
+    BB_STREAM_TRACE(2);
+    grid_arrive(p.bar, p.bar_base + 1u);
+
+    // ---- phase 2 work of this workgroup.  Wavefronts 1..3 request their first
+    // weight blocks now, so HBM stays busy while wavefront 0 runs the short
+    // synchronised part (barrier, hidden block, barrier) with nothing in flight
+    // that it would have to wait for.
+    const int i2 = b * p.per2;
     const int iend2 = min(i2 + p.per2, p.items2);
-    u32x4 rA[8], rB[8];
-    auto issue2 = [&](int nb, int kb, int kb1) {
+    u32x4 pre[STREAM_NP2][8];
+    auto issue2 = [&](int nb, int kb, int kb1, u32x4 (&r)[8]) {
         const int col = 128 * nb + 8 * jn;
-        const bool col_ok = col < p.D;
-        load_block(p.W2, p.D, 32 * kb + 8 * g4, p.F, col, col_ok && kb < kb1, rA);
-        load_block(p.W2, p.D, 32 * (kb + 4) + 8 * g4, p.F, col, col_ok && kb + 4 < kb1, rB);
+        load_block(p.W2, p.D, 32 * kb + 8 * g4, p.F, col, col < p.D && kb < kb1, r);
     };
-    bool preloaded = false;
-    if (i2 < iend2) {
-        const int nb = i2 / p.nkb2, kb0 = i2 % p.nkb2;
-        const int kb1 = min(p.nkb2, kb0 + (iend2 - i2));
-        issue2(nb, kb0 + w, kb1);
-        preloaded = true;
-    }
-
-    cooperative_groups::this_grid().sync();
-
-    // =====================  phase 2: down projection  =====================
-    {
+    auto prefetch2 = [&]() {
+        if (i2 < iend2) {
+            const int nb = i2 / p.nkb2, kb0 = i2 % p.nkb2;
+            const int kb1 = min(p.nkb2, kb0 + (iend2 - i2));
+#pragma unroll
+            for (int u = 0; u < STREAM_NP2; ++u) issue2(nb, kb0 + w + 4 * u, kb1, pre[u]);
+        }
+    };
+    if (w != 0) {
+        prefetch2();
+    } else {
+        BB_STREAM_TRACE(3);
+        if (lane == 0) bar_poll(p.bar, p.bar_base + 1u);
+        BB_STREAM_TRACE(4);
+        // =====================  phase 1b: hidden block  =====================
+        const int groups_per_row = p.Fp / 8;                   // tasks: (row, 8 consecutive hidden units)
+        const int total = 16 * groups_per_row;
+        const int slots0 = min(G - 1, (p.nkb1 - 1) / p.per1) + 1;   // workgroups that saw hidden block 0
         const float invD = 1.0f / (float)p.D;
-        const float rinv = rsqrtf(coherent_load_f32(p.ssq + jn) * invD + p.eps);  // token jn
-        // hidden fragment of token jn, hidden units 32 kb + 8 g4 .. +7 (zero past the end)
-        auto hidden = [&](int kb, int kb1) -> Chunk {
-            Chunk ha;
-            if (kb < kb1) {
-                const float* pp = p.pq + (size_t)jn * p.Fp + 32 * kb + 8 * g4;
-                const float* qq = pp + (size_t)16 * p.Fp;
-                float h[8];
+        // two tasks per lane and turn, so that all their loads are in flight together
+        for (int idx0 = b * 128 + lane; idx0 < total; idx0 += G * 128) {
+            f32x4 acc[2][4];
+            float ss[2];
+            int rowv[2], f0v[2];
+            bool live[2];
 #pragma unroll
-                for (int s = 0; s < 8; ++s)
-                    h[s] = swiglu(rinv * coherent_load_f32(pp + s), rinv * coherent_load_f32(qq + s));
+            for (int k = 0; k < 2; ++k) {
+                const int idx = idx0 + 64 * k;
+                live[k] = idx < total;
+                const int row = live[k] ? idx / groups_per_row : 0, f0 = live[k] ? 8 * (idx % groups_per_row) : 0;
+                rowv[k] = row;
+                f0v[k] = f0;
+                const int fb = f0 >> 7, cc = f0 & 127;
+                const int first = (fb * p.nkb1) / p.per1;
+                const int ns = live[k] ? min(G - 1, ((fb + 1) * p.nkb1 - 1) / p.per1) - first + 1 : 0;
+                const int nsq = live[k] ? slots0 : 0;
+                const float* src0 = p.ppart + (size_t)fb * p.S1 * RS + row * 128 + cc;
+                const f32x4 z = {0, 0, 0, 0};
+                acc[k][0] = z; acc[k][1] = z; acc[k][2] = z; acc[k][3] = z;
+                ss[k] = 0.f;
+                for (int s0 = 0; s0 < max(ns, nsq); s0 += 4) {   // four slots' loads in flight together
+                    f32x4 v[4][4];
+                    float sq[4];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) ha.u[q] = pack_bf16(h[2 * q], h[2 * q + 1]);
-            } else {
-                ha.u = zero4();
+                    for (int u = 0; u < 4; ++u) {
+                        const float* src = src0 + (size_t)(s0 + u) * RS;
+                        const bool ok = s0 + u < ns;
+                        v[u][0] = ok ? cload16f(src) : z;
+                        v[u][1] = ok ? cload16f(src + 4) : z;
+                        v[u][2] = ok ? cload16f(src + 2048) : z;
+                        v[u][3] = ok ? cload16f(src + 2048 + 4) : z;
+                        sq[u] = (s0 + u < nsq) ? cload4f(p.spart + (s0 + u) * 16 + row) : 0.f;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        acc[k][0] += v[u][0]; acc[k][1] += v[u][1]; acc[k][2] += v[u][2]; acc[k][3] += v[u][3];
+                        ss[k] += sq[u];
+                    }
+                }
             }
-            return ha;
-        };
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                if (!live[k]) continue;
+                const float rinv = (rowv[k] < p.M) ? rsqrtf(ss[k] * invD + p.eps) : 0.f;   // rows past M stay exactly zero
+                const f32x4 P0 = acc[k][0], P1 = acc[k][1], Q0 = acc[k][2], Q1 = acc[k][3];
+                u32x4 h;
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    h[q] = pack_bf16(swiglu(rinv * P0[2 * q], rinv * Q0[2 * q]),
+                                     swiglu(rinv * P0[2 * q + 1], rinv * Q0[2 * q + 1]));
+                    h[q + 2] = pack_bf16(swiglu(rinv * P1[2 * q], rinv * Q1[2 * q]),
+                                         swiglu(rinv * P1[2 * q + 1], rinv * Q1[2 * q + 1]));
+                }
+                u16* hd = p.H + (size_t)rowv[k] * p.Fp + f0v[k];
+                cstore8(hd, h[0], h[1]);
+                cstore8(hd + 4, h[2], h[3]);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0);                    // this wavefront's hidden stores are complete
+        BB_STREAM_TRACE(8);
+        if (lane == 0) {
+            bar_signal(p.bar, p.bar_base + 2u);
+            bar_poll(p.bar, p.bar_base + 2u);
+        }
+    }
+    __syncthreads();
+    if (w == 0) prefetch2();
+    const bool had_prefetch = i2 < iend2;
+    bool preloaded = had_prefetch;
+    BB_STREAM_TRACE(5);
+
+    // =====================  phase 2: partial outputs  =====================
+    {
         int i = i2;
-        const int iend = iend2;
-        while (i < iend) {                         // one segment = one output column block
+        while (i < iend2) {                        // one segment = one block of 128 output columns
             const int nb = i / p.nkb2, kb0 = i % p.nkb2;
-            const int kb1 = min(p.nkb2, kb0 + (iend - i));
+            const int kb1 = min(p.nkb2, kb0 + (iend2 - i));
+            const int slot = b - (nb * p.nkb2) / p.per2;
             f32x4 acc[8];
 #pragma unroll
             for (int c = 0; c < 8; ++c) acc[c] = f32x4{0, 0, 0, 0};
-            int kb = kb0 + w;
-            if (!preloaded) issue2(nb, kb, kb1);
+            // hidden fragments: row jn, hidden units 32 kb + 8 g4 .. +7
+            auto hfrag = [&](int kb) -> u32x4 {
+                if (kb >= kb1) return zero4();
+                const u16* hsrc = p.H + (size_t)jn * p.Fp + 32 * kb + 8 * g4;
+                const u32x2 lo = cload8(hsrc), hi = cload8(hsrc + 4);
+                const u32x4 r = {lo[0], lo[1], hi[0], hi[1]};
+                return r;
+            };
+            u32x4 hp[STREAM_NP2];
+#pragma unroll
+            for (int u = 0; u < STREAM_NP2; ++u) {
+                if (!preloaded) issue2(nb, kb0 + w + 4 * u, kb1, pre[u]);
+                hp[u] = hfrag(kb0 + w + 4 * u);
+            }
             preloaded = false;
-            while (kb < kb1) {                     // two items (kb, kb + 4) per turn
-                const Chunk hA = hidden(kb, kb1), hB = hidden(kb + 4, kb1);
-                u32x4 tA[8], tB[8];
-                transpose8x8(rA, tA);
-                transpose8x8(rB, tB);
-                kb += 8;
-                if (kb < kb1) issue2(nb, kb, kb1);
+            for (int kbb = kb0 + w; kbb < kb1; kbb += 4 * STREAM_NP2) {
 #pragma unroll
-                for (int c = 0; c < 8; ++c) {
-                    Chunk bA, bB;
-                    bA.u = tA[c];
-                    bB.u = tB[c];
-                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hA.v, bA.v, acc[c], 0, 0, 0);
-                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hB.v, bB.v, acc[c], 0, 0, 0);
-                }
-            }
+                for (int u = 0; u < STREAM_NP2; ++u) {
+                    const int kb = kbb + 4 * u;
+                    if (kb < kb1) {
+                        Chunk ha;
+                        ha.u = hp[u];
+                        u32x4 tt[8];
+                        transpose8x8(pre[u], tt);
+                        issue2(nb, kb + 4 * STREAM_NP2, kb1, pre[u]);
+                        hp[u] = hfrag(kb + 4 * STREAM_NP2);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const f32x4 y0 = {acc[0][e], acc[1][e], acc[2][e], acc[3][e]};
-                const f32x4 y1 = {acc[4][e], acc[5][e], acc[6][e], acc[7][e]};
-                float* rp = &sm.red[w][0][4 * g4 + e][8 * jn];
-                *reinterpret_cast<f32x4*>(rp) = y0;
-                *reinterpret_cast<f32x4*>(rp + 4) = y1;
-            }
-            __syncthreads();
-#pragma unroll 4
-            for (int j = 0; j < 8; ++j) {
-                const int idx = t + STREAM_THREADS * j;       // [token][col]
-                const int cc = idx & 127, tok = idx >> 7;
-                const float v = sm.red[0][0][tok][cc] + sm.red[1][0][tok][cc] +
-                                sm.red[2][0][tok][cc] + sm.red[3][0][tok][cc];
-                if (tok < p.M && 128 * nb + cc < p.D && v != 0.f)
-                    atomic_add_f32(p.yacc + (size_t)tok * p.D + 128 * nb + cc, v);
-            }
-            // ---- arrival count; the last workgroup of this column block
-            // converts it to bf16 and returns accumulator and counter to zero
-            __threadfence();
-            __syncthreads();
-            if (t == 0) {
-                const unsigned n = (unsigned)(kb1 - kb0);
-                const unsigned old = __hip_atomic_fetch_add(p.cnt + nb, n, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-                sm.flag = (old + n == (unsigned)p.nkb2) ? 1u : 0u;
-            }
-            __syncthreads();
-            if (sm.flag) {
-                __threadfence();
-#pragma unroll 2
-                for (int j = 0; j < 4; ++j) {
-                    const int idx = t + STREAM_THREADS * j;   // [token][column pair]
-                    const int cp = idx & 63, tok = idx >> 6;
-                    const int c0 = 128 * nb + 2 * cp;
-                    if (tok < p.M && c0 < p.D) {
-                        float* a = p.yacc + (size_t)tok * p.D + c0;
-                        const float v0 = coherent_load_f32(a), v1 = coherent_load_f32(a + 1);
-                        *reinterpret_cast<u32*>(p.Y + (size_t)tok * p.D + c0) = pack_bf16(v0, v1);
-                        __hip_atomic_store(a, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        __hip_atomic_store(a + 1, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        for (int c = 0; c < 8; ++c) {
+                            Chunk bw;
+                            bw.u = tt[c];
+                            acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ha.v, bw.v, acc[c], 0, 0, 0);
+                        }
                     }
                 }
-                if (t == 0) __hip_atomic_store(p.cnt + nb, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            stash_tile(sm.red[w][0], acc, lane);
+            __syncthreads();
+            float* dst = p.ypart + (size_t)(nb * p.S2 + slot) * 2048;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int i4 = t + STREAM_THREADS * j;        // float4 index in [16][128]
+                cstore16f(dst + 4 * i4, sum4(&sm.red[0][0][0][0], RS, i4));
             }
             __syncthreads();
             i += kb1 - kb0;
         }
     }
+
+    BB_STREAM_TRACE(6);
+    grid_arrive(p.bar, p.bar_base + 3u);
+    if (t == 0) bar_poll(p.bar, p.bar_base + 3u);
+    __syncthreads();
+    BB_STREAM_TRACE(9);
+
+    // =====================  phase 2b: output  =====================
+    {
+        const int groups_per_row = p.D / 8;                    // tasks: (row, 8 consecutive columns)
+        const int total = p.M * groups_per_row;
+        for (int idx = b * STREAM_THREADS + t; idx < total; idx += G * STREAM_THREADS) {
+            const int row = idx / groups_per_row, c0 = 8 * (idx % groups_per_row);
+            const int nb = c0 >> 7, cc = c0 & 127;
+            const int first = (nb * p.nkb2) / p.per2;
+            const int ns = min(G - 1, ((nb + 1) * p.nkb2 - 1) / p.per2) - first + 1;
+            const float* src0 = p.ypart + (size_t)nb * p.S2 * 2048 + row * 128 + cc;
+            f32x4 y0 = {0, 0, 0, 0}, y1 = y0;
+            for (int s0 = 0; s0 < ns; s0 += 8) {                 // eight slots' loads in flight together
+                f32x4 v[8][2];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const float* src = src0 + (size_t)(s0 + u) * 2048;
+                    const bool ok = s0 + u < ns;
+                    const f32x4 z = {0, 0, 0, 0};
+                    v[u][0] = ok ? cload16f(src) : z;
+                    v[u][1] = ok ? cload16f(src + 4) : z;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) { y0 += v[u][0]; y1 += v[u][1]; }
+            }
+            const u32x4 o = {pack_bf16(y0[0], y0[1]), pack_bf16(y0[2], y0[3]), pack_bf16(y1[0], y1[1]),
+                             pack_bf16(y1[2], y1[3])};
+            *reinterpret_cast<u32x4*>(p.Y + (size_t)row * p.D + c0) = o;
+        }
+    }
+    BB_STREAM_TRACE(7);
 }
 
 }  // namespace bb
