@@ -258,8 +258,14 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
     if (log_on())
         std::fprintf(stderr, "[bb] gemm mode %d BM %d M %d N %d K %d tiles %dx%d\n", MODE, BM, M, N, K,
                      a.tiles_m, a.tiles_n);
-    if (big) hipLaunchKernelGGL((gemm_kernel<MODE, 256>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((gemm_kernel<MODE, 128>), grid, block, 0, st, a);
+    const bool full = (M % BM == 0) && (N % ncol == 0) && (K % GEMM_BK == 0);
+    if (big) {
+        if (full) hipLaunchKernelGGL((gemm_kernel<MODE, 256, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((gemm_kernel<MODE, 256, false>), grid, block, 0, st, a);
+    } else {
+        if (full) hipLaunchKernelGGL((gemm_kernel<MODE, 128, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((gemm_kernel<MODE, 128, false>), grid, block, 0, st, a);
+    }
     BB_HIP(hipGetLastError());
     prof_mark(MODE == MODE_GATEUP ? "gemm_gateup" : MODE == MODE_LN ? "gemm_ln" : "gemm_plain", st);
     return BB_OK;

@@ -52,10 +52,12 @@ __device__ __forceinline__ void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[
 }
 
 // LDS tiles are arrays of 16-byte chunks, 8 chunks (64 contraction indices)
-// per row.  The chunk index is XOR-swizzled with row bits 1..3 so that 16
-// consecutive rows at one chunk index, or 2 rows x 8 chunks, fall on 16
-// different 16-byte bank groups.
-__device__ __forceinline__ int lds_pos(int row, int kc) { return row * 8 + (kc ^ ((row >> 1) & 7)); }
+// per row.  LDS has 32 four-byte banks and serves a 128-bit access of a
+// wavefront eight lanes at a time, so eight consecutive lanes must hit eight
+// different 16-byte bank groups.  The chunk index is XOR-swizzled with the low
+// three row bits: 8 consecutive rows at one chunk index, or one row's 8
+// chunks, then fall on 8 different groups.
+__device__ __forceinline__ int lds_pos(int row, int kc) { return row * 8 + (kc ^ (row & 7)); }
 
 __device__ __forceinline__ u32x4 zero4() { u32x4 z = {0u, 0u, 0u, 0u}; return z; }
 
