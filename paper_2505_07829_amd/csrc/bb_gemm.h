@@ -217,10 +217,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     // (they issue in order, so only instructions placed between two matrix
     // instructions run in the shadow of the first), and fetch the fragments of
     // the next group while the current one is multiplied.
-    Chunk fa[1][MT], fb[1][4];
+    Chunk fa[2][MT], fb[2][4];
     auto frag_load = [&](int buf, int ks, auto SETC) {
-        constexpr int S = 0;
-        (void)SETC;
+        constexpr int S = decltype(SETC)::value;
         const int kc = 2 * ks + lhi;
 #pragma unroll
         for (int s = 0; s < MT; ++s) fa[S][s].u = sm.a[buf][lds_pos(wm * (BM / 2) + 32 * s + l32, kc)];
@@ -228,8 +227,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
         for (int tt = 0; tt < 4; ++tt) fb[S][tt].u = sm.b[buf][lds_pos(wn * 128 + 32 * tt + l32, kc)];
     };
     auto mma = [&](auto SETC) {
-        constexpr int S = 0;
-        (void)SETC;
+        constexpr int S = decltype(SETC)::value;
 #pragma unroll
         for (int s = 0; s < MT; ++s)
 #pragma unroll
@@ -257,25 +255,25 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
         gload_b(kl, C1());
         frag_load(buf, 0, C0());
         __builtin_amdgcn_sched_barrier(0);
+        frag_load(buf, 1, C1());
         mma(C0());
         sstore_part(nbuf, C0(), C0());
         gload_part(kl, C0());
-        interleave(false);
-        frag_load(buf, 1, C0());
+        interleave(true);
         __builtin_amdgcn_sched_barrier(0);
-        mma(C0());
+        frag_load(buf, 2, C0());
+        mma(C1());
         sstore_part(nbuf, C0(), C1());
         gload_part(kl, C1());
-        interleave(false);
-        frag_load(buf, 2, C0());
+        interleave(true);
         __builtin_amdgcn_sched_barrier(0);
+        frag_load(buf, 3, C1());
         mma(C0());
         sstore_part(nbuf, C0(), C2());
         gload_part(kl, C2());
-        interleave(false);
-        frag_load(buf, 3, C0());
+        interleave(true);
         __builtin_amdgcn_sched_barrier(0);
-        mma(C0());
+        mma(C1());
         sstore_part(nbuf, C0(), C3());
         gload_part(kl, C3());
         interleave(false);
