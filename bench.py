@@ -28,6 +28,15 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this same script (profiles/hbm_traffic_c2_c3.txt; FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 as
+# calibrated against bb_calib_copy).  Counters cannot be read from inside a timed run, so the
+# figures are carried here; workloads without a counter run report null.
+MEASURED_TRAFFIC_BYTES = {
+    ("c2", "ffn_stream"): 281.2e6 + 16.2e6,
+    ("c3", "gemm_gateup"): 621.4e6 + 45.1e6,
+}
+
 
 def flops_of(cfg):
     return (6.0 if cfg.op == "ffn" else 2.0) * cfg.M * cfg.D * cfg.F
@@ -117,7 +126,8 @@ def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
         "kernels_ms": kernels_ms,
         "unfused_ms_per_step": ms_unfused,
         "roofline": {"kernel": dom, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                     "frac": achieved / peak, "traffic": None},
+                     "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((name, dom)),
+                     "algorithmic": work},
     }
 
     if with_cpu:
@@ -175,9 +185,12 @@ def calibrate(torch, bb):
         e1.record(); torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
     ms_r = t(lambda: bb.bb_calib_read(buf, sink), 10)
+    half = buf.numel() // 2          # plain copy of known size: the reference for HBM byte counters
+    ms_c = t(lambda: bb.bb_calib_copy(buf[:half], buf[half:]), 5)
     iters, wgs = 4000, 1024
     ms_m = t(lambda: bb.bb_calib_mfma(wgs, iters, sink), 3)
     return {"read_gbs": buf.numel() / (ms_r * 1e-3) / 1e9,
+            "copy_gbs_read_plus_write": 2 * half / (ms_c * 1e-3) / 1e9,
             "mfma_bf16_tflops": wgs * 4 * iters * 16 * 32768.0 / (ms_m * 1e-3) / 1e12}
 
 

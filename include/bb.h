@@ -56,12 +56,13 @@ typedef enum bb_status {
  *                      writes the hidden once as bf16 to the workspace; a
  *                      second GEMM contracts it with W2.  Two launches.
  * BB_VARIANT_STREAM    bandwidth-bound form for M <= 16 rows.  One persistent
- *                      cooperative kernel streams W1, W3 and then W2 exactly
- *                      once; both reductions (over the model dimension and
- *                      over the hidden dimension) run in parallel over all
- *                      workgroups with fp32 atomic accumulation (Rule 3's
- *                      atomic form; Example 3's epilogue proposes it for the
- *                      K-map).  The pre-activations (2 x 16 x F floats) pass
+ *                      kernel (one workgroup per compute unit, all resident)
+ *                      streams W1, W3 and then W2 exactly once; both
+ *                      reductions (over the model dimension and over the
+ *                      hidden dimension) run in parallel over all workgroups
+ *                      (Rule 3; Example 3's epilogue proposes it for the
+ *                      K-map) through per-workgroup partial-sum slots that a
+ *                      short phase adds up.  The hidden block (16 x F) passes
  *                      through a cache-resident scratch between the phases.
  * BB_VARIANT_AUTO      STREAM for M <= 16, SNAPSHOT1 otherwise.
  */
