@@ -259,13 +259,17 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
         std::fprintf(stderr, "[bb] gemm mode %d BM %d M %d N %d K %d tiles %dx%d\n", MODE, BM, M, N, K,
                      a.tiles_m, a.tiles_n);
     const bool full = (M % BM == 0) && (N % ncol == 0) && (K % GEMM_BK == 0);
+    const bool odd = (((K + GEMM_BK - 1) / GEMM_BK) & 1) != 0;
+#define BB_GEMM_LAUNCH(BM_, FULL_, ODD_) \
+    hipLaunchKernelGGL((gemm_kernel<MODE, BM_, FULL_, ODD_>), grid, block, 0, st, a)
     if (big) {
-        if (full) hipLaunchKernelGGL((gemm_kernel<MODE, 256, true>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((gemm_kernel<MODE, 256, false>), grid, block, 0, st, a);
+        if (full) { if (odd) BB_GEMM_LAUNCH(256, true, true); else BB_GEMM_LAUNCH(256, true, false); }
+        else      { if (odd) BB_GEMM_LAUNCH(256, false, true); else BB_GEMM_LAUNCH(256, false, false); }
     } else {
-        if (full) hipLaunchKernelGGL((gemm_kernel<MODE, 128, true>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((gemm_kernel<MODE, 128, false>), grid, block, 0, st, a);
+        if (full) { if (odd) BB_GEMM_LAUNCH(128, true, true); else BB_GEMM_LAUNCH(128, true, false); }
+        else      { if (odd) BB_GEMM_LAUNCH(128, false, true); else BB_GEMM_LAUNCH(128, false, false); }
     }
+#undef BB_GEMM_LAUNCH
     BB_HIP(hipGetLastError());
     prof_mark(MODE == MODE_GATEUP ? "gemm_gateup" : MODE == MODE_LN ? "gemm_ln" : "gemm_plain", st);
     return BB_OK;
