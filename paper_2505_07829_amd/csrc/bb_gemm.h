@@ -18,43 +18,43 @@
 // C [M,N] row-major, all bf16.  fp32 accumulation in 32x32x16 matrix
 // instructions.
 //
-// Tiling: 256 threads = 4 wavefronts (2x2), workgroup tile BM x 256 columns
-// (GATEUP: 128 hidden units = 128 columns of W1 + the same 128 of W3),
-// contraction step 64, LDS double buffered with one barrier per step.
+// Tiling: 256 threads = 4 wavefronts, workgroup tile BM x 256 columns (GATEUP:
+// 128 hidden units = 128 columns of W1 + the same 128 of W3), contraction step
+// 64, LDS double buffered with one barrier per step.  PLAIN arranges the
+// wavefronts 2x2 (least LDS read traffic); GATEUP and LN arrange them 4x1, so
+// that every wavefront owns its rows of A alone (see "A operand").
 //
-// B operand.  The weight tile (64 contraction rows x 512 bytes) goes from
-// global memory straight into LDS (load-to-LDS instructions, no registers, no
-// vector ALU work), row-major as it lies in memory.  The matrix instruction
-// wants, per lane, 8 consecutive contraction indices of one column; the
-// transposing LDS read (ds_read_b64_tr_b16) delivers exactly that from a
-// row-major tile, 4 contraction rows x 16 columns per group of 16 lanes.  Its
-// 16 lanes read 4 rows x 32 bytes; the 16-byte chunks of a row are XOR-swizzled
-// with the low two row bits (in units of 32 bytes) so that these four rows fall
-// on different banks.
+// Both operand tiles go from global memory straight into LDS with load-to-LDS
+// instructions: no staging registers, no vector ALU work, no LDS writes.
 //
-// A operand.  The activation tile goes global -> registers -> LDS because the
-// prologue works on it: the row sums are accumulated and the gain is applied
-// (rounded to bf16) on the way.  While step k is multiplied, tile k+1 moves
-// from the registers into the idle LDS buffer in four parts, one after each
-// group of matrix instructions, and each part's registers are at once refilled
-// with tile k+2, so the prologue's vector ALU work and the load latency run in
-// the shadow of the matrix cores.
+// B operand.  The weight tile (64 contraction rows x 512 bytes) lies in LDS
+// row-major as in memory.  The matrix instruction wants, per lane, 8
+// consecutive contraction indices of one column; the transposing LDS read
+// (ds_read_b64_tr_b16) delivers exactly that from a row-major tile, 4
+// contraction rows x 16 columns per group of 16 lanes.  Its 16 lanes read 4
+// rows x 32 bytes; the 16-byte chunks of a row are XOR-swizzled with the low
+// two row bits (in units of 32 bytes) so that these rows fall on different
+// banks.
 //
-// Waiting.  The load-to-LDS instructions are issued from inline assembly: the
-// compiler's wait-count pass answers a pending load-to-LDS with "wait for
-// every outstanding load" at each later use of a loaded register, which would
-// serialise the pipeline.  Unknown to the compiler, they are ordered by hand:
-// per step, (1) every register the step consumes is touched first, which makes
-// the compiler wait for the A loads of the previous step there; (2) then the
-// load-to-LDS instructions of the next B tile are issued, then the A loads of
-// the tile after it; (3) the step ends with an explicit wait for all of them
-// (a count that spares the A loads would be wrong when a wavefront skips
-// out-of-range A rows, and would rely on load-to-LDS and register loads
-// retiring in issue order).  The compiler's own counts never force the
-// completion of a load-to-LDS early, because none is in flight at (1).
-// The main loop is unrolled by two so that LDS buffers and register sets are
-// named statically; the parity of the step count is a template parameter so
-// that no branch with live accumulators on both sides is needed.
+// A operand.  The activation tile lies in LDS as rows of 8 chunks (16 bytes = 8
+// contraction indices), chunk index XOR-swizzled with the low row bits; one
+// 128-bit LDS read is one matrix-instruction operand.  The norm prologue works
+// on these operand registers: a fragment is read one group of matrix
+// instructions ahead, its squares (LN: and its values) are added to the
+// lane's row sums, and it is scaled by the gain (read from a small LDS copy of
+// the gain tile) and rounded to bf16 before it enters the matrix instruction.
+// With 4x1 wavefronts no fragment is read by two wavefronts, so this costs
+// each element one pass through the vector ALU, in the shadow of the matrix
+// instructions.
+//
+// Waiting.  Nothing in the main loop loads into registers from global memory,
+// so the only vector-memory waits are the explicit one at the end of a step
+// (all load-to-LDS of the next tiles have landed) followed by the barrier.
+// Every LDS buffer is its own __shared__ array and the main loop is unrolled
+// by two: the compiler tracks outstanding load-to-LDS per array and would
+// otherwise make the LDS reads of one buffer wait for the transfer into the
+// other.  The parity of the step count is a template parameter so that no
+// branch with live accumulators on both sides is needed.
 #pragma once
 #include <type_traits>
 
@@ -94,12 +94,13 @@ typedef void __attribute__((address_space(3))) * lptr_t;
 constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 
 // One load-to-LDS instruction: lane i of the wavefront copies the 16 bytes at
-// its own global address src to LDS byte address lds_base + 16 i (lds_base is
-// the same for all lanes and travels in M0).
-__device__ __forceinline__ void load_to_lds16(const void* src, u32 lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :: "s"(lds_base), "v"(src) : "memory");
+// its own global address src to LDS address dst + 16 i (dst is the same for
+// all lanes).
+__device__ __forceinline__ void load_to_lds16(const void* src, void* dst) {
+    __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 16, 0, 0);
 }
+
+// LDS byte address of a pointer into a __shared__ array
 __device__ __forceinline__ u32 lds_addr(const void* q) {
     return (u32)(size_t)((__attribute__((address_space(3))) const char*)q);
 }
@@ -123,11 +124,17 @@ __device__ __forceinline__ void quad_transpose(u32& d0, u32& d1, bool upper, u32
 // ODD: the number of contraction steps ceil(K / 64) is odd.
 template <int MODE, int BM, bool FULL, bool ODD>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
-    constexpr int AI = BM / 32;   // A chunks per thread per step
-    constexpr int MT = BM / 64;   // 32-row subtiles per wavefront
+    constexpr int WM = (MODE == MODE_PLAIN) ? 2 : 4;   // wavefronts along the rows
+    constexpr int WN = 4 / WM;                          // and along the columns
+    constexpr int WR = BM / WM, WC = 256 / WN;          // wavefront tile
+    constexpr int MT = WR / 32, NT = WC / 32;           // 32x32 subtiles per wavefront
     constexpr int NCOL = (MODE == MODE_GATEUP) ? 128 : 256;  // output columns per tile
-    __shared__ u32x4 sA0[BM * 8], sA1[BM * 8];       // [row][8 chunks], lds_pos swizzle
+    constexpr int ADMA = BM / 32;   // A load-to-LDS instructions per wavefront and step
+    // (the B arrays come first: the many transposing reads of a step then reach
+    // their addresses with the 16-bit displacement of the LDS instructions)
     __shared__ u32x4 sB0[64 * 32], sB1[64 * 32];     // [contraction row][32 chunks], swizzled
+    __shared__ u32x4 xA0[BM * 8], xA1[BM * 8];       // [row][8 chunks], lds_pos swizzle
+    __shared__ u32x4 sG0[64], sG1[64];               // gain tile: chunks 0..7 (stored 8 times)
     __shared__ float stat0[BM];                      // inverse norm / inverse std
     __shared__ float stat1[BM];                      // mean (LN)
 
@@ -141,40 +148,42 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     const int m0 = tm * BM, n0 = tn * NCOL;
 
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
-    const int wm = w >> 1, wn = w & 1;
+    const int wm = w / WN, wn = w % WN;
     const int l32 = lane & 31, lhi = lane >> 5;
+    const u16* const zsrc = reinterpret_cast<const u16*>(&gemm_zero_chunk);
 
-    // ---- A: global-load role: chunk kcA of rows rowA + 32 i
-    const int kcA = t & 7, rowA = t >> 3;
+    // ---- A: load-to-LDS role.  One instruction fills 64 chunks = 8 tile rows,
+    // lane i -> chunk position i % 8 of row i / 8, which holds source chunk
+    // (i % 8) ^ (row % 8).  Wavefront w issues row groups w ADMA .. w ADMA + ADMA-1.
+    const int rowA = 8 * ADMA * w + (lane >> 3);                 // + 8 j for instruction j
+    const int kcA = (lane & 7) ^ ((lane >> 3) & 7);
+    const u16* const Alane = p.A + (size_t)(m0 + rowA) * p.lda + 8 * kcA;
 
-    // ---- B: load-to-LDS role.  One instruction of a wavefront fills 1 KiB =
-    // two tile rows, lane i -> byte 16 i.  Wavefront w issues row pairs w, w+4,
-    // ..., w+28; this lane therefore always serves tile rows = 2 w + lhi (mod 8)
-    // and LDS chunk position l32, which holds source chunk l32 ^ 2 (row & 3).
-    // Source chunk c of a tile row is columns n0 + 8 c (PLAIN, LN); in GATEUP
-    // it is laid out so that each wavefront's four 32-column subtiles are
-    // W1[h..h+32), W1[h+32..h+64), W3[h..h+32), W3[h+32..h+64) of the same 64
-    // hidden units: a lane's accumulators then hold the gate and the up
-    // product of the same hidden unit.
+    // ---- B: load-to-LDS role.  One instruction fills 1 KiB = two tile rows,
+    // lane i -> byte 16 i.  Wavefront w issues row pairs w, w+4, ..., w+28; this
+    // lane therefore always serves tile rows = 2 w + lhi (mod 8) and chunk
+    // position l32, which holds source chunk l32 ^ 2 (row & 3).  Source chunk c
+    // of a tile row is columns n0 + 8 c; in GATEUP chunks 0..15 are W1's 128
+    // columns and chunks 16..31 are W3's, so that subtiles tt and tt + 4 of the
+    // (single-column) wavefront tile are the gate and the up product of the
+    // same hidden units.
     const int rowB = 2 * w + lhi;
     const int chunkB = l32 ^ ((rowB & 3) << 1);
     const u16* Bsrc = p.B0;
     int colB;
     if (MODE == MODE_GATEUP) {
-        const int ttc = (chunkB >> 2) & 3;
-        if (ttc >> 1) Bsrc = p.B1;
-        colB = n0 + 64 * (chunkB >> 4) + 32 * (ttc & 1) + 8 * (chunkB & 3);
+        if (chunkB >> 4) Bsrc = p.B1;
+        colB = n0 + 8 * (chunkB & 15);
     } else {
         colB = n0 + 8 * chunkB;
     }
     const bool colB_ok = FULL || colB < p.N;
     const u16* const Blane = Bsrc + (size_t)rowB * p.ldb + (colB_ok ? colB : 0);
-    const u16* const zsrc = reinterpret_cast<const u16*>(&gemm_zero_chunk);
 
     // ---- B: fragment-read role.  Group b = lane / 16 of a transposing read
     // covers contraction rows 8 (b / 2) + 4 h + (0..3) (+ 16 per matrix
     // instruction) and columns 32 tt + 16 (b % 2) + (0..15) of the wavefront's
-    // 128; lane i' = lane % 16 supplies the address of row i' / 4, 4-column
+    // columns; lane i' = lane % 16 supplies the address of row i' / 4, 4-column
     // piece i' % 4.  Byte offsets for tt even / odd (the swizzle XORs bit 2 of
     // the chunk index, which is tt's low bit, so odd tt is not a plain offset).
     int offB[2];
@@ -184,202 +193,203 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
         const int piece = ip & 3;
 #pragma unroll
         for (int o = 0; o < 2; ++o) {
-            const int chunk = 16 * wn + 4 * o + 2 * (b & 1) + (piece >> 1);
+            const int chunk = (WC / 8) * wn + 4 * o + 2 * (b & 1) + (piece >> 1);
             offB[o] = r * 512 + ((chunk ^ ((r & 3) << 1)) << 4) + 8 * (piece & 1);
         }
     }
 
-    // A register sets: tile j travels in set j % 2 (with its gain chunk)
-    u32x4 ra[2][AI], rg[2] = {zero4(), zero4()};
-    float ssq[AI], ssum[AI];
+    // Quarter `part` (0..3) of the load-to-LDS instructions of B tile kt (8 per
+    // wavefront and tile) into LDS array dB
+    auto dma_b = [&](int kt, u32x4* dB, int part) {
+        const int k0 = kt * GEMM_BK;
+        const u16* srcB = Blane + (size_t)k0 * p.ldb;
 #pragma unroll
-    for (int i = 0; i < AI; ++i) { ssq[i] = 0.f; ssum[i] = 0.f; }
-    constexpr int APER = AI / 4;
-
-    // B tile kt -> LDS array dst (8 load-to-LDS instructions per wavefront)
-    auto dma_b = [&](int kt, u32x4* dst) {
-        const u16* src = Blane + (size_t)kt * GEMM_BK * p.ldb;
-        const u32 base = __builtin_amdgcn_readfirstlane(lds_addr(dst) + (u32)w * 1024u);
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const u16* g = src + (size_t)(8 * q) * p.ldb;
-            if (!FULL) {
-                const int k = kt * GEMM_BK + 8 * q + rowB;
-                g = (colB_ok && k < p.K) ? g : zsrc;
-            }
-            load_to_lds16(g, base + (u32)q * 4096u);
+        for (int qq = 0; qq < 2; ++qq) {
+            const int q = 2 * part + qq;
+            const u16* g = srcB + (size_t)(8 * q) * p.ldb;
+            if (!FULL) g = (colB_ok && k0 + 8 * q + rowB < p.K) ? g : zsrc;
+            load_to_lds16(g, dB + (w + 4 * q) * 64);
         }
     };
-    // A tile kt and its gain chunk -> register set S
-    auto gload_a = [&](int kt, auto SETC) {
-        constexpr int S = decltype(SETC)::value;
-        const int ka = kt * GEMM_BK + 8 * kcA;
-        const bool ka_ok = FULL || ka < p.K;
-        if (MODE != MODE_PLAIN) rg[S] = ka_ok ? ldg16(p.gain + ka) : zero4();
+    // Quarter `part` of A tile kt (ADMA instructions per wavefront and tile)
+    // into dA; the last quarter also brings the gain chunks into dG (every
+    // wavefront writes the same bytes there: no branch in the step)
+    auto dma_a = [&](int kt, u32x4* dA, u32x4* dG, int part) {
+        const int k0 = kt * GEMM_BK;
+        const u16* srcA = Alane + k0;
+        const bool ka_ok = FULL || k0 + 8 * kcA < p.K;
 #pragma unroll
-        for (int i = 0; i < AI; ++i) {
-            const int m = m0 + rowA + 32 * i;
-            ra[S][i] = (FULL || (ka_ok && m < p.M)) ? ldg16(p.A + (size_t)m * p.lda + ka) : zero4();
+        for (int jj = 0; jj < ADMA / 4; ++jj) {
+            const int j = (ADMA / 4) * part + jj;
+            const u16* g = srcA + (size_t)(8 * j) * p.lda;
+            if (!FULL) g = (ka_ok && m0 + rowA + 8 * j < p.M) ? g : zsrc;
+            load_to_lds16(g, dA + (ADMA * w + j) * 64);
         }
-    };
-    // makes the compiler wait here for everything register set S was loaded with
-    auto touch = [&](auto SETC) {
-        constexpr int S = decltype(SETC)::value;
-#pragma unroll
-        for (int i = 0; i < AI; ++i) asm volatile("" : "+v"(ra[S][i]));
-        u32x4& gref = rg[S];
-        if (MODE != MODE_PLAIN) asm volatile("" : "+v"(gref));
-    };
-    // part `part` (0..3) of writing register set S into LDS array dst: AI/4
-    // chunks, scaled by the gain chunk, rounded, row sums updated
-    auto sstore_part = [&](u32x4* dst, auto SETC, auto PARTC) {
-        constexpr int S = decltype(SETC)::value;
-        constexpr int part = decltype(PARTC)::value;
-        const u32x4 gv = rg[S];
-#pragma unroll
-        for (int ii = 0; ii < APER; ++ii) {
-            const int i = part * APER + ii;
-            u32x4 v = ra[S][i];
-            if (MODE != MODE_PLAIN) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const u32 xw = v[q];
-                    const bf16x2 xb = *reinterpret_cast<const bf16x2*>(&xw);
-                    ssq[i] = __builtin_amdgcn_fdot2_f32_bf16(xb, xb, ssq[i], false);
-                    if (MODE == MODE_LN) {
-                        const u32 onew = 0x3f803f80u;
-                        ssum[i] = __builtin_amdgcn_fdot2_f32_bf16(xb, *reinterpret_cast<const bf16x2*>(&onew), ssum[i], false);
-                    }
-                    v[q] = pack_bf16(bf_lo(xw) * bf_lo(gv[q]), bf_hi(xw) * bf_hi(gv[q]));
-                }
-            }
-            dst[lds_pos(rowA + 32 * i, kcA)] = v;
+        if (MODE != MODE_PLAIN && part == 3) {
+            const int kg = k0 + 8 * (lane & 7);
+            const u16* g = p.gain + kg;
+            if (!FULL) g = (kg < p.K) ? g : zsrc;
+            load_to_lds16(g, dG);
         }
     };
 
-    f32x16 acc[MT][4];
+    f32x16 acc[MT][NT];
 #pragma unroll
     for (int s = 0; s < MT; ++s)
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt)
+        for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[s][tt][v] = 0.f;
+    // row sums of the fragments this lane has seen: row 32 s + l32 of the
+    // wavefront's rows, contraction chunks with (chunk % 2) == lhi
+    float ssq[MT], ssum[MT];
+#pragma unroll
+    for (int s = 0; s < MT; ++s) { ssq[s] = 0.f; ssum[s] = 0.f; }
 
     using C0 = std::integral_constant<int, 0>;
     using C1 = std::integral_constant<int, 1>;
-    using C2 = std::integral_constant<int, 2>;
-    using C3 = std::integral_constant<int, 3>;
 
     const int nk = (p.K + GEMM_BK - 1) / GEMM_BK;
 
-    // fragments of contraction slice ks (16 indices) of one LDS buffer pair
-    Chunk fa[2][MT], fb[2][4];
-    auto frag_load = [&](const u32x4* bufA, const u32x4* bufB, int ks, auto SETC) {
+    // fragments of contraction slice ks (16 indices) of one LDS buffer set
+    Chunk fa[2][MT], fb[2][NT], fg[2];
+    auto frag_load = [&](const u32x4* bufA, auto PBC, const u32x4* bufG, int ks, auto SETC) {
         constexpr int S = decltype(SETC)::value;
+        constexpr int PB = decltype(PBC)::value;      // which B array
         const int kc = 2 * ks + lhi;
 #pragma unroll
-        for (int s = 0; s < MT; ++s) fa[S][s].u = bufA[lds_pos(wm * (BM / 2) + 32 * s + l32, kc)];
-        const char* bb = reinterpret_cast<const char*>(bufB) + ks * (16 * 512);
+        for (int s = 0; s < MT; ++s) fa[S][s].u = bufA[lds_pos(WR * wm + 32 * s + l32, kc)];
+        if (MODE != MODE_PLAIN) fg[S].u = bufG[kc];
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) {
-            const char* q = bb + offB[tt & 1] + 128 * (tt >> 1);
+        for (int tt = 0; tt < NT; ++tt) {
+            const char* q = reinterpret_cast<const char*>(PB ? sB1 : sB0) + offB[tt & 1] + ks * (16 * 512) + 128 * (tt >> 1);
             const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(q));
             const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(q + 4 * 512));
             u32x2 l2 = *reinterpret_cast<const u32x2*>(&lo), h2 = *reinterpret_cast<const u32x2*>(&hi);
             fb[S][tt].u = u32x4{l2[0], l2[1], h2[0], h2[1]};
         }
     };
-    auto mma = [&](auto SETC) {
+    // norm prologue on the A fragments of set S: row sums, gain, rounding.
+    // The MT x 4 (subtile, dword) items are numbered s * 4 + q; one call works
+    // on items [lo, hi).
+    auto cook = [&](auto SETC, int lo, int hi) {
+        constexpr int S = decltype(SETC)::value;
+        if (MODE == MODE_PLAIN) return;
+        const u32x4 gv = fg[S].u;
+#pragma unroll
+        for (int s = 0; s < MT; ++s) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int item = 4 * s + q;
+                if (item < lo || item >= hi) continue;
+                const u32 xw = fa[S][s].u[q];
+                const bf16x2 xb = *reinterpret_cast<const bf16x2*>(&xw);
+                ssq[s] = __builtin_amdgcn_fdot2_f32_bf16(xb, xb, ssq[s], false);
+                if (MODE == MODE_LN) {
+                    const u32 onew = 0x3f803f80u;
+                    ssum[s] = __builtin_amdgcn_fdot2_f32_bf16(xb, *reinterpret_cast<const bf16x2*>(&onew), ssum[s], false);
+                }
+                fa[S][s].u[q] = pack_bf16(bf_lo(xw) * bf_lo(gv[q]), bf_hi(xw) * bf_hi(gv[q]));
+            }
+        }
+    };
+    constexpr int NMMA = MT * NT;          // matrix instructions per group (one contraction slice)
+    constexpr int QMMA = NMMA / 4;         // per quarter of a group
+    static_assert(NT >= QMMA, "the first quarter must use subtile row 0 only");
+    // quarter `part` of the matrix instructions of fragment set S, subtile rows first
+    auto mma = [&](auto SETC, int part) {
         constexpr int S = decltype(SETC)::value;
 #pragma unroll
         for (int s = 0; s < MT; ++s)
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt)
+            for (int tt = 0; tt < NT; ++tt) {
+                const int i = s * NT + tt;
+                if (i / QMMA != part) continue;
                 acc[s][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[S][s].v, fb[S][tt].v, acc[s][tt], 0, 0, 0);
+            }
     };
-    constexpr int NMMA = 4 * MT;                                       // matrix instructions per group
-    constexpr int VALU_PER = (MODE == MODE_PLAIN ? 4 : 4 + 28 * APER) / NMMA + 1;
-    auto interleave = [&](bool with_frags) {
-        // (the compiler honours data dependences; the pattern below is a placement request)
-        if (with_frags) __builtin_amdgcn_sched_group_barrier(0x100, MT + 8, 0);      // LDS reads first
+    constexpr int NDSR = MT + 2 * NT + (MODE != MODE_PLAIN ? 1 : 0);   // LDS reads per fragment set
+    constexpr int ITEMS = 4 * MT;                                      // prologue items per fragment set
+    constexpr int P1 = (ITEMS + 2) / 3, P2 = (2 * ITEMS + 2) / 3;      // item ranges of quarters 1, 2, 3
+    // Placement request inside one quarter (the instructions issue in order,
+    // so only what stands between two matrix instructions runs in the shadow
+    // of the first): the LDS reads first, then per matrix instruction a slice
+    // of the vector ALU work, and a load-to-LDS after every second one.
+    auto pattern = [&](bool with_frags, auto VALUC, bool with_dma) {
+        constexpr int valu = decltype(VALUC)::value;
+        if (with_frags) __builtin_amdgcn_sched_group_barrier(0x100, NDSR, 0);
 #pragma unroll
-        for (int i = 0; i < NMMA; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // one matrix instruction
-            __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER, 0);                // a slice of the vector ALU work
-            if (i % 8 == 7) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);       // an LDS write
+        for (int i = 0; i < QMMA; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (valu > 0) __builtin_amdgcn_sched_group_barrier(0x002, valu, 0);
+            if (with_dma && ((i & 1) || QMMA < 4)) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
     };
+    using VQ = std::integral_constant<int, (MODE == MODE_PLAIN) ? 2 : (6 * ITEMS) / (3 * QMMA) + 4>;   // vector ALU slice per matrix instruction
+    using V2 = std::integral_constant<int, 2>;
+    using V0 = std::integral_constant<int, 0>;
 
-    // One contraction step on buffer pair PAR (tile kt, kt % 2 == PAR): multiply
-    // it; meanwhile B tile kt+1 streams into the other pair's B array, A tile
-    // kt+1 goes from register set 1-PAR into the other A array, one part per
-    // group of 16 matrix instructions, and register set PAR is refilled with
-    // tile kl (kt + 2, or the last tile when there is no such tile: a valid
-    // address whose data is never stored).  The scheduling directives spread
-    // each part's vector ALU and LDS instructions between the matrix
-    // instructions (they issue in order, so only instructions placed between
-    // two matrix instructions run in the shadow of the first), and fetch the
-    // fragments of the next group while the current one is multiplied.
-    auto step = [&](int kt, int kl, auto PARC) {
+    // One contraction step on buffer set PAR (tile kt, kt % 2 == PAR): four
+    // groups of matrix instructions (one per 16 contraction indices), each in
+    // four quarters.  The first quarter of a group issues the LDS reads of the
+    // next group's fragments, the other three run the norm prologue on them.
+    // The load-to-LDS instructions of tile kt + 1 are spread over the quarters
+    // of the first two groups (B, then A), so that the step's second half is
+    // left for them to land.
+    auto step = [&](int kt, auto PARC) {
         constexpr int PAR = decltype(PARC)::value;
-        using SN = std::integral_constant<int, 1 - PAR>;      // register set of tile kt + 1
-        using SL = std::integral_constant<int, PAR>;          // register set being refilled
-        u32x4* const curA = PAR ? sA1 : sA0;
-        u32x4* const curB = PAR ? sB1 : sB0;
-        u32x4* const nxtA = PAR ? sA0 : sA1;
+        const u32x4* const curA = PAR ? xA1 : xA0;
+        const u32x4* const curG = PAR ? sG1 : sG0;
+        u32x4* const nxtA = PAR ? xA0 : xA1;
         u32x4* const nxtB = PAR ? sB0 : sB1;
+        u32x4* const nxtG = PAR ? sG0 : sG1;
         __syncthreads();
-        touch(SN());
+        frag_load(curA, PARC, curG, 0, C0());
+        cook(C0(), 0, 4);                               // subtile row 0: all the first quarter needs
         __builtin_amdgcn_sched_barrier(0);
-        dma_b(kt + 1, nxtB);
-        gload_a(kl, SL());
-        __builtin_amdgcn_sched_barrier(0);
-        frag_load(curA, curB, 0, C0());
-        __builtin_amdgcn_sched_barrier(0);
-        frag_load(curA, curB, 1, C1());
-        mma(C0());
-        sstore_part(nxtA, SN(), C0());
-        interleave(true);
-        __builtin_amdgcn_sched_barrier(0);
-        frag_load(curA, curB, 2, C0());
-        mma(C1());
-        sstore_part(nxtA, SN(), C1());
-        interleave(true);
-        __builtin_amdgcn_sched_barrier(0);
-        frag_load(curA, curB, 3, C1());
-        mma(C0());
-        sstore_part(nxtA, SN(), C2());
-        interleave(true);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(C1());
-        sstore_part(nxtA, SN(), C3());
-        interleave(false);
+        // group 0
+        frag_load(curA, PARC, curG, 1, C1());
+        mma(C0(), 0); cook(C0(), 4, ITEMS); dma_b(kt + 1, nxtB, 0); pattern(true, VQ(), true);
+        mma(C0(), 1); cook(C1(), 0, P1);    dma_b(kt + 1, nxtB, 1); pattern(false, VQ(), true);
+        mma(C0(), 2); cook(C1(), P1, P2);   dma_b(kt + 1, nxtB, 2); pattern(false, VQ(), true);
+        mma(C0(), 3); cook(C1(), P2, ITEMS); dma_b(kt + 1, nxtB, 3); pattern(false, VQ(), true);
+        // group 1
+        frag_load(curA, PARC, curG, 2, C0());
+        mma(C1(), 0);                       dma_a(kt + 1, nxtA, nxtG, 0); pattern(true, V2(), true);
+        mma(C1(), 1); cook(C0(), 0, P1);    dma_a(kt + 1, nxtA, nxtG, 1); pattern(false, VQ(), true);
+        mma(C1(), 2); cook(C0(), P1, P2);   dma_a(kt + 1, nxtA, nxtG, 2); pattern(false, VQ(), true);
+        mma(C1(), 3); cook(C0(), P2, ITEMS); dma_a(kt + 1, nxtA, nxtG, 3); pattern(false, VQ(), true);
+        // group 2
+        frag_load(curA, PARC, curG, 3, C1());
+        mma(C0(), 0);                       pattern(true, V0(), false);
+        mma(C0(), 1); cook(C1(), 0, P1);    pattern(false, VQ(), false);
+        mma(C0(), 2); cook(C1(), P1, P2);   pattern(false, VQ(), false);
+        mma(C0(), 3); cook(C1(), P2, ITEMS); pattern(false, VQ(), false);
+        // group 3
+        mma(C1(), 0); mma(C1(), 1); mma(C1(), 2); mma(C1(), 3);
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     };
-    auto last_step = [&](auto PARC) {          // nothing left to store or load
+    auto last_step = [&](auto PARC) {          // nothing left to load
         constexpr int PAR = decltype(PARC)::value;
-        const u32x4* const curA = PAR ? sA1 : sA0;
-        const u32x4* const curB = PAR ? sB1 : sB0;
+        const u32x4* const curA = PAR ? xA1 : xA0;
+        const u32x4* const curG = PAR ? sG1 : sG0;
         __syncthreads();
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            frag_load(curA, curB, ks, C0());
-            mma(C0());
+            frag_load(curA, PARC, curG, ks, C0());
+            cook(C0(), 0, ITEMS);
+            mma(C0(), 0); mma(C0(), 1); mma(C0(), 2); mma(C0(), 3);
         }
     };
 
-    // prologue: tile 0 into buffer pair 0, A tile 1 in flight in register set 1
-    gload_a(0, C0());
-    touch(C0());
-    __builtin_amdgcn_sched_barrier(0);
-    dma_b(0, sB0);
-    gload_a(min(1, nk - 1), C1());
-    __builtin_amdgcn_sched_barrier(0);
-    sstore_part(sA0, C0(), C0());
-    sstore_part(sA0, C0(), C1());
-    sstore_part(sA0, C0(), C2());
-    sstore_part(sA0, C0(), C3());
+    // prologue: tile 0 into buffer set 0
+#pragma unroll
+    for (int part = 0; part < 4; ++part) {
+        dma_b(0, sB0, part);
+        dma_a(0, xA0, sG0, part);
+    }
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
 
@@ -387,36 +397,33 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     {
         int kt = 0;
         for (; kt + 2 < nk; kt += 2) {
-            step(kt, kt + 2, C0());
-            step(kt + 1, min(kt + 3, nk - 1), C1());
+            step(kt, C0());
+            step(kt + 1, C1());
         }
         if (ODD) {
             last_step(C0());
         } else {
-            step(kt, kt + 1, C0());
+            step(kt, C0());
             last_step(C1());
         }
     }
 
-    // ---- row statistics: finish the sums over the 8 lanes sharing a row
+    // ---- row statistics: add the two lanes that share a row (lane, lane ^ 32)
     if (MODE != MODE_PLAIN) {
 #pragma unroll
-        for (int i = 0; i < AI; ++i) {
-            float s2 = ssq[i], s1 = ssum[i];
-#pragma unroll
-            for (int o = 1; o < 8; o <<= 1) {
-                s2 += __shfl_xor(s2, o);
-                if (MODE == MODE_LN) s1 += __shfl_xor(s1, o);
-            }
-            if (kcA == 0) {
+        for (int s = 0; s < MT; ++s) {
+            const float s2 = ssq[s] + __shfl_xor(ssq[s], 32);
+            const float s1 = ssum[s] + __shfl_xor(ssum[s], 32);
+            if (lhi == 0) {
                 const float invK = 1.0f / (float)p.K;
+                const int rl = WR * wm + 32 * s + l32;
                 if (MODE == MODE_LN) {
                     const float mu = s1 * invK;
                     const float var = fmaxf(s2 * invK - mu * mu, 0.f);
-                    stat0[rowA + 32 * i] = rsqrtf(var + p.eps);
-                    stat1[rowA + 32 * i] = mu;
+                    stat0[rl] = rsqrtf(var + p.eps);
+                    stat1[rl] = mu;
                 } else {
-                    stat0[rowA + 32 * i] = rsqrtf(s2 * invK + p.eps);
+                    stat0[rl] = rsqrtf(s2 * invK + p.eps);
                 }
             }
         }
@@ -433,21 +440,22 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     const u32 tsel = (eq & 1) ? 0x03020706u : 0x05040100u;
     const bool tup = (eq & 2) != 0;
     if (MODE == MODE_GATEUP) {
-        const int fcol = n0 + 64 * wn + 4 * (l32 >> 2);       // + 32 u
+        static_assert(MODE != MODE_GATEUP || NT == 8, "gate and up subtiles must share a wavefront");
+        const int fcol = n0 + 4 * (l32 >> 2);       // + 32 u
 #pragma unroll
         for (int s = 0; s < MT; ++s) {
 #pragma unroll
             for (int vg = 0; vg < 4; ++vg) {
-                const int rl = wm * (BM / 2) + 32 * s + 8 * vg + 4 * lhi;
+                const int rl = WR * wm + 32 * s + 8 * vg + 4 * lhi;
                 float r[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) r[i] = stat0[rl + i];
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
+                for (int u = 0; u < NT / 2; ++u) {
                     float h[4];
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        h[i] = swiglu(r[i] * acc[s][u][4 * vg + i], r[i] * acc[s][u + 2][4 * vg + i]);
+                        h[i] = swiglu(r[i] * acc[s][u][4 * vg + i], r[i] * acc[s][u + NT / 2][4 * vg + i]);
                     u32 d0 = pack_bf16(h[0], h[1]), d1 = pack_bf16(h[2], h[3]);
                     quad_transpose(d0, d1, tup, tsel);
                     const int m = m0 + rl + eq, col = fcol + 32 * u;
@@ -459,12 +467,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
             }
         }
     } else {
-        const int ncol = n0 + 128 * wn + l32;                 // + 32 tt: the column this lane accumulated
-        const int scol = n0 + 128 * wn + 4 * (l32 >> 2);      // + 32 tt: first of the 4 columns it stores
-        float cc[4], cb[4];
+        const int ncol = n0 + WC * wn + l32;                 // + 32 tt: the column this lane accumulated
+        const int scol = n0 + WC * wn + 4 * (l32 >> 2);      // + 32 tt: first of the 4 columns it stores
+        float cc[NT], cb[NT];
         if (MODE == MODE_LN) {
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt) {
+            for (int tt = 0; tt < NT; ++tt) {
                 const bool ok = FULL || ncol + 32 * tt < p.N;
                 cc[tt] = ok ? p.colc[ncol + 32 * tt] : 0.f;
                 cb[tt] = ok ? p.colb[ncol + 32 * tt] : 0.f;
@@ -474,14 +482,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
         for (int s = 0; s < MT; ++s) {
 #pragma unroll
             for (int vg = 0; vg < 4; ++vg) {
-                const int rl = wm * (BM / 2) + 32 * s + 8 * vg + 4 * lhi;
+                const int rl = WR * wm + 32 * s + 8 * vg + 4 * lhi;
                 float r[4], mu[4];
                 if (MODE == MODE_LN) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) { r[i] = stat0[rl + i]; mu[i] = stat1[rl + i]; }
                 }
 #pragma unroll
-                for (int tt = 0; tt < 4; ++tt) {
+                for (int tt = 0; tt < NT; ++tt) {
                     float y[4];
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
