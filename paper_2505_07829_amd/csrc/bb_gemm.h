@@ -311,32 +311,35 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     constexpr int NDSR = MT + 2 * NT + (MODE != MODE_PLAIN ? 1 : 0);   // LDS reads per fragment set
     constexpr int ITEMS = 4 * MT;                                      // prologue items per fragment set
     constexpr int P1 = (ITEMS + 2) / 3, P2 = (2 * ITEMS + 2) / 3;      // item ranges of quarters 1, 2, 3
-    // Placement request inside one quarter (the instructions issue in order,
-    // so only what stands between two matrix instructions runs in the shadow
-    // of the first): the LDS reads first, then per matrix instruction a slice
-    // of the vector ALU work, and a load-to-LDS after every second one.
-    auto pattern = [&](bool with_frags, auto VALUC, bool with_dma) {
-        constexpr int valu = decltype(VALUC)::value;
-        if (with_frags) __builtin_amdgcn_sched_group_barrier(0x100, NDSR, 0);
+    // Placement request for one group of matrix instructions (the instructions
+    // issue in order, so only what stands between two matrix instructions runs
+    // in the shadow of the first).  The A and gain reads of the next fragment
+    // set come first (the prologue waits for them); then every matrix
+    // instruction is followed by its share of the B reads (so that the four
+    // wavefronts do not burst into the LDS together), a slice of the vector ALU
+    // work and, every second time, one load-to-LDS.
+    constexpr int NDSR_A = MT + (MODE != MODE_PLAIN ? 1 : 0);
+    constexpr int DSR_PER = (2 * NT + NMMA - 1) / NMMA;
+    constexpr int VQ = (MODE == MODE_PLAIN) ? 2 : (7 * ITEMS + 8) / NMMA + 3;   // vector ALU slice per matrix instruction
+    auto pattern = [&](bool with_frags, bool with_dma) {
+        if (with_frags) __builtin_amdgcn_sched_group_barrier(0x100, NDSR_A, 0);
 #pragma unroll
-        for (int i = 0; i < QMMA; ++i) {
+        for (int i = 0; i < NMMA; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (valu > 0) __builtin_amdgcn_sched_group_barrier(0x002, valu, 0);
-            if (with_dma && ((i & 1) || QMMA < 4)) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+            if (with_frags) __builtin_amdgcn_sched_group_barrier(0x100, DSR_PER, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, VQ, 0);
+            if (with_dma && ((i & 1) || NMMA < 16)) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
     };
-    using VQ = std::integral_constant<int, (MODE == MODE_PLAIN) ? 2 : (6 * ITEMS) / (3 * QMMA) + 4>;   // vector ALU slice per matrix instruction
-    using V2 = std::integral_constant<int, 2>;
-    using V0 = std::integral_constant<int, 0>;
+    auto mma_all = [&](auto SETC) { mma(SETC, 0); mma(SETC, 1); mma(SETC, 2); mma(SETC, 3); };
 
     // One contraction step on buffer set PAR (tile kt, kt % 2 == PAR): four
-    // groups of matrix instructions (one per 16 contraction indices), each in
-    // four quarters.  The first quarter of a group issues the LDS reads of the
-    // next group's fragments, the other three run the norm prologue on them.
-    // The load-to-LDS instructions of tile kt + 1 are spread over the quarters
-    // of the first two groups (B, then A), so that the step's second half is
-    // left for them to land.
+    // groups of matrix instructions (one per 16 contraction indices).  Each
+    // group reads the next group's fragments and runs the norm prologue on
+    // them.  The load-to-LDS instructions of tile kt + 1 are spread over the
+    // first two groups (B, then A), so that the step's second half is left for
+    // them to land.
     auto step = [&](int kt, auto PARC) {
         constexpr int PAR = decltype(PARC)::value;
         const u32x4* const curA = PAR ? xA1 : xA0;
@@ -346,28 +349,30 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
         u32x4* const nxtG = PAR ? sG0 : sG1;
         __syncthreads();
         frag_load(curA, PARC, curG, 0, C0());
-        cook(C0(), 0, 4);                               // subtile row 0: all the first quarter needs
+        cook(C0(), 0, 4);                               // subtile row 0: all the first matrix instructions need
         __builtin_amdgcn_sched_barrier(0);
         // group 0
         frag_load(curA, PARC, curG, 1, C1());
-        mma(C0(), 0); cook(C0(), 4, ITEMS); dma_b(kt + 1, nxtB, 0); pattern(true, VQ(), true);
-        mma(C0(), 1); cook(C1(), 0, P1);    dma_b(kt + 1, nxtB, 1); pattern(false, VQ(), true);
-        mma(C0(), 2); cook(C1(), P1, P2);   dma_b(kt + 1, nxtB, 2); pattern(false, VQ(), true);
-        mma(C0(), 3); cook(C1(), P2, ITEMS); dma_b(kt + 1, nxtB, 3); pattern(false, VQ(), true);
+        cook(C0(), 4, ITEMS);
+        mma_all(C0());
+        cook(C1(), 0, ITEMS);
+#pragma unroll
+        for (int part = 0; part < 4; ++part) dma_b(kt + 1, nxtB, part);
+        pattern(true, true);
         // group 1
         frag_load(curA, PARC, curG, 2, C0());
-        mma(C1(), 0);                       dma_a(kt + 1, nxtA, nxtG, 0); pattern(true, V2(), true);
-        mma(C1(), 1); cook(C0(), 0, P1);    dma_a(kt + 1, nxtA, nxtG, 1); pattern(false, VQ(), true);
-        mma(C1(), 2); cook(C0(), P1, P2);   dma_a(kt + 1, nxtA, nxtG, 2); pattern(false, VQ(), true);
-        mma(C1(), 3); cook(C0(), P2, ITEMS); dma_a(kt + 1, nxtA, nxtG, 3); pattern(false, VQ(), true);
+        mma_all(C1());
+        cook(C0(), 0, ITEMS);
+#pragma unroll
+        for (int part = 0; part < 4; ++part) dma_a(kt + 1, nxtA, nxtG, part);
+        pattern(true, true);
         // group 2
         frag_load(curA, PARC, curG, 3, C1());
-        mma(C0(), 0);                       pattern(true, V0(), false);
-        mma(C0(), 1); cook(C1(), 0, P1);    pattern(false, VQ(), false);
-        mma(C0(), 2); cook(C1(), P1, P2);   pattern(false, VQ(), false);
-        mma(C0(), 3); cook(C1(), P2, ITEMS); pattern(false, VQ(), false);
+        mma_all(C0());
+        cook(C1(), 0, ITEMS);
+        pattern(true, false);
         // group 3
-        mma(C1(), 0); mma(C1(), 1); mma(C1(), 2); mma(C1(), 3);
+        mma_all(C1());
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     };
