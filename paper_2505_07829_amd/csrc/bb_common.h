@@ -51,13 +51,15 @@ __device__ __forceinline__ void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[
     }
 }
 
-// LDS tiles are arrays of 16-byte chunks, 8 chunks (64 contraction indices)
-// per row.  LDS has 32 four-byte banks and serves a 128-bit access of a
-// wavefront eight lanes at a time, so eight consecutive lanes must hit eight
-// different 16-byte bank groups.  The chunk index is XOR-swizzled with the low
-// three row bits: 8 consecutive rows at one chunk index, or one row's 8
-// chunks, then fall on 8 different groups.
-__device__ __forceinline__ int lds_pos(int row, int kc) { return row * 8 + (kc ^ (row & 7)); }
+// LDS tiles of the A operand are arrays of 16-byte chunks, 8 chunks (64
+// contraction indices) per row.  The LDS of gfx950 has 64 four-byte banks and
+// serves a 128-bit read of a wavefront sixteen lanes at a time (measured: 256
+// bytes per clock when these sixteen chunks fall on sixteen different 16-byte
+// bank groups, half of that with a swizzle that only separates eight).  A
+// fragment read has 16 consecutive lanes on 16 consecutive rows at one chunk
+// index; two rows are one pass through the banks, so the chunk index is
+// XOR-swizzled with bits 1..3 of the row.
+__device__ __forceinline__ int lds_pos(int row, int kc) { return row * 8 + (kc ^ ((row >> 1) & 7)); }
 
 __device__ __forceinline__ u32x4 zero4() { u32x4 z = {0u, 0u, 0u, 0u}; return z; }
 

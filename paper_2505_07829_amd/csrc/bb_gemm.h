@@ -31,13 +31,12 @@
 // row-major as in memory.  The matrix instruction wants, per lane, 8
 // consecutive contraction indices of one column; the transposing LDS read
 // (ds_read_b64_tr_b16) delivers exactly that from a row-major tile, 4
-// contraction rows x 16 columns per group of 16 lanes.  Its 16 lanes read 4
-// rows x 32 bytes; the 16-byte chunks of a row are XOR-swizzled with the low
-// two row bits (in units of 32 bytes) so that these rows fall on different
-// banks.
+// contraction rows x 16 columns per group of 16 lanes.  The 16-byte chunks of
+// a row are XOR-swizzled with the low two row bits (in units of 64 bytes) so
+// that the rows read together fall on different banks.
 //
 // A operand.  The activation tile lies in LDS as rows of 8 chunks (16 bytes = 8
-// contraction indices), chunk index XOR-swizzled with the low row bits; one
+// contraction indices), chunk index XOR-swizzled with row bits 1..3; one
 // 128-bit LDS read is one matrix-instruction operand.  The norm prologue works
 // on these operand registers: a fragment is read one group of matrix
 // instructions ahead, its squares (LN: and its values) are added to the
@@ -153,22 +152,28 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     const u16* const zsrc = reinterpret_cast<const u16*>(&gemm_zero_chunk);
 
     // ---- A: load-to-LDS role.  One instruction fills 64 chunks = 8 tile rows,
-    // lane i -> chunk position i % 8 of row i / 8, which holds source chunk
-    // (i % 8) ^ (row % 8).  Wavefront w issues row groups w ADMA .. w ADMA + ADMA-1.
+    // lane i -> chunk position i % 8 of row i / 8 (+ 8 per instruction), which
+    // holds source chunk (i % 8) ^ ((row / 2) % 8): two lane constants, for even
+    // and odd instructions.  Wavefront w issues row groups w ADMA .. w ADMA + ADMA-1.
     const int rowA = 8 * ADMA * w + (lane >> 3);                 // + 8 j for instruction j
-    const int kcA = (lane & 7) ^ ((lane >> 3) & 7);
-    const u16* const Alane = p.A + (size_t)(m0 + rowA) * p.lda + 8 * kcA;
+    int kcA[2];
+    const u16* Alane[2];
+#pragma unroll
+    for (int o = 0; o < 2; ++o) {
+        kcA[o] = (lane & 7) ^ (((rowA + 8 * o) >> 1) & 7);
+        Alane[o] = p.A + (size_t)(m0 + rowA) * p.lda + 8 * kcA[o];
+    }
 
     // ---- B: load-to-LDS role.  One instruction fills 1 KiB = two tile rows,
     // lane i -> byte 16 i.  Wavefront w issues row pairs w, w+4, ..., w+28; this
     // lane therefore always serves tile rows = 2 w + lhi (mod 8) and chunk
-    // position l32, which holds source chunk l32 ^ 2 (row & 3).  Source chunk c
+    // position l32, which holds source chunk l32 ^ 4 (row & 3).  Source chunk c
     // of a tile row is columns n0 + 8 c; in GATEUP chunks 0..15 are W1's 128
     // columns and chunks 16..31 are W3's, so that subtiles tt and tt + 4 of the
     // (single-column) wavefront tile are the gate and the up product of the
     // same hidden units.
     const int rowB = 2 * w + lhi;
-    const int chunkB = l32 ^ ((rowB & 3) << 1);
+    const int chunkB = l32 ^ ((rowB & 3) << 2);
     const u16* Bsrc = p.B0;
     int colB;
     if (MODE == MODE_GATEUP) {
@@ -184,17 +189,21 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     // covers contraction rows 8 (b / 2) + 4 h + (0..3) (+ 16 per matrix
     // instruction) and columns 32 tt + 16 (b % 2) + (0..15) of the wavefront's
     // columns; lane i' = lane % 16 supplies the address of row i' / 4, 4-column
-    // piece i' % 4.  Byte offsets for tt even / odd (the swizzle XORs bit 2 of
-    // the chunk index, which is tt's low bit, so odd tt is not a plain offset).
-    int offB[2];
+    // piece i' % 4.  The 32 lanes served together read 4 rows x 64 bytes; rows
+    // are 512 bytes apart, i.e. on the same banks, so the 16-byte chunk index is
+    // XOR-swizzled with 4 (row % 4): the four rows then take the four 64-byte
+    // quarters of the 256-byte bank line.  The XOR touches the chunk bits that
+    // tt % 4 occupies, hence one byte offset per tt % 4 (tt / 4 is a plain
+    // displacement).
+    int offB[4];
     {
         const int b = lane >> 4, ip = lane & 15;
         const int r = 8 * (b >> 1) + (ip >> 2);
         const int piece = ip & 3;
 #pragma unroll
-        for (int o = 0; o < 2; ++o) {
+        for (int o = 0; o < 4; ++o) {
             const int chunk = (WC / 8) * wn + 4 * o + 2 * (b & 1) + (piece >> 1);
-            offB[o] = r * 512 + ((chunk ^ ((r & 3) << 1)) << 4) + 8 * (piece & 1);
+            offB[o] = r * 512 + ((chunk ^ ((r & 3) << 2)) << 4) + 8 * (piece & 1);
         }
     }
 
@@ -216,13 +225,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     // wavefront writes the same bytes there: no branch in the step)
     auto dma_a = [&](int kt, u32x4* dA, u32x4* dG, int part) {
         const int k0 = kt * GEMM_BK;
-        const u16* srcA = Alane + k0;
-        const bool ka_ok = FULL || k0 + 8 * kcA < p.K;
 #pragma unroll
         for (int jj = 0; jj < ADMA / 4; ++jj) {
             const int j = (ADMA / 4) * part + jj;
-            const u16* g = srcA + (size_t)(8 * j) * p.lda;
-            if (!FULL) g = (ka_ok && m0 + rowA + 8 * j < p.M) ? g : zsrc;
+            const u16* g = Alane[j & 1] + k0 + (size_t)(8 * j) * p.lda;
+            if (!FULL) g = (k0 + 8 * kcA[j & 1] < p.K && m0 + rowA + 8 * j < p.M) ? g : zsrc;
             load_to_lds16(g, dA + (ADMA * w + j) * 64);
         }
         if (MODE != MODE_PLAIN && part == 3) {
@@ -242,9 +249,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
             for (int v = 0; v < 16; ++v) acc[s][tt][v] = 0.f;
     // row sums of the fragments this lane has seen: row 32 s + l32 of the
     // wavefront's rows, contraction chunks with (chunk % 2) == lhi
-    float ssq[MT], ssum[MT];
+    // (two partial sums each, for the even and the odd elements)
+    float ssq[MT][2], ssum[MT][2];
 #pragma unroll
-    for (int s = 0; s < MT; ++s) { ssq[s] = 0.f; ssum[s] = 0.f; }
+    for (int s = 0; s < MT; ++s) { ssq[s][0] = ssq[s][1] = 0.f; ssum[s][0] = ssum[s][1] = 0.f; }
 
     using C0 = std::integral_constant<int, 0>;
     using C1 = std::integral_constant<int, 1>;
@@ -262,7 +270,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
         if (MODE != MODE_PLAIN) fg[S].u = bufG[kc];
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt) {
-            const char* q = reinterpret_cast<const char*>(PB ? sB1 : sB0) + offB[tt & 1] + ks * (16 * 512) + 128 * (tt >> 1);
+            const char* q = reinterpret_cast<const char*>(PB ? sB1 : sB0) + offB[tt & 3] + ks * (16 * 512) + 256 * (tt >> 2);
             const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(q));
             const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(q + 4 * 512));
             u32x2 l2 = *reinterpret_cast<const u32x2*>(&lo), h2 = *reinterpret_cast<const u32x2*>(&hi);
@@ -283,13 +291,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
                 const int item = 4 * s + q;
                 if (item < lo || item >= hi) continue;
                 const u32 xw = fa[S][s].u[q];
-                const bf16x2 xb = *reinterpret_cast<const bf16x2*>(&xw);
-                ssq[s] = __builtin_amdgcn_fdot2_f32_bf16(xb, xb, ssq[s], false);
-                if (MODE == MODE_LN) {
-                    const u32 onew = 0x3f803f80u;
-                    ssum[s] = __builtin_amdgcn_fdot2_f32_bf16(xb, *reinterpret_cast<const bf16x2*>(&onew), ssum[s], false);
-                }
-                fa[S][s].u[q] = pack_bf16(bf_lo(xw) * bf_lo(gv[q]), bf_hi(xw) * bf_hi(gv[q]));
+                const float xl = bf_lo(xw), xh = bf_hi(xw);
+                // (plain multiply-adds: the bf16 dot-product instruction does not
+                // overlap with matrix instructions and costs ~20 cycles next to them)
+                ssq[s][0] = fmaf(xl, xl, ssq[s][0]);
+                ssq[s][1] = fmaf(xh, xh, ssq[s][1]);
+                if (MODE == MODE_LN) { ssum[s][0] += xl; ssum[s][1] += xh; }
+                fa[S][s].u[q] = pack_bf16(xl * bf_lo(gv[q]), xh * bf_hi(gv[q]));
             }
         }
     };
@@ -320,7 +328,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     // work and, every second time, one load-to-LDS.
     constexpr int NDSR_A = MT + (MODE != MODE_PLAIN ? 1 : 0);
     constexpr int DSR_PER = (2 * NT + NMMA - 1) / NMMA;
-    constexpr int VQ = (MODE == MODE_PLAIN) ? 2 : (7 * ITEMS + 8) / NMMA + 3;   // vector ALU slice per matrix instruction
+    constexpr int VQ = (MODE == MODE_PLAIN) ? 2 : ((MODE == MODE_LN ? 9 : 7) * ITEMS + 8) / NMMA + 3;   // vector ALU slice per matrix instruction
     auto pattern = [&](bool with_frags, bool with_dma) {
         if (with_frags) __builtin_amdgcn_sched_group_barrier(0x100, NDSR_A, 0);
 #pragma unroll
@@ -334,62 +342,77 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     };
     auto mma_all = [&](auto SETC) { mma(SETC, 0); mma(SETC, 1); mma(SETC, 2); mma(SETC, 3); };
 
-    // One contraction step on buffer set PAR (tile kt, kt % 2 == PAR): four
-    // groups of matrix instructions (one per 16 contraction indices).  Each
-    // group reads the next group's fragments and runs the norm prologue on
-    // them.  The load-to-LDS instructions of tile kt + 1 are spread over the
-    // first two groups (B, then A), so that the step's second half is left for
-    // them to land.
+    // One contraction step on buffer set PAR (tile kt, kt % 2 == PAR, not the
+    // last tile): four groups of matrix instructions (one per 16 contraction
+    // indices).  Each group reads the next group's fragments and runs the norm
+    // prologue on them.  The step is rotated against the tiles: on entry
+    // fragment set 0 already holds slice 0 of tile kt; the barrier stands before
+    // the last group, which reads slice 0 of tile kt + 1 from the other buffer
+    // set, so that no wavefront stands at a barrier or waits for its first
+    // fragments with nothing queued for the matrix core.  Loads: group 0 issues
+    // the A tile kt + 1 into the other set (free since the previous barrier),
+    // the last group issues the B tile kt + 2 into this set (free since this
+    // step's barrier; for the last but one tile there is no such tile and the
+    // last tile is fetched again into the then unused set).
     auto step = [&](int kt, auto PARC) {
         constexpr int PAR = decltype(PARC)::value;
+        using NPAR = std::integral_constant<int, 1 - PAR>;
         const u32x4* const curA = PAR ? xA1 : xA0;
         const u32x4* const curG = PAR ? sG1 : sG0;
+        u32x4* const curB = PAR ? sB1 : sB0;
         u32x4* const nxtA = PAR ? xA0 : xA1;
-        u32x4* const nxtB = PAR ? sB0 : sB1;
         u32x4* const nxtG = PAR ? sG0 : sG1;
-        __syncthreads();
-        frag_load(curA, PARC, curG, 0, C0());
-        cook(C0(), 0, 4);                               // subtile row 0: all the first matrix instructions need
-        __builtin_amdgcn_sched_barrier(0);
         // group 0
         frag_load(curA, PARC, curG, 1, C1());
-        cook(C0(), 4, ITEMS);
         mma_all(C0());
         cook(C1(), 0, ITEMS);
 #pragma unroll
-        for (int part = 0; part < 4; ++part) dma_b(kt + 1, nxtB, part);
+        for (int part = 0; part < 4; ++part) dma_a(kt + 1, nxtA, nxtG, part);
         pattern(true, true);
         // group 1
         frag_load(curA, PARC, curG, 2, C0());
         mma_all(C1());
         cook(C0(), 0, ITEMS);
-#pragma unroll
-        for (int part = 0; part < 4; ++part) dma_a(kt + 1, nxtA, nxtG, part);
-        pattern(true, true);
+        pattern(true, false);
         // group 2
         frag_load(curA, PARC, curG, 3, C1());
         mma_all(C0());
         cook(C1(), 0, ITEMS);
         pattern(true, false);
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        __syncthreads();
         // group 3
+        frag_load(nxtA, NPAR(), nxtG, 0, C0());
+        mma_all(C1());
+        cook(C0(), 0, ITEMS);
+        const int kb = min(kt + 2, nk - 1);
+#pragma unroll
+        for (int part = 0; part < 4; ++part) dma_b(kb, curB, part);
+        pattern(true, true);
+    };
+    auto last_step = [&](auto PARC) {          // last tile: nothing left to load
+        constexpr int PAR = decltype(PARC)::value;
+        const u32x4* const curA = PAR ? xA1 : xA0;
+        const u32x4* const curG = PAR ? sG1 : sG0;
+        frag_load(curA, PARC, curG, 1, C1());
+        mma_all(C0());
+        cook(C1(), 0, ITEMS);
+        pattern(true, false);
+        frag_load(curA, PARC, curG, 2, C0());
+        mma_all(C1());
+        cook(C0(), 0, ITEMS);
+        pattern(true, false);
+        frag_load(curA, PARC, curG, 3, C1());
+        mma_all(C0());
+        cook(C1(), 0, ITEMS);
+        pattern(true, false);
         mma_all(C1());
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     };
-    auto last_step = [&](auto PARC) {          // nothing left to load
-        constexpr int PAR = decltype(PARC)::value;
-        const u32x4* const curA = PAR ? xA1 : xA0;
-        const u32x4* const curG = PAR ? sG1 : sG0;
-        __syncthreads();
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            frag_load(curA, PARC, curG, ks, C0());
-            cook(C0(), 0, ITEMS);
-            mma(C0(), 0); mma(C0(), 1); mma(C0(), 2); mma(C0(), 3);
-        }
-    };
 
-    // prologue: tile 0 into buffer set 0
+    // prologue: tile 0 into buffer set 0, its slice 0 into fragment set 0, B
+    // tile 1 under way
 #pragma unroll
     for (int part = 0; part < 4; ++part) {
         dma_b(0, sB0, part);
@@ -397,6 +420,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     }
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
+#pragma unroll
+    for (int part = 0; part < 4; ++part) dma_b(min(1, nk - 1), sB1, part);
+    frag_load(xA0, C0(), sG0, 0, C0());
+    cook(C0(), 0, ITEMS);
+    __builtin_amdgcn_sched_barrier(0);
 
     // pairs of steps; the tail depends on the parity of nk only
     {
@@ -417,8 +446,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     if (MODE != MODE_PLAIN) {
 #pragma unroll
         for (int s = 0; s < MT; ++s) {
-            const float s2 = ssq[s] + __shfl_xor(ssq[s], 32);
-            const float s1 = ssum[s] + __shfl_xor(ssum[s], 32);
+            const float q2 = ssq[s][0] + ssq[s][1], q1 = ssum[s][0] + ssum[s][1];
+            const float s2 = q2 + __shfl_xor(q2, 32);
+            const float s1 = q1 + __shfl_xor(q1, 32);
             if (lhi == 0) {
                 const float invK = 1.0f / (float)p.K;
                 const int rl = WR * wm + 32 * s + l32;
