@@ -366,14 +366,16 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
         frag_load(curA, PARC, curG, 1, C1());
         mma_all(C0());
         cook(C1(), 0, ITEMS);
-#pragma unroll
-        for (int part = 0; part < 4; ++part) dma_a(kt + 1, nxtA, nxtG, part);
+        dma_a(kt + 1, nxtA, nxtG, 0);
+        dma_a(kt + 1, nxtA, nxtG, 1);
         pattern(true, true);
         // group 1
         frag_load(curA, PARC, curG, 2, C0());
         mma_all(C1());
         cook(C0(), 0, ITEMS);
-        pattern(true, false);
+        dma_a(kt + 1, nxtA, nxtG, 2);
+        dma_a(kt + 1, nxtA, nxtG, 3);
+        pattern(true, true);
         // group 2
         frag_load(curA, PARC, curG, 3, C1());
         mma_all(C0());
