@@ -195,7 +195,7 @@ size_t zone_bytes(int op, int64_t M, int64_t D, int64_t F) {
 size_t scratch_bytes(int op, int64_t M, int64_t D, int64_t F) {
     switch (op) {
         case BB_OP_RMSNORM_SWIGLU_FFN: return align_up((size_t)M * F * 2);
-        case BB_OP_LAYERNORM_MATMUL: return 2 * align_up((size_t)F * 4);
+        case BB_OP_LAYERNORM_MATMUL: return (2 + 2 * COLVEC_SPLITS) * align_up((size_t)F * 4);
         case BB_OP_RMSNORM_SWIGLU_FFN_UNFUSED: return align_up((size_t)M * D * 2) + 3 * align_up((size_t)M * F * 2);
         case BB_OP_LAYERNORM_MATMUL_UNFUSED: return align_up((size_t)M * D * 2);
         default: return 0;
@@ -427,8 +427,12 @@ int bb_layernorm_matmul(const void* X, const void* gamma, const void* beta, cons
     float* colc = (float*)g_ws.ptr;
     float* colb = (float*)((char*)g_ws.ptr + align_up((size_t)N * 4));
     prof_begin(st);
-    hipLaunchKernelGGL(colvec_kernel, dim3((unsigned)((N + 63) / 64)), dim3(256), 0, st, (const u16*)W,
-                       (const u16*)gamma, (const u16*)beta, colc, colb, (int)D, (int)N);
+    float* part = (float*)((char*)g_ws.ptr + 2 * align_up((size_t)N * 4));
+    hipLaunchKernelGGL(colvec_partial_kernel, dim3((unsigned)((N + 511) / 512), COLVEC_SPLITS), dim3(256), 0, st,
+                       (const u16*)W, (const u16*)gamma, (const u16*)beta, part, (int)D, (int)N);
+    BB_HIP(hipGetLastError());
+    hipLaunchKernelGGL(colvec_sum_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, part, colc, colb,
+                       (int)N);
     BB_HIP(hipGetLastError());
     prof_mark("colvec", st);
     return launch_gemm<MODE_LN>((const u16*)X, (int)D, (const u16*)W, nullptr, (int)N, (u16*)Y, (int)N,

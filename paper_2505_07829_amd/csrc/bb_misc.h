@@ -87,40 +87,71 @@ __global__ __launch_bounds__(256) void silu_mul_kernel(const u16* P, const u16* 
 
 // colc[n] = sum_d gamma[d] W[d,n],  colb[n] = sum_d beta[d] W[d,n]   (Rule 5:
 // the column sums of the gain-scaled weight; beta's image is the bias row).
-// One workgroup per 64 columns: thread = (row group t/8 of 32, 8-column chunk t%8).
-__global__ __launch_bounds__(256) void colvec_kernel(const u16* W, const u16* gamma, const u16* beta,
-                                                     float* colc, float* colb, int D, int N) {
-    __shared__ float red[2][32][64];
-    const int t = threadIdx.x, cg = t & 7, rg = t >> 3;
-    const int col = blockIdx.x * 64 + 8 * cg;
+// W is streamed once.  Workgroup (x, y) takes 512 columns and the y-th of
+// COLVEC_SPLITS row ranges; each wavefront reads whole 1 KiB row segments (one
+// 16-byte load per lane, eight rows in flight), the four wavefronts' sums are
+// added through LDS and written as partial sums part[y][0/1][n]; a second
+// small kernel adds the COLVEC_SPLITS partial sums (fixed order, no atomics).
+constexpr int COLVEC_SPLITS = 8;
+__global__ __launch_bounds__(256) void colvec_partial_kernel(const u16* W, const u16* gamma, const u16* beta,
+                                                             float* part, int D, int N) {
+    __shared__ float red[3][2][512];
+    const int t = threadIdx.x, lane = t & 63, w = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int col = blockIdx.x * 512 + 8 * lane;
+    const int dper = ((D + COLVEC_SPLITS - 1) / COLVEC_SPLITS + 7) / 8 * 8;      // multiple of 8 (so is D)
+    const int dbeg = blockIdx.y * dper, dend = min(D, dbeg + dper);
     float c[8], b[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) { c[j] = 0.f; b[j] = 0.f; }
     if (col < N) {
-        for (int d = rg; d < D; d += 32) {
-            const u32x4 wv = ldg16(W + (size_t)d * N + col);
-            const float ga = __uint_as_float((u32)gamma[d] << 16), be = __uint_as_float((u32)beta[d] << 16);
+        // a wavefront takes 8 consecutive rows per turn: one 16-byte load of gamma
+        // and of beta serves them, and the 8 row segments are in flight together
+        for (int d0 = dbeg + 8 * w; d0 < dend; d0 += 8 * 4) {
+            u32x4 wv[8];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float w0 = bf_lo(wv[q]), w1 = bf_hi(wv[q]);
-                c[2 * q] = fmaf(ga, w0, c[2 * q]);
-                c[2 * q + 1] = fmaf(ga, w1, c[2 * q + 1]);
-                b[2 * q] = fmaf(be, w0, b[2 * q]);
-                b[2 * q + 1] = fmaf(be, w1, b[2 * q + 1]);
+            for (int u = 0; u < 8; ++u) wv[u] = ldg16(W + (size_t)(d0 + u) * N + col);
+            const u32x4 gv = ldg16(gamma + d0), bv = ldg16(beta + d0);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float ga = (u & 1) ? bf_hi(gv[u >> 1]) : bf_lo(gv[u >> 1]);
+                const float be = (u & 1) ? bf_hi(bv[u >> 1]) : bf_lo(bv[u >> 1]);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float w0 = bf_lo(wv[u][q]), w1 = bf_hi(wv[u][q]);
+                    c[2 * q] = fmaf(ga, w0, c[2 * q]);
+                    c[2 * q + 1] = fmaf(ga, w1, c[2 * q + 1]);
+                    b[2 * q] = fmaf(be, w0, b[2 * q]);
+                    b[2 * q + 1] = fmaf(be, w1, b[2 * q + 1]);
+                }
             }
         }
     }
+    if (w > 0) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) { red[0][rg][8 * cg + j] = c[j]; red[1][rg][8 * cg + j] = b[j]; }
-    __syncthreads();
-    if (t < 128) {
-        const int sel = t >> 6, cc = t & 63;
-        float s = 0.f;
-#pragma unroll 8
-        for (int r = 0; r < 32; ++r) s += red[sel][r][cc];
-        const int n = blockIdx.x * 64 + cc;
-        if (n < N) (sel ? colb : colc)[n] = s;
+        for (int j = 0; j < 8; ++j) { red[w - 1][0][8 * lane + j] = c[j]; red[w - 1][1][8 * lane + j] = b[j]; }
     }
+    __syncthreads();
+    if (w == 0 && col < N) {
+        float* pc = part + ((size_t)blockIdx.y * 2 + 0) * N + col;
+        float* pb = part + ((size_t)blockIdx.y * 2 + 1) * N + col;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            pc[j] = c[j] + red[0][0][8 * lane + j] + red[1][0][8 * lane + j] + red[2][0][8 * lane + j];
+            pb[j] = b[j] + red[0][1][8 * lane + j] + red[1][1][8 * lane + j] + red[2][1][8 * lane + j];
+        }
+    }
+}
+__global__ __launch_bounds__(256) void colvec_sum_kernel(const float* part, float* colc, float* colb, int N) {
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    float c = 0.f, b = 0.f;
+#pragma unroll
+    for (int y = 0; y < COLVEC_SPLITS; ++y) {
+        c += part[((size_t)y * 2 + 0) * N + n];
+        b += part[((size_t)y * 2 + 1) * N + n];
+    }
+    colc[n] = c;
+    colb[n] = b;
 }
 
 __global__ __launch_bounds__(256) void fill_zero_kernel(u32x4* p, size_t n16) {
