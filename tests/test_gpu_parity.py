@@ -165,6 +165,27 @@ def test_ln_gamma_zero_gives_bias_row():
     assert torch.all(Y == Y[0:1])                        # every row identical
 
 
+# Complete-tile kernels (no bounds checks) with an odd and an even number of
+# contraction steps, and the shortest contractions (one and two steps): the
+# rotated main loop has a prologue, paired steps and a parity-dependent tail.
+@pytest.mark.parametrize("M,D,F", [(256, 256, 384), (256, 192, 384), (128, 256, 448), (128, 64, 128),
+                                   (128, 128, 64), (384, 320, 640), (512, 64, 192)])
+@pytest.mark.parametrize("unfused", [False, True])
+def test_complete_tiles_and_step_parities_ffn(M, D, F, unfused):
+    err = ffn_case(bb_inputs.make_ffn(M, D, F, seed=M + D + F), 1e-6, variant=bb.VARIANT_SNAPSHOT1, unfused=unfused)
+    assert err <= TOL
+
+
+@pytest.mark.parametrize("M,D,N", [(256, 192, 512), (256, 256, 512), (128, 64, 256), (128, 128, 768), (384, 448, 256)])
+@pytest.mark.parametrize("unfused", [False, True])
+def test_complete_tiles_and_step_parities_ln(M, D, N, unfused):
+    cpu = bb_inputs.make_ln(M, D, N, seed=M + D + N)
+    Y = bb.bb_layernorm_matmul(*dev(cpu), 1e-5, unfused=unfused)
+    torch.cuda.synchronize()
+    ref = orc.layernorm_matmul(*cpu, 1e-5)
+    assert row_rel_err(Y, ref) <= TOL
+
+
 # ------------------------------------------------------------ full-size configs
 def test_c2_decode_full():
     c = bb_inputs.CONFIGS["c2"]
