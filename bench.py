@@ -189,7 +189,13 @@ def calibrate(torch, bb):
     ms_c = t(lambda: bb.bb_calib_copy(buf[:half], buf[half:]), 5)
     iters, wgs = 4000, 1024
     ms_m = t(lambda: bb.bb_calib_mfma(wgs, iters, sink), 3)
-    return {"read_gbs": buf.numel() / (ms_r * 1e-3) / 1e9,
+    # the same matrix-instruction stream on random N(0,1) operands: the clock the chip sustains
+    # depends on the operand data, so this is the rate attainable on real data
+    g = torch.Generator(device="cpu"); g.manual_seed(1)
+    ops = torch.randn(16384, generator=g).to(torch.bfloat16).cuda()
+    ms_d = t(lambda: bb.bb_calib_mfma_data(ops, wgs, iters, sink), 3)
+    return {"mfma_bf16_tflops_random_operands": wgs * 4 * iters * 16 * 32768.0 / (ms_d * 1e-3) / 1e12,
+            "read_gbs": buf.numel() / (ms_r * 1e-3) / 1e9,
             "copy_gbs_read_plus_write": 2 * half / (ms_c * 1e-3) / 1e9,
             "mfma_bf16_tflops": wgs * 4 * iters * 16 * 32768.0 / (ms_m * 1e-3) / 1e12}
 

@@ -120,7 +120,8 @@ int bb_rmsnorm_swiglu_ffn(const void* X, const void* g, const void* W1,
  * D and N positive multiples of 8, M >= 0.  The one-pass variance
  * sum(x^2)/D - mean^2 is evaluated in fp32: rows whose |mean|/std exceeds a
  * few hundred lose accuracy.  Workspace: bb_workspace_bytes(
- * BB_OP_LAYERNORM_MATMUL, M, D, N) (two fp32 vectors of length N).
+ * BB_OP_LAYERNORM_MATMUL, M, D, N) (fp32 column vectors of length N and their
+ * partial sums).
  */
 int bb_layernorm_matmul(const void* X, const void* gamma, const void* beta,
                         const void* W, void* Y, int64_t M, int64_t D,
@@ -195,10 +196,16 @@ int bb_profile_get(int i, float* ms, const char** name);
  *                 32x32x16 matrix instructions on register operands; `sink`
  *                 (>= 64 floats) is only there to keep the work alive.  Flops
  *                 issued = workgroups * 4 waves * iters * 16 * 32768.
+ * bb_calib_mfma_data: the same instruction stream with operands read from
+ *                 `operands` (device, 16-byte aligned, 32 KiB of bf16 values):
+ *                 with random real-valued operands the matrix cores draw more
+ *                 power than with constants and the clock drops, so this is
+ *                 the rate attainable on real data.
  */
 int bb_calib_copy(const void* src, void* dst, size_t bytes, void* stream);
 int bb_calib_read(const void* src, size_t bytes, void* sink, void* stream);
 int bb_calib_mfma(int workgroups, int iters, void* sink, void* stream);
+int bb_calib_mfma_data(const void* operands, int workgroups, int iters, void* sink, void* stream);
 
 #ifdef __cplusplus
 }

@@ -23,7 +23,7 @@ EXPORTS = [
     "bb_rmsnorm_swiglu_ffn_unfused", "bb_layernorm_matmul_unfused",
     "bb_workspace_bytes", "bb_set_workspace", "bb_set_variant", "bb_get_variant",
     "bb_shutdown", "bb_status_string", "bb_version", "bb_last_hip_error",
-    "bb_calib_copy", "bb_calib_read", "bb_calib_mfma",
+    "bb_calib_copy", "bb_calib_read", "bb_calib_mfma", "bb_calib_mfma_data",
     "bb_profile_enable", "bb_profile_count", "bb_profile_get",
 ]
 
@@ -59,6 +59,7 @@ def load() -> ctypes.CDLL:
     lib.bb_calib_copy.argtypes = [vp, vp, sz, vp]
     lib.bb_calib_read.argtypes = [vp, sz, vp, vp]
     lib.bb_calib_mfma.argtypes = [ci, ci, vp, vp]
+    lib.bb_calib_mfma_data.argtypes = [vp, ci, ci, vp, vp]
     lib.bb_profile_enable.argtypes = [ci]
     lib.bb_profile_get.argtypes = [ci, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_char_p)]
     for name in EXPORTS:
@@ -171,6 +172,11 @@ def bb_calib_read(src, sink) -> None:
 
 def bb_calib_mfma(workgroups: int, iters: int, sink) -> None:
     _check(load().bb_calib_mfma(int(workgroups), int(iters), _ptr(sink), _stream()), "bb_calib_mfma")
+
+
+def bb_calib_mfma_data(operands, workgroups: int, iters: int, sink) -> None:
+    _check(load().bb_calib_mfma_data(_ptr(operands), int(workgroups), int(iters), _ptr(sink), _stream()),
+           "bb_calib_mfma_data")
 
 
 def bb_profile_enable(on: bool) -> None:

@@ -559,4 +559,16 @@ int bb_calib_mfma(int workgroups, int iters, void* sink, void* stream) {
     return BB_OK;
 }
 
+int bb_calib_mfma_data(const void* operands, int workgroups, int iters, void* sink, void* stream) {
+    if (!sink || !operands) return BB_ERR_NULL;
+    if (misaligned(operands) || misaligned(sink)) return BB_ERR_ALIGN;
+    if (workgroups <= 0 || iters <= 0 || workgroups > 65536 || iters > (1 << 22)) return BB_ERR_SHAPE;
+    const DeviceInfo* dev = nullptr;
+    if (int rc = current_device_info(&dev)) return rc;
+    hipLaunchKernelGGL(calib_mfma_data_kernel, dim3(workgroups), dim3(256), 0, as_stream(stream),
+                       (const u32x4*)operands, (float*)sink, iters);
+    BB_HIP(hipGetLastError());
+    return BB_OK;
+}
+
 }  // extern "C"

@@ -201,4 +201,30 @@ __global__ __launch_bounds__(256) void calib_mfma_kernel(float* sink, int iters)
     if (s == -1.f) sink[threadIdx.x & 63] = s;
 }
 
+// Same instruction stream, but the operands come from memory (lane t takes the
+// 16-byte chunks t, t + 256, ... of `src`, 8 chunks in all): with real-valued
+// random operands the matrix cores draw more power than with constants and the
+// chip lowers its clock, so this is the attainable rate for real data.
+__global__ __launch_bounds__(256) void calib_mfma_data_kernel(const u32x4* src, float* sink, int iters) {
+    Chunk a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { a[i].u = src[threadIdx.x + 256 * i]; b[i].u = src[threadIdx.x + 256 * (i + 4)]; }
+    f32x16 acc[16];
+#pragma unroll
+    for (int s = 0; s < 16; ++s)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[s][v] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < 16; ++s)
+            acc[s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s & 3].v, b[s >> 2].v, acc[s], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s += acc[k][v];
+    if (s == -1.f) sink[threadIdx.x & 63] = s;
+}
+
 }  // namespace bb

@@ -114,3 +114,6 @@ def test_calibration_argument_errors(lib):
     assert lib.bb_calib_copy(A, A + 512, 1024, None) == -5
     assert lib.bb_calib_read(A, 1024, None, None) == -1
     assert lib.bb_calib_mfma(0, 10, A, None) == -2
+    assert lib.bb_calib_mfma_data(None, 4, 10, A, None) == -1
+    assert lib.bb_calib_mfma_data(A + 8, 4, 10, A, None) == -3
+    assert lib.bb_calib_mfma_data(A, 4, 0, A, None) == -2
