@@ -258,7 +258,9 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
     if (log_on())
         std::fprintf(stderr, "[bb] gemm mode %d BM %d M %d N %d K %d tiles %dx%d\n", MODE, BM, M, N, K,
                      a.tiles_m, a.tiles_n);
-    const bool full = (M % BM == 0) && (N % ncol == 0) && (K % GEMM_BK == 0);
+    // complete tiles, and operands small enough for the kernels' 32-bit byte offsets
+    const bool small = (size_t)M * lda * 2 < (1ull << 32) && (size_t)K * ldb * 2 < (1ull << 32);
+    const bool full = (M % BM == 0) && (N % ncol == 0) && (K % GEMM_BK == 0) && small;
     const bool odd = (((K + GEMM_BK - 1) / GEMM_BK) & 1) != 0;
 #define BB_GEMM_LAUNCH(BM_, FULL_, ODD_) \
     hipLaunchKernelGGL((gemm_kernel<MODE, BM_, FULL_, ODD_>), grid, block, 0, st, a)

@@ -119,7 +119,8 @@ __device__ __forceinline__ void quad_transpose(u32& d0, u32& d1, bool upper, u32
 }
 
 // FULL: every tile is complete (M % BM == 0, N % columns-per-tile == 0,
-// K % 64 == 0), so the main loop has no bounds checks.
+// K % 64 == 0) and A and B are smaller than 4 GiB each, so the main loop has no
+// bounds checks and addresses its loads with 32-bit offsets.
 // ODD: the number of contraction steps ceil(K / 64) is odd.
 template <int MODE, int BM, bool FULL, bool ODD>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
@@ -146,10 +147,27 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     const int tm = lin % p.tiles_m, tn = lin / p.tiles_m;
     const int m0 = tm * BM, n0 = tn * NCOL;
 
-    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int t = threadIdx.x, lane = t & 63;
+    const int w = __builtin_amdgcn_readfirstlane(t >> 6);        // in a scalar register: what is built from it stays scalar
     const int wm = w / WN, wn = w % WN;
+    constexpr int kt0 = 0;
     const int l32 = lane & 31, lhi = lane >> 5;
     const u16* const zsrc = reinterpret_cast<const u16*>(&gemm_zero_chunk);
+
+    // Source addresses of the load-to-LDS instructions.  With FULL set (complete
+    // tiles, and every operand smaller than 4 GiB) an address is the matrix
+    // pointer (a kernel argument, in scalar registers) plus a 32-bit byte
+    // offset = a wavefront-uniform part (scalar arithmetic) + a lane constant:
+    // one 32-bit vector add per instruction.  Otherwise the offset is 64-bit and
+    // lanes outside the matrix read the zero chunk instead.
+    auto src_of = [&](const u16* base, size_t uniform_elems, u32 lane_elems, bool ok) -> const void* {
+        if (FULL) {
+            const u32 off = (u32)uniform_elems * 2u + lane_elems * 2u;
+            return reinterpret_cast<const char*>(base) + off;
+        }
+        const u16* g = base + uniform_elems + lane_elems;
+        return ok ? g : zsrc;
+    };
 
     // ---- A: load-to-LDS role.  One instruction fills 64 chunks = 8 tile rows,
     // lane i -> chunk position i % 8 of row i / 8 (+ 8 per instruction), which
@@ -157,44 +175,44 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     // and odd instructions.  Wavefront w issues row groups w ADMA .. w ADMA + ADMA-1.
     const int rowA = 8 * ADMA * w + (lane >> 3);                 // + 8 j for instruction j
     int kcA[2];
-    const u16* Alane[2];
+    u32 laneA[2];
 #pragma unroll
     for (int o = 0; o < 2; ++o) {
         kcA[o] = (lane & 7) ^ (((rowA + 8 * o) >> 1) & 7);
-        Alane[o] = p.A + (size_t)(m0 + rowA) * p.lda + 8 * kcA[o];
+        laneA[o] = (u32)((lane >> 3) * p.lda + 8 * kcA[o]);
     }
 
-    // ---- B: load-to-LDS role.  One instruction fills 1 KiB = two tile rows,
-    // lane i -> byte 16 i.  Wavefront w issues row pairs w, w+4, ..., w+28; this
-    // lane therefore always serves tile rows = 2 w + lhi (mod 8) and chunk
-    // position l32, which holds source chunk l32 ^ 4 (row & 3).  Source chunk c
-    // of a tile row is columns n0 + 8 c; in GATEUP chunks 0..15 are W1's 128
-    // columns and chunks 16..31 are W3's, so that subtiles tt and tt + 4 of the
-    // (single-column) wavefront tile are the gate and the up product of the
-    // same hidden units.
-    const int rowB = 2 * w + lhi;
-    const int chunkB = l32 ^ ((rowB & 3) << 2);
-    const u16* Bsrc = p.B0;
-    int colB;
-    if (MODE == MODE_GATEUP) {
-        if (chunkB >> 4) Bsrc = p.B1;
-        colB = n0 + 8 * (chunkB & 15);
-    } else {
-        colB = n0 + 8 * chunkB;
-    }
+    // ---- B: load-to-LDS role.
+    // PLAIN, LN: the LDS tile is [64 rows][32 chunks]; one instruction fills two
+    // rows, lane i -> byte 16 i.  Wavefront w issues row pairs w, w+4, ..., w+28,
+    // so this lane always serves tile rows = 2 w + lhi (mod 8) and chunk position
+    // l32, which holds source chunk l32 ^ 4 (row % 4) = columns n0 + 8 chunk.
+    // GATEUP: the LDS tile is two half tiles [W1 | W3][64 rows][16 chunks] (the
+    // 128 columns of W1, then the same 128 of W3), so that one instruction reads
+    // one matrix only: it fills four rows of a half tile, lane i -> row i / 16,
+    // chunk position i % 16, which holds source chunk (i % 16) ^ 4 (row % 4).
+    // Instructions 0..3 of a wavefront serve W1, 4..7 W3, row groups
+    // 4 (q % 4) + w.  Subtiles tt and tt + 4 of the (single-column) wavefront
+    // tile are then the gate and the up product of the same hidden units.
+    constexpr bool HALF = (MODE == MODE_GATEUP);
+    const int rowBl = HALF ? (lane >> 4) : lhi;                  // row of this lane within an instruction
+    const int chunkB = HALF ? ((lane & 15) ^ ((lane >> 4) << 2)) : (l32 ^ (((2 * w + lhi) & 3) << 2));
+    const int colB = n0 + 8 * chunkB;
     const bool colB_ok = FULL || colB < p.N;
-    const u16* const Blane = Bsrc + (size_t)rowB * p.ldb + (colB_ok ? colB : 0);
+    const u32 laneB = (u32)(rowBl * p.ldb + (colB_ok ? 8 * chunkB : 0));
 
     // ---- B: fragment-read role.  Group b = lane / 16 of a transposing read
     // covers contraction rows 8 (b / 2) + 4 h + (0..3) (+ 16 per matrix
     // instruction) and columns 32 tt + 16 (b % 2) + (0..15) of the wavefront's
     // columns; lane i' = lane % 16 supplies the address of row i' / 4, 4-column
     // piece i' % 4.  The 32 lanes served together read 4 rows x 64 bytes; rows
-    // are 512 bytes apart, i.e. on the same banks, so the 16-byte chunk index is
-    // XOR-swizzled with 4 (row % 4): the four rows then take the four 64-byte
-    // quarters of the 256-byte bank line.  The XOR touches the chunk bits that
-    // tt % 4 occupies, hence one byte offset per tt % 4 (tt / 4 is a plain
-    // displacement).
+    // are a multiple of 256 bytes apart, i.e. on the same banks, so the 16-byte
+    // chunk index is XOR-swizzled with 4 (row % 4): the four rows then take the
+    // four 64-byte quarters of the 256-byte bank line.  The XOR touches the
+    // chunk bits that tt % 4 occupies, hence one byte offset per tt % 4 (tt / 4
+    // is a plain displacement: 256 bytes, or the other half tile).
+    constexpr int BROW = HALF ? 256 : 512;                       // bytes per LDS tile row
+    constexpr int BTT4 = HALF ? 64 * 256 : 256;                  // displacement of subtile tt + 4
     int offB[4];
     {
         const int b = lane >> 4, ip = lane & 15;
@@ -202,40 +220,46 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
         const int piece = ip & 3;
 #pragma unroll
         for (int o = 0; o < 4; ++o) {
-            const int chunk = (WC / 8) * wn + 4 * o + 2 * (b & 1) + (piece >> 1);
-            offB[o] = r * 512 + ((chunk ^ ((r & 3) << 2)) << 4) + 8 * (piece & 1);
+            const int chunk = (HALF ? 0 : (WC / 8) * wn) + 4 * o + 2 * (b & 1) + (piece >> 1);
+            offB[o] = r * BROW + ((chunk ^ ((r & 3) << 2)) << 4) + 8 * (piece & 1);
         }
     }
 
     // Quarter `part` (0..3) of the load-to-LDS instructions of B tile kt (8 per
     // wavefront and tile) into LDS array dB
     auto dma_b = [&](int kt, u32x4* dB, int part) {
-        const int k0 = kt * GEMM_BK;
-        const u16* srcB = Blane + (size_t)k0 * p.ldb;
+        const int k0 = (kt0 + kt) * GEMM_BK;
 #pragma unroll
         for (int qq = 0; qq < 2; ++qq) {
             const int q = 2 * part + qq;
-            const u16* g = srcB + (size_t)(8 * q) * p.ldb;
-            if (!FULL) g = (colB_ok && k0 + 8 * q + rowB < p.K) ? g : zsrc;
-            load_to_lds16(g, dB + (w + 4 * q) * 64);
+            if (HALF) {
+                const int rg = 4 * (q & 3) + w;                      // four-row group of the half tile
+                const u16* base = (q >> 2) ? p.B1 : p.B0;
+                const void* g = src_of(base, (size_t)(k0 + 4 * rg) * p.ldb + n0, laneB,
+                                       colB_ok && k0 + 4 * rg + rowBl < p.K);
+                load_to_lds16(g, dB + (q >> 2) * 1024 + rg * 64);
+            } else {
+                const int rp = w + 4 * q;                            // row pair of the tile
+                const void* g = src_of(p.B0, (size_t)(k0 + 2 * rp) * p.ldb + n0, laneB,
+                                       colB_ok && k0 + 2 * rp + rowBl < p.K);
+                load_to_lds16(g, dB + rp * 64);
+            }
         }
     };
     // Quarter `part` of A tile kt (ADMA instructions per wavefront and tile)
     // into dA; the last quarter also brings the gain chunks into dG (every
     // wavefront writes the same bytes there: no branch in the step)
     auto dma_a = [&](int kt, u32x4* dA, u32x4* dG, int part) {
-        const int k0 = kt * GEMM_BK;
+        const int k0 = (kt0 + kt) * GEMM_BK;
 #pragma unroll
         for (int jj = 0; jj < ADMA / 4; ++jj) {
             const int j = (ADMA / 4) * part + jj;
-            const u16* g = Alane[j & 1] + k0 + (size_t)(8 * j) * p.lda;
-            if (!FULL) g = (k0 + 8 * kcA[j & 1] < p.K && m0 + rowA + 8 * j < p.M) ? g : zsrc;
+            const void* g = src_of(p.A, (size_t)(m0 + 8 * ADMA * w + 8 * j) * p.lda + k0, laneA[j & 1],
+                                   k0 + 8 * kcA[j & 1] < p.K && m0 + rowA + 8 * j < p.M);
             load_to_lds16(g, dA + (ADMA * w + j) * 64);
         }
         if (MODE != MODE_PLAIN && part == 3) {
-            const int kg = k0 + 8 * (lane & 7);
-            const u16* g = p.gain + kg;
-            if (!FULL) g = (kg < p.K) ? g : zsrc;
+            const void* g = src_of(p.gain, (size_t)k0, (u32)(8 * (lane & 7)), k0 + 8 * (lane & 7) < p.K);
             load_to_lds16(g, dG);
         }
     };
@@ -270,9 +294,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
         if (MODE != MODE_PLAIN) fg[S].u = bufG[kc];
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt) {
-            const char* q = reinterpret_cast<const char*>(PB ? sB1 : sB0) + offB[tt & 3] + ks * (16 * 512) + 256 * (tt >> 2);
+            const char* q = reinterpret_cast<const char*>(PB ? sB1 : sB0) + offB[tt & 3] + ks * (16 * BROW) + BTT4 * (tt >> 2);
             const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(q));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(q + 4 * 512));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(q + 4 * BROW));
             u32x2 l2 = *reinterpret_cast<const u32x2*>(&lo), h2 = *reinterpret_cast<const u32x2*>(&hi);
             fb[S][tt].u = u32x4{l2[0], l2[1], h2[0], h2[1]};
         }
