@@ -54,7 +54,12 @@ typedef enum bb_status {
  *                      GEMM (sum x^2 and both products from one pass over X,
  *                      inverse norm after the dots, Swish*gate epilogue)
  *                      writes the hidden once as bf16 to the workspace; a
- *                      second GEMM contracts it with W2.  Two launches.
+ *                      second GEMM contracts it with W2.  Two launches.  With
+ *                      few rows (fewer output tiles than half the compute
+ *                      units) either contraction is split over several
+ *                      workgroups per tile, whose fp32 partial results a small
+ *                      kernel adds in fixed order before the epilogue (Rule 3's
+ *                      parallel reduction without atomics): up to four launches.
  * BB_VARIANT_STREAM    bandwidth-bound form for M <= 16 rows.  One persistent
  *                      kernel (one workgroup per compute unit, all resident)
  *                      streams W1, W3 and then W2 exactly once; both

@@ -187,6 +187,32 @@ StreamPlan stream_plan(int64_t D, int64_t F, int G) {
 
 constexpr int kPlanCUs = 256;   // workgroups assumed by bb_workspace_bytes (one per compute unit of an MI355X)
 
+// Split contraction: with fewer 128-row tiles than half the compute units (few
+// rows), nsplit workgroups share a tile's contraction range.  Returns nsplit
+// (1 = no split) and the steps per workgroup.
+int plan_split(int mode, int M, int N, int K, int cus, int* nk_split) {
+    const int ncol = (mode == MODE_GATEUP) ? 128 : 256;
+    const int tiles = ((M + 127) / 128) * ((N + ncol - 1) / ncol);
+    const int nk = (K + GEMM_BK - 1) / GEMM_BK;
+    *nk_split = nk;
+    if (mode == MODE_LN || tiles * 2 > cus) return 1;
+    int S = std::min(std::min(cus / tiles, 16), nk / 4);     // at least four steps per workgroup
+    if (S < 2) return 1;
+    const int per = (nk + S - 1) / S;
+    S = (nk + per - 1) / per;                                // no workgroup without a step
+    *nk_split = per;
+    return S;
+}
+// bytes of partial results a split launch of this shape needs (0 = not split)
+size_t split_bytes(int mode, int64_t M, int64_t N, int64_t K, int cus) {
+    int per = 0;
+    const int S = plan_split(mode, (int)M, (int)N, (int)K, cus, &per);
+    if (S < 2) return 0;
+    const size_t cols = (mode == MODE_GATEUP) ? 2 * (size_t)N : (size_t)N;
+    return align_up((size_t)S * M * cols * 4) + align_up((size_t)S * M * 4);
+}
+
+
 size_t zone_bytes(int op, int64_t M, int64_t D, int64_t F) {
     if (op == BB_OP_RMSNORM_SWIGLU_FFN && M <= kStreamMaxM) return stream_plan(D, F, kPlanCUs).total_bytes;
     return 0;
@@ -194,9 +220,14 @@ size_t zone_bytes(int op, int64_t M, int64_t D, int64_t F) {
 
 size_t scratch_bytes(int op, int64_t M, int64_t D, int64_t F) {
     switch (op) {
-        case BB_OP_RMSNORM_SWIGLU_FFN: return align_up((size_t)M * F * 2);
+        // (the FFN ops end with room for the partial results of a split contraction)
+        case BB_OP_RMSNORM_SWIGLU_FFN:
+            return align_up((size_t)M * F * 2) +
+                   std::max(split_bytes(MODE_GATEUP, M, F, D, kPlanCUs), split_bytes(MODE_PLAIN, M, D, F, kPlanCUs));
         case BB_OP_LAYERNORM_MATMUL: return (2 + 2 * COLVEC_SPLITS) * align_up((size_t)F * 4);
-        case BB_OP_RMSNORM_SWIGLU_FFN_UNFUSED: return align_up((size_t)M * D * 2) + 3 * align_up((size_t)M * F * 2);
+        case BB_OP_RMSNORM_SWIGLU_FFN_UNFUSED:
+            return align_up((size_t)M * D * 2) + 3 * align_up((size_t)M * F * 2) +
+                   std::max(split_bytes(MODE_PLAIN, M, F, D, kPlanCUs), split_bytes(MODE_PLAIN, M, D, F, kPlanCUs));
         case BB_OP_LAYERNORM_MATMUL_UNFUSED: return align_up((size_t)M * D * 2);
         default: return 0;
     }
@@ -239,32 +270,52 @@ void mark_dirty(size_t off) {
 }
 
 // ------------------------------------------------------------------- launches
+// `split`: device scratch of split_bytes(...) for this launch, or nullptr (never split)
 template <int MODE>
 int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u16* C, int ldc,
                 const u16* gain, const float* colc, const float* colb, int M, int N, int K, float eps,
-                int cus, hipStream_t st) {
+                int cus, hipStream_t st, void* split = nullptr) {
     GemmArgs a;
+    a.nsplit = 1; a.nk_split = 0; a.ldp = 0; a.part = nullptr; a.ssqpart = nullptr;
     a.A = A; a.B0 = B0; a.B1 = B1; a.C = C; a.gain = gain; a.colc = colc; a.colb = colb;
     a.M = M; a.N = N; a.K = K; a.lda = lda; a.ldb = ldb; a.ldc = ldc; a.eps = eps;
     const int ncol = (MODE == MODE_GATEUP) ? 128 : 256;
     a.tiles_n = (N + ncol - 1) / ncol;
     const int tiles256 = ((M + 255) / 256) * a.tiles_n;
-    const bool big = tiles256 >= cus;
+    int nk_split = 0;
+    const int nsplit = split ? plan_split(MODE, M, N, K, cus, &nk_split) : 1;
+    const bool do_split = nsplit >= 2;
+    const bool big = !do_split && tiles256 >= cus;
     const int BM = big ? 256 : 128;
     a.tiles_m = (M + BM - 1) / BM;
     const int tiles = a.tiles_m * a.tiles_n;
-    a.tiles_per_xcd = (tiles + 7) / 8;
+    if (do_split) {
+        a.nsplit = nsplit;
+        a.nk_split = nk_split;
+        a.ldp = (MODE == MODE_GATEUP) ? 2 * N : N;
+        a.part = (float*)split;
+        a.ssqpart = (float*)((char*)split + align_up((size_t)nsplit * M * a.ldp * 4));
+    }
+    a.tiles_per_xcd = (tiles * a.nsplit + 7) / 8;
     const dim3 grid(8 * a.tiles_per_xcd), block(GEMM_THREADS);
     if (log_on())
-        std::fprintf(stderr, "[bb] gemm mode %d BM %d M %d N %d K %d tiles %dx%d\n", MODE, BM, M, N, K,
-                     a.tiles_m, a.tiles_n);
+        std::fprintf(stderr, "[bb] gemm mode %d BM %d M %d N %d K %d tiles %dx%d split %d x %d steps\n", MODE, BM,
+                     M, N, K, a.tiles_m, a.tiles_n, a.nsplit, do_split ? nk_split : (K + GEMM_BK - 1) / GEMM_BK);
     // complete tiles, and operands small enough for the kernels' 32-bit byte offsets
     const bool small = (size_t)M * lda * 2 < (1ull << 32) && (size_t)K * ldb * 2 < (1ull << 32);
     const bool full = (M % BM == 0) && (N % ncol == 0) && (K % GEMM_BK == 0) && small;
-    const bool odd = (((K + GEMM_BK - 1) / GEMM_BK) & 1) != 0;
+    const bool odd = ((do_split ? nk_split : (K + GEMM_BK - 1) / GEMM_BK) & 1) != 0;
 #define BB_GEMM_LAUNCH(BM_, FULL_, ODD_) \
     hipLaunchKernelGGL((gemm_kernel<MODE, BM_, FULL_, ODD_>), grid, block, 0, st, a)
-    if (big) {
+    if (do_split) {
+        constexpr int SM = (MODE == MODE_LN) ? MODE_PLAIN : MODE;     // (LN is never split)
+        if (odd) hipLaunchKernelGGL((gemm_kernel<SM, 128, false, true, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((gemm_kernel<SM, 128, false, false, true>), grid, block, 0, st, a);
+        BB_HIP(hipGetLastError());
+        const size_t threads = (size_t)M * (N / 8);
+        hipLaunchKernelGGL((splitk_reduce_kernel<SM>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                           (const float*)a.part, (const float*)a.ssqpart, C, M, N, K, a.ldp, ldc, nsplit, eps);
+    } else if (big) {
         if (full) { if (odd) BB_GEMM_LAUNCH(256, true, true); else BB_GEMM_LAUNCH(256, true, false); }
         else      { if (odd) BB_GEMM_LAUNCH(256, false, true); else BB_GEMM_LAUNCH(256, false, false); }
     } else {
@@ -407,13 +458,15 @@ int bb_rmsnorm_swiglu_ffn(const void* X, const void* g, const void* W1, const vo
         return run_stream(x, gg, w1, w3, w2, (u16*)Y, (int)M, (int)D, (int)F, eps, dev->cus, st);
     // first snapshot: hidden written once (bf16), then contracted with W2
     u16* H = (u16*)((char*)g_ws.ptr + zone);
+    void* split = (char*)H + align_up((size_t)M * F * 2);
+    const int pcus = std::min(dev->cus, kPlanCUs);          // (the workspace was sized for this many)
     mark_dirty(zone);
     prof_begin(st);
     if (int rc = launch_gemm<MODE_GATEUP>(x, (int)D, w1, w3, (int)F, H, (int)F, gg, nullptr, nullptr, (int)M,
-                                          (int)F, (int)D, eps, dev->cus, st))
+                                          (int)F, (int)D, eps, pcus, st, split))
         return rc;
     return launch_gemm<MODE_PLAIN>(H, (int)F, w2, nullptr, (int)D, (u16*)Y, (int)D, nullptr, nullptr, nullptr,
-                                   (int)M, (int)D, (int)F, 0.f, dev->cus, st);
+                                   (int)M, (int)D, (int)F, 0.f, pcus, st, split);
 }
 
 int bb_layernorm_matmul(const void* X, const void* gamma, const void* beta, const void* W, void* Y,
@@ -458,16 +511,18 @@ int bb_rmsnorm_swiglu_ffn_unfused(const void* X, const void* g, const void* W1, 
     u16* P = (u16*)(base + align_up((size_t)M * D * 2));
     u16* Q = (u16*)((char*)P + nMF);
     u16* H = (u16*)((char*)Q + nMF);
+    void* split = (char*)H + nMF;
+    const int pcus = std::min(dev->cus, kPlanCUs);
     prof_begin(st);
     hipLaunchKernelGGL(rmsnorm_rows_kernel, dim3((unsigned)M), dim3(256), 0, st, (const u16*)X, (const u16*)g,
                        Xh, (int)D, eps);
     BB_HIP(hipGetLastError());
     prof_mark("rmsnorm_rows", st);
     if (int rc = launch_gemm<MODE_PLAIN>(Xh, (int)D, (const u16*)W1, nullptr, (int)F, P, (int)F, nullptr,
-                                         nullptr, nullptr, (int)M, (int)F, (int)D, 0.f, dev->cus, st))
+                                         nullptr, nullptr, (int)M, (int)F, (int)D, 0.f, pcus, st, split))
         return rc;
     if (int rc = launch_gemm<MODE_PLAIN>(Xh, (int)D, (const u16*)W3, nullptr, (int)F, Q, (int)F, nullptr,
-                                         nullptr, nullptr, (int)M, (int)F, (int)D, 0.f, dev->cus, st))
+                                         nullptr, nullptr, (int)M, (int)F, (int)D, 0.f, pcus, st, split))
         return rc;
     const size_t n8 = (size_t)M * F / 8;
     hipLaunchKernelGGL(silu_mul_kernel, dim3((unsigned)std::min<size_t>((n8 + 255) / 256, 4096)), dim3(256), 0,
@@ -475,7 +530,7 @@ int bb_rmsnorm_swiglu_ffn_unfused(const void* X, const void* g, const void* W1, 
     BB_HIP(hipGetLastError());
     prof_mark("silu_mul", st);
     return launch_gemm<MODE_PLAIN>(H, (int)F, (const u16*)W2, nullptr, (int)D, (u16*)Y, (int)D, nullptr,
-                                   nullptr, nullptr, (int)M, (int)D, (int)F, 0.f, dev->cus, st);
+                                   nullptr, nullptr, (int)M, (int)D, (int)F, 0.f, pcus, st, split);
 }
 
 int bb_layernorm_matmul_unfused(const void* X, const void* gamma, const void* beta, const void* W, void* Y,

@@ -75,6 +75,13 @@ struct GemmArgs {
     int lda, ldb, ldc;
     int tiles_m, tiles_n, tiles_per_xcd;
     float eps;
+    // split contraction (SPLIT kernels): `nsplit` workgroups per tile, each with
+    // `nk_split` contraction steps; fp32 partial results part[split][M][ldp]
+    // (GATEUP: columns [0,N) the W1 product, [N,2N) the W3 product) and the
+    // partial sums of squares ssqpart[split][M]
+    int nsplit, nk_split, ldp;
+    float* part;
+    float* ssqpart;
 };
 
 constexpr int GEMM_THREADS = 256;
@@ -121,8 +128,16 @@ __device__ __forceinline__ void quad_transpose(u32& d0, u32& d1, bool upper, u32
 // FULL: every tile is complete (M % BM == 0, N % columns-per-tile == 0,
 // K % 64 == 0) and A and B are smaller than 4 GiB each, so the main loop has no
 // bounds checks and addresses its loads with 32-bit offsets.
-// ODD: the number of contraction steps ceil(K / 64) is odd.
-template <int MODE, int BM, bool FULL, bool ODD>
+// ODD: the number of contraction steps of a workgroup is odd.
+// SPLIT (PLAIN, GATEUP; for shapes with fewer tiles than half the compute
+// units, i.e. few rows): nsplit workgroups share a tile, each contracts
+// nk_split steps of the contraction range (steps past the end load zeros, so
+// SPLIT kernels are built with FULL = false) and stores its fp32 accumulators
+// (GATEUP: and its partial row sums of squares) instead of running the
+// epilogue; splitk_reduce_kernel adds the partial results in fixed order and
+// applies the epilogue.  This is Rule 3's parallel reduction over the
+// contraction blocks, with per-workgroup partial results instead of atomics.
+template <int MODE, int BM, bool FULL, bool ODD, bool SPLIT = false>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     constexpr int WM = (MODE == MODE_PLAIN) ? 2 : 4;   // wavefronts along the rows
     constexpr int WN = 4 / WM;                          // and along the columns
@@ -143,14 +158,16 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     // share B columns and A rows in that XCD's L2.
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
     const int lin = xcd * p.tiles_per_xcd + local;
-    if (local >= p.tiles_per_xcd || lin >= p.tiles_m * p.tiles_n) return;
-    const int tm = lin % p.tiles_m, tn = lin / p.tiles_m;
+    const int ntiles = p.tiles_m * p.tiles_n;
+    if (local >= p.tiles_per_xcd || lin >= (SPLIT ? ntiles * p.nsplit : ntiles)) return;
+    const int tile = SPLIT ? lin % ntiles : lin, split = SPLIT ? lin / ntiles : 0;
+    const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
+    const int kt0 = SPLIT ? split * p.nk_split : 0;           // first contraction step of this workgroup
     const int m0 = tm * BM, n0 = tn * NCOL;
 
     const int t = threadIdx.x, lane = t & 63;
     const int w = __builtin_amdgcn_readfirstlane(t >> 6);        // in a scalar register: what is built from it stays scalar
     const int wm = w / WN, wn = w % WN;
-    constexpr int kt0 = 0;
     const int l32 = lane & 31, lhi = lane >> 5;
     const u16* const zsrc = reinterpret_cast<const u16*>(&gemm_zero_chunk);
 
@@ -281,7 +298,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     using C0 = std::integral_constant<int, 0>;
     using C1 = std::integral_constant<int, 1>;
 
-    const int nk = (p.K + GEMM_BK - 1) / GEMM_BK;
+    const int nk = SPLIT ? p.nk_split : (p.K + GEMM_BK - 1) / GEMM_BK;    // steps of this workgroup
 
     // fragments of contraction slice ks (16 indices) of one LDS buffer set
     Chunk fa[2][MT], fb[2][NT], fg[2];
@@ -468,6 +485,35 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
         }
     }
 
+    // ---- split contraction: store the partial results, no epilogue
+    if (SPLIT) {
+        static_assert(!SPLIT || (MODE != MODE_LN && !FULL), "split kernels: PLAIN or GATEUP, with bounds checks");
+        float* const part = p.part + (size_t)split * p.M * p.ldp;
+#pragma unroll
+        for (int s = 0; s < MT; ++s)
+#pragma unroll
+            for (int tt = 0; tt < NT; ++tt) {
+                // GATEUP: subtiles 0..3 are the W1 product of hidden units n0 + 32 tt + l32, 4..7 the W3 product
+                const int col = (MODE == MODE_GATEUP) ? n0 + 32 * (tt & 3) + l32 : n0 + WC * wn + 32 * tt + l32;
+                const int pcol = (MODE == MODE_GATEUP && tt >= 4) ? p.N + col : col;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + WR * wm + 32 * s + 8 * (v >> 2) + 4 * lhi + (v & 3);
+                    if (m < p.M && col < p.N) part[(size_t)m * p.ldp + pcol] = acc[s][tt][v];
+                }
+            }
+        if (MODE == MODE_GATEUP) {
+#pragma unroll
+            for (int s = 0; s < MT; ++s) {
+                const float q2 = ssq[s][0] + ssq[s][1];
+                const float s2 = q2 + __shfl_xor(q2, 32);
+                const int m = m0 + WR * wm + 32 * s + l32;
+                if (lhi == 0 && tn == 0 && m < p.M) p.ssqpart[(size_t)split * p.M + m] = s2;
+            }
+        }
+        return;
+    }
+
     // ---- row statistics: add the two lanes that share a row (lane, lane ^ 32)
     if (MODE != MODE_PLAIN) {
 #pragma unroll
@@ -568,6 +614,43 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
             }
         }
     }
+}
+
+// Adds the nsplit partial results of a split contraction in fixed order and
+// applies the epilogue: PLAIN C = bf16(sum); GATEUP h = SiLU(r P) (r Q) with
+// r = (sum of the partial sums of squares / K + eps)^-1/2.  One thread per row
+// and 8 consecutive output columns.
+template <int MODE>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* part, const float* ssqpart, u16* C,
+                                                            int M, int N, int K, int ldp, int ldc, int nsplit,
+                                                            float eps) {
+    const int groups = N / 8;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)M * groups) return;
+    const int m = (int)(idx / groups), c0 = 8 * (int)(idx % groups);
+    f32x4 a0 = {0, 0, 0, 0}, a1 = a0, b0 = a0, b1 = a0;
+    float s2 = 0.f;
+    for (int sp = 0; sp < nsplit; ++sp) {
+        const float* src = part + ((size_t)sp * M + m) * ldp + c0;
+        a0 += *reinterpret_cast<const f32x4*>(src);
+        a1 += *reinterpret_cast<const f32x4*>(src + 4);
+        if (MODE == MODE_GATEUP) {
+            b0 += *reinterpret_cast<const f32x4*>(src + N);
+            b1 += *reinterpret_cast<const f32x4*>(src + N + 4);
+            s2 += ssqpart[(size_t)sp * M + m];
+        }
+    }
+    u32x4 o;
+    if (MODE == MODE_GATEUP) {
+        const float r = rsqrtf(s2 / (float)K + eps);
+        o = u32x4{pack_bf16(swiglu(r * a0[0], r * b0[0]), swiglu(r * a0[1], r * b0[1])),
+                  pack_bf16(swiglu(r * a0[2], r * b0[2]), swiglu(r * a0[3], r * b0[3])),
+                  pack_bf16(swiglu(r * a1[0], r * b1[0]), swiglu(r * a1[1], r * b1[1])),
+                  pack_bf16(swiglu(r * a1[2], r * b1[2]), swiglu(r * a1[3], r * b1[3]))};
+    } else {
+        o = u32x4{pack_bf16(a0[0], a0[1]), pack_bf16(a0[2], a0[3]), pack_bf16(a1[0], a1[1]), pack_bf16(a1[2], a1[3])};
+    }
+    *reinterpret_cast<u32x4*>(C + (size_t)m * ldc + c0) = o;
 }
 
 }  // namespace bb

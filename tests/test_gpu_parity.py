@@ -186,6 +186,18 @@ def test_complete_tiles_and_step_parities_ln(M, D, N, unfused):
     assert row_rel_err(Y, ref) <= TOL
 
 
+# Few rows, long contractions: fewer tiles than compute units, so the
+# contraction range of a tile is split over several workgroups (fp32 partial
+# results + a reduce kernel), for the gate/up product and for the down product.
+@pytest.mark.parametrize("M,D,F", [(17, 4096, 11008), (48, 4096, 11008), (130, 2048, 5632), (300, 1024, 2816),
+                                   (64, 520, 1416), (33, 264, 2056)])
+def test_split_contraction_few_rows(M, D, F):
+    cpu = bb_inputs.make_ffn(M, D, F, seed=M + 7)
+    assert ffn_case(cpu, 1e-6, variant=bb.VARIANT_SNAPSHOT1) <= TOL
+    if D <= 2048:
+        assert ffn_case(cpu, 1e-6, unfused=True) <= TOL
+
+
 # ------------------------------------------------------------ full-size configs
 def test_c2_decode_full():
     c = bb_inputs.CONFIGS["c2"]
