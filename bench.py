@@ -111,6 +111,28 @@ def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
 
     ms_unfused, _ = timed(True)
 
+    # the same operator through the transposed-weight entry points (W^T layouts), timed the same way
+    ms_transposed = None
+    if not stream_variant:
+        d0 = dev_sets[0]
+        if cfg.op == "ffn":
+            dt = [d0[0], d0[1]] + [w.t().contiguous() for w in d0[2:]]
+            stept = lambda: bb.bb_rmsnorm_swiglu_ffn_t(*dt, cfg.eps, Y=out)
+        else:
+            dt = [d0[0], d0[1], d0[2], d0[3].t().contiguous()]
+            stept = lambda: bb.bb_layernorm_matmul_t(*dt, cfg.eps, Y=out)
+        for _ in range(warmup):
+            stept()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            stept()
+        e1.record()
+        torch.cuda.synchronize()
+        ms_transposed = e0.elapsed_time(e1) / steps
+        del dt
+
     dom, work, bound = dominant_kernel(cfg, stream_variant)
     dom_ms = kernels_ms[dom]
     if bound == "mfma":
@@ -125,6 +147,7 @@ def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
         "gbs": bytes_of(cfg) / (ms_step * 1e-3) / 1e9,
         "kernels_ms": kernels_ms,
         "unfused_ms_per_step": ms_unfused,
+        "transposed_weights_ms_per_step": ms_transposed,
         "roofline": {"kernel": dom, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
                      "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((name, dom)),
                      "algorithmic": work},
@@ -250,6 +273,7 @@ def main():
         "parity": primary.get("parity"),
         "kernels_ms": primary["kernels_ms"],
         "unfused_ms_per_step": primary["unfused_ms_per_step"],
+        "transposed_weights_ms_per_step": primary["transposed_weights_ms_per_step"],
         "measured_peaks": peaks,
     }
     if "c2" in others:

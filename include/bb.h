@@ -133,6 +133,30 @@ int bb_layernorm_matmul(const void* X, const void* gamma, const void* beta,
                         int64_t N, float eps, void* stream);
 
 /* ------------------------------------------------------------------------
+ * The same two operators with the weights given TRANSPOSED, which is the form
+ * the paper's block programs take their inputs in (W^T, V^T, U^T; Section 2.1
+ * says non-row-major inputs are transposed on their way to local memory) and
+ * the layout of linear-layer checkpoints:
+ *
+ *   W1t [F, D], W3t [F, D], W2t [D, F]   with  W1t[f,d] = W1[d,f]  etc.
+ *   Wt  [N, D]                           with  Wt[n,d]  = W[d,n]
+ *
+ * Everything else (arguments, arithmetic, results, workspace of the op without
+ * the suffix, errors) is as for bb_rmsnorm_swiglu_ffn / bb_layernorm_matmul.
+ * The contraction index is contiguous in these layouts, so the weight tiles
+ * need no transposition on chip.  Every M goes through the tiled kernels (for
+ * few rows with the split contraction); the streaming variant takes the
+ * untransposed layout only, and bb_set_variant has no effect here.
+ */
+int bb_rmsnorm_swiglu_ffn_t(const void* X, const void* g, const void* W1t,
+                            const void* W3t, const void* W2t, void* Y,
+                            int64_t M, int64_t D, int64_t F, float eps,
+                            void* stream);
+int bb_layernorm_matmul_t(const void* X, const void* gamma, const void* beta,
+                          const void* Wt, void* Y, int64_t M, int64_t D,
+                          int64_t N, float eps, void* stream);
+
+/* ------------------------------------------------------------------------
  * The UNFUSED block programs (Example 3 / Example 2, initial block programs):
  * one kernel per array operator, every intermediate materialised in global
  * memory.  Built from the same tile primitives; exported so that the cost of

@@ -21,6 +21,7 @@ OP_FFN, OP_LN, OP_FFN_UNFUSED, OP_LN_UNFUSED = 0, 1, 2, 3
 EXPORTS = [
     "bb_rmsnorm_swiglu_ffn", "bb_layernorm_matmul",
     "bb_rmsnorm_swiglu_ffn_unfused", "bb_layernorm_matmul_unfused",
+    "bb_rmsnorm_swiglu_ffn_t", "bb_layernorm_matmul_t",
     "bb_workspace_bytes", "bb_set_workspace", "bb_set_variant", "bb_get_variant",
     "bb_shutdown", "bb_status_string", "bb_version", "bb_last_hip_error",
     "bb_calib_copy", "bb_calib_read", "bb_calib_mfma", "bb_calib_mfma_data",
@@ -48,6 +49,8 @@ def load() -> ctypes.CDLL:
     vp, i64, f32, sz, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t, ctypes.c_int
     lib.bb_rmsnorm_swiglu_ffn.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
     lib.bb_rmsnorm_swiglu_ffn_unfused.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
+    lib.bb_rmsnorm_swiglu_ffn_t.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
+    lib.bb_layernorm_matmul_t.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
     lib.bb_layernorm_matmul.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
     lib.bb_layernorm_matmul_unfused.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
     lib.bb_workspace_bytes.argtypes = [ci, i64, i64, i64]
@@ -110,6 +113,38 @@ def bb_rmsnorm_swiglu_ffn(X, g, W1, W3, W2, eps: float, Y=None, unfused: bool = 
     fn = lib.bb_rmsnorm_swiglu_ffn_unfused if unfused else lib.bb_rmsnorm_swiglu_ffn
     _check(fn(_ptr(X), _ptr(g), _ptr(W1), _ptr(W3), _ptr(W2), _ptr(Y), M, D, F, float(eps), _stream()),
            "bb_rmsnorm_swiglu_ffn" + ("_unfused" if unfused else ""))
+    return Y
+
+
+def bb_rmsnorm_swiglu_ffn_t(X, g, W1t, W3t, W2t, eps: float, Y=None):
+    """The same operator with transposed weights W1t [F,D], W3t [F,D], W2t [D,F].  Returns Y."""
+    import torch
+    lib = load()
+    M, D = X.shape
+    F = W1t.shape[0]
+    _require(X, (M, D), "X"); _require(g, (D,), "g")
+    _require(W1t, (F, D), "W1t"); _require(W3t, (F, D), "W3t"); _require(W2t, (D, F), "W2t")
+    if Y is None:
+        Y = torch.empty((M, D), dtype=torch.bfloat16, device=X.device)
+    _require(Y, (M, D), "Y")
+    _check(lib.bb_rmsnorm_swiglu_ffn_t(_ptr(X), _ptr(g), _ptr(W1t), _ptr(W3t), _ptr(W2t), _ptr(Y), M, D, F,
+                                       float(eps), _stream()), "bb_rmsnorm_swiglu_ffn_t")
+    return Y
+
+
+def bb_layernorm_matmul_t(X, gamma, beta, Wt, eps: float, Y=None):
+    """Y = LN(X; gamma, beta, eps) W with W given transposed, Wt [N,D].  Returns Y."""
+    import torch
+    lib = load()
+    M, D = X.shape
+    N = Wt.shape[0]
+    _require(X, (M, D), "X"); _require(gamma, (D,), "gamma"); _require(beta, (D,), "beta")
+    _require(Wt, (N, D), "Wt")
+    if Y is None:
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device)
+    _require(Y, (M, N), "Y")
+    _check(lib.bb_layernorm_matmul_t(_ptr(X), _ptr(gamma), _ptr(beta), _ptr(Wt), _ptr(Y), M, D, N, float(eps),
+                                     _stream()), "bb_layernorm_matmul_t")
     return Y
 
 

@@ -270,8 +270,9 @@ void mark_dirty(size_t off) {
 }
 
 // ------------------------------------------------------------------- launches
-// `split`: device scratch of split_bytes(...) for this launch, or nullptr (never split)
-template <int MODE>
+// `split`: device scratch of split_bytes(...) for this launch, or nullptr (never split).
+// BT: B0/B1 are given transposed ([N, K] row-major, ldb = K).
+template <int MODE, bool BT = false>
 int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u16* C, int ldc,
                 const u16* gain, const float* colc, const float* colb, int M, int N, int K, float eps,
                 int cus, hipStream_t st, void* split = nullptr) {
@@ -299,30 +300,34 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
     a.tiles_per_xcd = (tiles * a.nsplit + 7) / 8;
     const dim3 grid(8 * a.tiles_per_xcd), block(GEMM_THREADS);
     if (log_on())
-        std::fprintf(stderr, "[bb] gemm mode %d BM %d M %d N %d K %d tiles %dx%d split %d x %d steps\n", MODE, BM,
-                     M, N, K, a.tiles_m, a.tiles_n, a.nsplit, do_split ? nk_split : (K + GEMM_BK - 1) / GEMM_BK);
+        std::fprintf(stderr, "[bb] gemm mode %d%s BM %d M %d N %d K %d tiles %dx%d split %d x %d steps\n", MODE,
+                     BT ? " (B transposed)" : "", BM, M, N, K, a.tiles_m, a.tiles_n, a.nsplit,
+                     do_split ? nk_split : (K + GEMM_BK - 1) / GEMM_BK);
     // complete tiles, and operands small enough for the kernels' 32-bit byte offsets
-    const bool small = (size_t)M * lda * 2 < (1ull << 32) && (size_t)K * ldb * 2 < (1ull << 32);
+    const size_t bbytes = BT ? (size_t)N * ldb * 2 : (size_t)K * ldb * 2;
+    const bool small = (size_t)M * lda * 2 < (1ull << 32) && bbytes < (1ull << 32);
     const bool full = (M % BM == 0) && (N % ncol == 0) && (K % GEMM_BK == 0) && small;
     const bool odd = ((do_split ? nk_split : (K + GEMM_BK - 1) / GEMM_BK) & 1) != 0;
-#define BB_GEMM_LAUNCH(BM_, FULL_, ODD_) \
-    hipLaunchKernelGGL((gemm_kernel<MODE, BM_, FULL_, ODD_>), grid, block, 0, st, a)
+    using T = std::true_type;
+    using F_ = std::false_type;
+    auto go = [&](auto BMc, auto FULLc, auto ODDc) {
+        hipLaunchKernelGGL((gemm_kernel<MODE, decltype(BMc)::value, decltype(FULLc)::value, decltype(ODDc)::value, false, BT>),
+                           grid, block, 0, st, a);
+    };
+    auto go2 = [&](auto BMc, auto FULLc) { if (odd) go(BMc, FULLc, T()); else go(BMc, FULLc, F_()); };
     if (do_split) {
         constexpr int SM = (MODE == MODE_LN) ? MODE_PLAIN : MODE;     // (LN is never split)
-        if (odd) hipLaunchKernelGGL((gemm_kernel<SM, 128, false, true, true>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((gemm_kernel<SM, 128, false, false, true>), grid, block, 0, st, a);
+        if (odd) hipLaunchKernelGGL((gemm_kernel<SM, 128, false, true, true, BT>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((gemm_kernel<SM, 128, false, false, true, BT>), grid, block, 0, st, a);
         BB_HIP(hipGetLastError());
         const size_t threads = (size_t)M * (N / 8);
         hipLaunchKernelGGL((splitk_reduce_kernel<SM>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
                            (const float*)a.part, (const float*)a.ssqpart, C, M, N, K, a.ldp, ldc, nsplit, eps);
     } else if (big) {
-        if (full) { if (odd) BB_GEMM_LAUNCH(256, true, true); else BB_GEMM_LAUNCH(256, true, false); }
-        else      { if (odd) BB_GEMM_LAUNCH(256, false, true); else BB_GEMM_LAUNCH(256, false, false); }
+        if (full) go2(std::integral_constant<int, 256>(), T()); else go2(std::integral_constant<int, 256>(), F_());
     } else {
-        if (full) { if (odd) BB_GEMM_LAUNCH(128, true, true); else BB_GEMM_LAUNCH(128, true, false); }
-        else      { if (odd) BB_GEMM_LAUNCH(128, false, true); else BB_GEMM_LAUNCH(128, false, false); }
+        if (full) go2(std::integral_constant<int, 128>(), T()); else go2(std::integral_constant<int, 128>(), F_());
     }
-#undef BB_GEMM_LAUNCH
     BB_HIP(hipGetLastError());
     prof_mark(MODE == MODE_GATEUP ? "gemm_gateup" : MODE == MODE_LN ? "gemm_ln" : "gemm_plain", st);
     return BB_OK;
@@ -492,6 +497,50 @@ int bb_layernorm_matmul(const void* X, const void* gamma, const void* beta, cons
     prof_mark("colvec", st);
     return launch_gemm<MODE_LN>((const u16*)X, (int)D, (const u16*)W, nullptr, (int)N, (u16*)Y, (int)N,
                                 (const u16*)gamma, colc, colb, (int)M, (int)N, (int)D, eps, dev->cus, st);
+}
+
+int bb_rmsnorm_swiglu_ffn_t(const void* X, const void* g, const void* W1t, const void* W3t, const void* W2t,
+                            void* Y, int64_t M, int64_t D, int64_t F, float eps, void* stream) {
+    if (int rc = validate_ffn(X, g, W1t, W3t, W2t, Y, M, D, F, eps)) return rc;
+    if (M == 0) return BB_OK;
+    std::lock_guard<std::mutex> lk(g_mu);
+    const DeviceInfo* dev = nullptr;
+    if (int rc = current_device_info(&dev)) return rc;
+    const size_t zone = zone_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F);
+    if (int rc = ensure_workspace(zone + scratch_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F))) return rc;
+    hipStream_t st = as_stream(stream);
+    u16* H = (u16*)((char*)g_ws.ptr + zone);
+    void* split = (char*)H + align_up((size_t)M * F * 2);
+    const int pcus = std::min(dev->cus, kPlanCUs);
+    mark_dirty(zone);
+    prof_begin(st);
+    if (int rc = (launch_gemm<MODE_GATEUP, true>((const u16*)X, (int)D, (const u16*)W1t, (const u16*)W3t, (int)D, H,
+                                                 (int)F, (const u16*)g, nullptr, nullptr, (int)M, (int)F, (int)D,
+                                                 eps, pcus, st, split)))
+        return rc;
+    return launch_gemm<MODE_PLAIN, true>(H, (int)F, (const u16*)W2t, nullptr, (int)F, (u16*)Y, (int)D, nullptr,
+                                         nullptr, nullptr, (int)M, (int)D, (int)F, 0.f, pcus, st, split);
+}
+
+int bb_layernorm_matmul_t(const void* X, const void* gamma, const void* beta, const void* Wt, void* Y,
+                          int64_t M, int64_t D, int64_t N, float eps, void* stream) {
+    if (int rc = validate_ln(X, gamma, beta, Wt, Y, M, D, N, eps)) return rc;
+    if (M == 0) return BB_OK;
+    std::lock_guard<std::mutex> lk(g_mu);
+    const DeviceInfo* dev = nullptr;
+    if (int rc = current_device_info(&dev)) return rc;
+    if (int rc = ensure_workspace(scratch_bytes(BB_OP_LAYERNORM_MATMUL, M, D, N))) return rc;
+    hipStream_t st = as_stream(stream);
+    mark_dirty(0);
+    float* colc = (float*)g_ws.ptr;
+    float* colb = (float*)((char*)g_ws.ptr + align_up((size_t)N * 4));
+    prof_begin(st);
+    hipLaunchKernelGGL(colvec_t_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, st, (const u16*)Wt,
+                       (const u16*)gamma, (const u16*)beta, colc, colb, (int)D, (int)N);
+    BB_HIP(hipGetLastError());
+    prof_mark("colvec", st);
+    return launch_gemm<MODE_LN, true>((const u16*)X, (int)D, (const u16*)Wt, nullptr, (int)D, (u16*)Y, (int)N,
+                                      (const u16*)gamma, colc, colb, (int)M, (int)N, (int)D, eps, dev->cus, st);
 }
 
 int bb_rmsnorm_swiglu_ffn_unfused(const void* X, const void* g, const void* W1, const void* W3,

@@ -65,8 +65,8 @@ enum { MODE_PLAIN = 0, MODE_GATEUP = 1, MODE_LN = 2 };
 
 struct GemmArgs {
     const u16* A;        // [M, K]
-    const u16* B0;       // [K, N]
-    const u16* B1;       // [K, N]  (GATEUP only: W3)
+    const u16* B0;       // [K, N]  (BT kernels: [N, K])
+    const u16* B1;       // [K, N]  (GATEUP only: W3; BT kernels: [N, K])
     u16* C;              // [M, N]
     const u16* gain;     // [K]     (GATEUP: g, LN: gamma)
     const float* colc;   // [N]     (LN: gamma^T W)
@@ -137,7 +137,11 @@ __device__ __forceinline__ void quad_transpose(u32& d0, u32& d1, bool upper, u32
 // epilogue; splitk_reduce_kernel adds the partial results in fixed order and
 // applies the epilogue.  This is Rule 3's parallel reduction over the
 // contraction blocks, with per-workgroup partial results instead of atomics.
-template <int MODE, int BM, bool FULL, bool ODD, bool SPLIT = false>
+// BT: B is given transposed, [N, K] row-major (ldb = its row length): the layout
+// of the paper's block programs (W^T) and of linear-layer checkpoints.  Its tile
+// then lies in LDS exactly like the A tile (rows of 8 contraction chunks, same
+// swizzle, same load-to-LDS role) and its fragments are plain 128-bit reads.
+template <int MODE, int BM, bool FULL, bool ODD, bool SPLIT = false, bool BT = false>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     constexpr int WM = (MODE == MODE_PLAIN) ? 2 : 4;   // wavefronts along the rows
     constexpr int WN = 4 / WM;                          // and along the columns
@@ -217,6 +221,16 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     const int colB = n0 + 8 * chunkB;
     const bool colB_ok = FULL || colB < p.N;
     const u32 laneB = (u32)(rowBl * p.ldb + (colB_ok ? 8 * chunkB : 0));
+    // BT: like the A tile.  256 tile rows (= output columns; GATEUP: 128 rows of
+    // W1^T, then the same 128 of W3^T), 8 instructions per wavefront, each 8 rows.
+    const int rowT = 64 * w + (lane >> 3);                       // + 8 j for instruction j
+    int kcT[2];
+    u32 laneT[2];
+#pragma unroll
+    for (int o = 0; o < 2; ++o) {
+        kcT[o] = (lane & 7) ^ (((rowT + 8 * o) >> 1) & 7);
+        laneT[o] = (u32)((lane >> 3) * p.ldb + 8 * kcT[o]);
+    }
 
     // ---- B: fragment-read role.  Group b = lane / 16 of a transposing read
     // covers contraction rows 8 (b / 2) + 4 h + (0..3) (+ 16 per matrix
@@ -249,7 +263,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
 #pragma unroll
         for (int qq = 0; qq < 2; ++qq) {
             const int q = 2 * part + qq;
-            if (HALF) {
+            if (BT) {
+                const int r0 = 64 * w + 8 * q;                       // first tile row of the instruction
+                const u16* base = (HALF && w >= 2) ? p.B1 : p.B0;
+                const int nrow = HALF ? n0 + (r0 & 127) : n0 + r0;   // first matrix row (output column)
+                const void* g = src_of(base, (size_t)nrow * p.ldb + k0, laneT[q & 1],
+                                       k0 + 8 * kcT[q & 1] < p.K && nrow + (lane >> 3) < p.N);
+                load_to_lds16(g, dB + (8 * w + q) * 64);
+            } else if (HALF) {
                 const int rg = 4 * (q & 3) + w;                      // four-row group of the half tile
                 const u16* base = (q >> 2) ? p.B1 : p.B0;
                 const void* g = src_of(base, (size_t)(k0 + 4 * rg) * p.ldb + n0, laneB,
@@ -311,11 +332,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
         if (MODE != MODE_PLAIN) fg[S].u = bufG[kc];
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt) {
-            const char* q = reinterpret_cast<const char*>(PB ? sB1 : sB0) + offB[tt & 3] + ks * (16 * BROW) + BTT4 * (tt >> 2);
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(q));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(q + 4 * BROW));
-            u32x2 l2 = *reinterpret_cast<const u32x2*>(&lo), h2 = *reinterpret_cast<const u32x2*>(&hi);
-            fb[S][tt].u = u32x4{l2[0], l2[1], h2[0], h2[1]};
+            if (BT) {
+                fb[S][tt].u = (PB ? sB1 : sB0)[lds_pos((HALF ? 0 : WC * wn) + 32 * tt + l32, kc)];
+            } else {
+                const char* q = reinterpret_cast<const char*>(PB ? sB1 : sB0) + offB[tt & 3] + ks * (16 * BROW) + BTT4 * (tt >> 2);
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(q));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(q + 4 * BROW));
+                u32x2 l2 = *reinterpret_cast<const u32x2*>(&lo), h2 = *reinterpret_cast<const u32x2*>(&hi);
+                fb[S][tt].u = u32x4{l2[0], l2[1], h2[0], h2[1]};
+            }
         }
     };
     // norm prologue on the A fragments of set S: row sums, gain, rounding.
@@ -368,7 +393,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     // wavefronts do not burst into the LDS together), a slice of the vector ALU
     // work and, every second time, one load-to-LDS.
     constexpr int NDSR_A = MT + (MODE != MODE_PLAIN ? 1 : 0);
-    constexpr int DSR_PER = (2 * NT + NMMA - 1) / NMMA;
+    constexpr int DSR_PER = ((BT ? 1 : 2) * NT + NMMA - 1) / NMMA;
     constexpr int VQ = (MODE == MODE_PLAIN) ? 2 : ((MODE == MODE_LN ? 9 : 7) * ITEMS + 8) / NMMA + 3;   // vector ALU slice per matrix instruction
     auto pattern = [&](bool with_frags, bool with_dma) {
         if (with_frags) __builtin_amdgcn_sched_group_barrier(0x100, NDSR_A, 0);

@@ -154,6 +154,39 @@ __global__ __launch_bounds__(256) void colvec_sum_kernel(const float* part, floa
     colb[n] = b;
 }
 
+// The same column vectors for a transposed weight Wt [N, D]: colc[n] = sum_d
+// gamma[d] Wt[n,d], colb[n] = sum_d beta[d] Wt[n,d].  One wavefront per row n
+// (contiguous reads of 1 KiB), wavefront reduction at the end.
+__global__ __launch_bounds__(256) void colvec_t_kernel(const u16* Wt, const u16* gamma, const u16* beta,
+                                                       float* colc, float* colb, int D, int N) {
+    const int lane = threadIdx.x & 63;
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (n >= N) return;
+    float c = 0.f, b = 0.f;
+    for (int d0 = 8 * lane; d0 < D; d0 += 512 * 4) {          // four chunks in flight
+        u32x4 wv[4], gv[4], bv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int d = d0 + 512 * u;
+            const bool ok = d < D;
+            wv[u] = ok ? ldg16(Wt + (size_t)n * D + d) : zero4();
+            gv[u] = ok ? ldg16(gamma + d) : zero4();
+            bv[u] = ok ? ldg16(beta + d) : zero4();
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float w0 = bf_lo(wv[u][q]), w1 = bf_hi(wv[u][q]);
+                c = fmaf(bf_lo(gv[u][q]), w0, c); c = fmaf(bf_hi(gv[u][q]), w1, c);
+                b = fmaf(bf_lo(bv[u][q]), w0, b); b = fmaf(bf_hi(bv[u][q]), w1, b);
+            }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { c += __shfl_xor(c, o); b += __shfl_xor(b, o); }
+    if (lane == 0) { colc[n] = c; colb[n] = b; }
+}
+
 __global__ __launch_bounds__(256) void fill_zero_kernel(u32x4* p, size_t n16) {
     const u32x4 z = {0u, 0u, 0u, 0u};
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) p[i] = z;

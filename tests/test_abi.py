@@ -54,9 +54,9 @@ def ln(lib, X=A, ga=2 * A, be=3 * A, W=4 * A, Y=6 * A, M=4, D=64, N=128, eps=1e-
     return fn(X, ga, be, W, Y, M, D, N, eps, None)
 
 
-@pytest.mark.parametrize("unfused", [False, True])
+@pytest.mark.parametrize("unfused", ["", "_unfused", "_t"])
 def test_ffn_argument_errors(lib, unfused):
-    fn = lib.bb_rmsnorm_swiglu_ffn_unfused if unfused else lib.bb_rmsnorm_swiglu_ffn
+    fn = getattr(lib, "bb_rmsnorm_swiglu_ffn" + unfused)
     assert ffn(lib, fn=fn, M=0) == 0                       # empty input: nothing to do
     assert ffn(lib, fn=fn, M=0, X=None, Y=None) == 0
     assert ffn(lib, fn=fn, M=-1) == -2
@@ -75,9 +75,9 @@ def test_ffn_argument_errors(lib, unfused):
     assert ffn(lib, fn=fn, Y=5 * A + 64) == -5             # overlap with W2
 
 
-@pytest.mark.parametrize("unfused", [False, True])
+@pytest.mark.parametrize("unfused", ["", "_unfused", "_t"])
 def test_ln_argument_errors(lib, unfused):
-    fn = lib.bb_layernorm_matmul_unfused if unfused else lib.bb_layernorm_matmul
+    fn = getattr(lib, "bb_layernorm_matmul" + unfused)
     assert ln(lib, fn=fn, M=0) == 0
     assert ln(lib, fn=fn, M=-3) == -2
     assert ln(lib, fn=fn, N=12) == -2

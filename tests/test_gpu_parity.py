@@ -198,6 +198,40 @@ def test_split_contraction_few_rows(M, D, F):
         assert ffn_case(cpu, 1e-6, unfused=True) <= TOL
 
 
+# Transposed-weight entry points (W1t [F,D], W3t [F,D], W2t [D,F]; Wt [N,D]):
+# the oracle takes the logical matrices, the library their transposes.
+def tr(w):
+    return w.t().contiguous()
+
+
+@pytest.mark.parametrize("M,D,F", [(1, 64, 64), (16, 256, 704), (130, 264, 712), (300, 520, 1032), (256, 256, 384),
+                                   (256, 192, 384), (128, 64, 128), (48, 2048, 5632), (17, 4096, 11008)])
+def test_transposed_weights_ffn(M, D, F):
+    X, g, W1, W3, W2 = bb_inputs.make_ffn(M, D, F, seed=M + D)
+    Y = bb.bb_rmsnorm_swiglu_ffn_t(*dev((X, g, tr(W1), tr(W3), tr(W2))), 1e-6)
+    torch.cuda.synchronize()
+    assert row_rel_err(Y, orc.rmsnorm_swiglu_ffn(X, g, W1, W3, W2, 1e-6)) <= TOL
+
+
+@pytest.mark.parametrize("M,D,N", [(1, 64, 64), (64, 256, 512), (130, 264, 712), (256, 192, 512), (384, 448, 256)])
+def test_transposed_weights_ln(M, D, N):
+    X, ga, be, W = bb_inputs.make_ln(M, D, N, seed=M + N)
+    Y = bb.bb_layernorm_matmul_t(*dev((X, ga, be, tr(W))), 1e-5)
+    torch.cuda.synchronize()
+    assert row_rel_err(Y, orc.layernorm_matmul(X, ga, be, W, 1e-5)) <= TOL
+
+
+def test_c3_transposed_weights_sampled_rows():
+    c = bb_inputs.CONFIGS["c3"]
+    X, g, W1, W3, W2 = bb_inputs.make_config("c3")
+    rows = sample_rows(c.M)
+    Y = bb.bb_rmsnorm_swiglu_ffn_t(*dev((X, g, tr(W1), tr(W3), tr(W2))), c.eps)
+    torch.cuda.synchronize()
+    err = row_rel_err(Y[rows], orc.rmsnorm_swiglu_ffn(X, g, W1, W3, W2, c.eps, rows=rows))
+    print("c3 transposed rel err", err)
+    assert err <= TOL
+
+
 # ------------------------------------------------------------ full-size configs
 def test_c2_decode_full():
     c = bb_inputs.CONFIGS["c2"]
