@@ -99,6 +99,18 @@ def make_ln(M: int, D: int, N: int, seed: int = 0, x_dist: str = "normal_2_3"):
     return tuple(t.to(torch.bfloat16).contiguous() for t in (X, gamma, beta, W))
 
 
+def make_attn(B: int, M: int, N: int, d: int, dv: int, seed: int = 0, q_scale: float = 1.0):
+    """Q [B,M,d], K [B,N,d], V [B,N,dv] as CPU bf16 tensors, all N(0,1) (Q times
+    q_scale): scores Q K^T / sqrt(d) then have unit variance, like attention
+    logits of a trained model at initialisation."""
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(seed)
+    Q = q_scale * torch.randn(B, M, d, generator=gen, dtype=torch.float32)
+    K = torch.randn(B, N, d, generator=gen, dtype=torch.float32)
+    V = torch.randn(B, N, dv, generator=gen, dtype=torch.float32)
+    return tuple(t.to(torch.bfloat16).contiguous() for t in (Q, K, V))
+
+
 def make_config(name: str, seed: int = 0, M: Optional[int] = None):
     """Inputs of a named configuration (optionally with fewer/more rows)."""
     c = CONFIGS[name]

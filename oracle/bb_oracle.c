@@ -6,6 +6,8 @@
  *                              its initial block program)
  *   - LayerNorm -> matmul     (paper: Example 2, original array program,
  *                              the sigma formula of Example 2)
+ *   - Attention               (paper: Example 1, original array program:
+ *                              softmax(Q K^T / sqrt(d)) V)
  *
  * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  Only the tests, the smoke
  * check and the bench's cpu_baseline leg may load it.  It shares no source,
@@ -214,6 +216,85 @@ int bb_oracle_layernorm_matmul(const uint16_t* X, const uint16_t* gamma,
             }
         }
         free(z);
+    }
+    return fail ? -1 : 0;
+}
+
+/*
+ * Attention, Example 1 (original array program): for every problem b of a
+ * batch and every query row i
+ *
+ *   s_j  = sum_k Q[b,i,k] K[b,j,k] / sqrt(d)          j = 0..N-1
+ *   p_j  = exp(s_j) / sum_j' exp(s_j')                 (softmax over the keys)
+ *   O[b,i,:] = sum_j p_j V[b,j,:]
+ *
+ * The paper states the operator for single matrices Q [M,d], K [N,d], V [N,L]
+ * (L = dv here); the batch index only repeats it for independent problems
+ * (heads).  exp(s_j) is evaluated as exp(s_j - max_j' s_j') in numerator and
+ * denominator, which is the same quotient (the paper's Appendix: numerical
+ * safety changes the representation, not the value).  No mask, no dropout:
+ * the paper has none.
+ *
+ * Q [B,M,d], K [B,N,d], V [B,N,dv] : bf16 bit patterns.  rows: nrows indices
+ * into the B*M flattened query rows (b*M + i), or NULL for the first nrows.
+ * O [nrows, dv] double.
+ */
+int bb_oracle_attention(const uint16_t* Q, const uint16_t* K, const uint16_t* V,
+                        double* O, int64_t B, int64_t M, int64_t N, int64_t d,
+                        int64_t dv, const int64_t* rows, int64_t nrows) {
+    if (B <= 0 || M <= 0 || N <= 0 || d <= 0 || dv <= 0 || nrows < 0) return -1;
+    if (!rows && nrows > B * M) return -1;
+    if (nrows == 0) return 0;
+    if (!Q || !K || !V || !O) return -1;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double* sc = (double*)malloc(sizeof(double) * (size_t)N);
+        if (!sc) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp barrier
+        int bad;
+#pragma omp atomic read
+        bad = fail;
+        if (!bad) {
+            const double inv = 1.0 / sqrt((double)d);
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t k = 0; k < nrows; ++k) {
+                const int64_t r = rows ? rows[k] : k;
+                if (r < 0 || r >= B * M) {
+#pragma omp atomic write
+                    fail = 1;
+                    continue;
+                }
+                const int64_t b = r / M;
+                const uint16_t* q = Q + (size_t)r * (size_t)d;
+                const uint16_t* Kb = K + (size_t)b * (size_t)N * (size_t)d;
+                const uint16_t* Vb = V + (size_t)b * (size_t)N * (size_t)dv;
+                double mx = -INFINITY;
+                for (int64_t j = 0; j < N; ++j) {
+                    double acc = 0.0;
+                    for (int64_t c = 0; c < d; ++c)
+                        acc += bf16_to_double(q[c]) * bf16_to_double(Kb[(size_t)j * (size_t)d + c]);
+                    sc[j] = acc * inv;
+                    if (sc[j] > mx) mx = sc[j];
+                }
+                double den = 0.0;
+                for (int64_t j = 0; j < N; ++j) {
+                    sc[j] = exp(sc[j] - mx);
+                    den += sc[j];
+                }
+                double* o = O + (size_t)k * (size_t)dv;
+                for (int64_t c = 0; c < dv; ++c) o[c] = 0.0;
+                for (int64_t j = 0; j < N; ++j) {
+                    const double pj = sc[j] / den;
+                    const uint16_t* v = Vb + (size_t)j * (size_t)dv;
+                    for (int64_t c = 0; c < dv; ++c) o[c] += pj * bf16_to_double(v[c]);
+                }
+            }
+        }
+        free(sc);
     }
     return fail ? -1 : 0;
 }

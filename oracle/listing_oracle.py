@@ -168,3 +168,72 @@ def fused_layernorm_matmul(X, gamma, beta, W, eps, nM=1, nN=1, nK=1):
             t = row_scale(t, rstd)
             Z[m, n] = t + bia[None, :]
     return Z
+
+
+# ============================================================ Example 1
+def fused_attention(Q, K, V, nM=1, nN=1, nD=1, nL=1):
+    """Example 1's final fused nest (the "unsafe" Flash Attention the fusion
+    algorithm ends with): per (m, l) output block a serial loop over key blocks
+    n; inside it a serial loop over feature blocks d accumulates the dot of the
+    query block with the key block; the scaled scores are exponentiated block by
+    block, their row sums and the dot with the transposed value block are
+    accumulated, and the rows are divided by the accumulated row sums at the
+    end.  No stabilisation: plain exp.  Q [M,d], K [N,d], V [N,L] float64."""
+    Mt, dt = Q.shape
+    Nt, Lt = V.shape
+    mb, nb = np.array_split(np.arange(Mt), nM), np.array_split(np.arange(Nt), nN)
+    db, lb = np.array_split(np.arange(dt), nD), np.array_split(np.arange(Lt), nL)
+    O = np.empty((Mt, Lt))
+    VT = V.T
+    for m in mb:
+        for l in lb:
+            t5 = np.zeros(len(m))
+            t7 = np.zeros((len(m), len(l)))
+            for n in nb:
+                t3 = np.zeros((len(m), len(n)))
+                for d in db:
+                    t3 = add(t3, dot(Q[np.ix_(m, d)], K[np.ix_(n, d)]))
+                t4 = np.exp(t3 * (dt ** -0.5))
+                t5 = add(t5, row_sum(t4))
+                t7 = add(t7, dot(t4, VT[np.ix_(l, n)]))
+            O[np.ix_(m, l)] = row_scale(t7, 1.0 / t5)
+    return O
+
+
+# --- the Appendix: numbers as significand-exponent pairs (s, t) = s * e^t ---
+# Here in its row-wise form: a block carries one exponent per row.
+def se_exp(X):
+    """elementwise exp of a block as (significands, row exponents)"""
+    z = X.max(axis=1)
+    return np.exp(X - z[:, None]), z
+
+
+def se_add(a, b):
+    """(S1,t1) + (S2,t2) with a common exponent z = max(t1,t2) per row; S may be
+    a block or a vector of per-row values"""
+    (S1, t1), (S2, t2) = a, b
+    z = np.maximum(t1, t2)
+    w1, w2 = np.exp(t1 - z), np.exp(t2 - z)
+    if S1.ndim == 2:
+        return S1 * w1[:, None] + S2 * w2[:, None], z
+    return S1 * w1 + S2 * w2, z
+
+
+def safe_attention(Q, K, V, nM=1, nN=1):
+    """The same nest with the Appendix's numerical safety: every exponentiated
+    block is a (significand block, per-row exponent) pair, sums of pairs are
+    brought to the larger exponent, the final division is a division of pairs.
+    This is the form the GPU kernel follows (row-wise shared exponents)."""
+    Mt, dt = Q.shape
+    Nt, Lt = V.shape
+    O = np.empty((Mt, Lt))
+    for m in np.array_split(np.arange(Mt), nM):
+        den = (np.zeros(len(m)), np.full(len(m), -np.inf))        # the number 0
+        num = (np.zeros((len(m), Lt)), np.full(len(m), -np.inf))
+        for n in np.array_split(np.arange(Nt), nN):
+            S, t = se_exp(dot(Q[m], K[n]) * (dt ** -0.5))
+            den = se_add(den, (row_sum(S), t))
+            num = se_add(num, (dot(S, V[n].T), t))
+        # (num_S e^{num_t}) / (den_S e^{den_t}): both carry the same exponent history
+        O[m] = row_scale(num[0], 1.0 / den[0]) * np.exp(num[1] - den[1])[:, None]
+    return O

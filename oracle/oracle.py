@@ -50,6 +50,9 @@ def _load():
             u16p, u16p, u16p, u16p, f64p, i64, i64, i64,
             ctypes.c_double, i64p, i64]
         lib.bb_oracle_layernorm_matmul.restype = ctypes.c_int
+        lib.bb_oracle_attention.argtypes = [
+            u16p, u16p, u16p, f64p, i64, i64, i64, i64, i64, i64p, i64]
+        lib.bb_oracle_attention.restype = ctypes.c_int
         lib.bb_oracle_num_threads.restype = ctypes.c_int
         lib.bb_oracle_set_num_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -136,3 +139,22 @@ def layernorm_matmul(X, gamma, beta, W, eps: float,
     if rc != 0:
         raise RuntimeError("bb_oracle_layernorm_matmul failed")
     return Y
+
+
+def attention(Q, K, V, rows: Optional[Sequence[int]] = None) -> np.ndarray:
+    """Definition of Example 1's array program, softmax(Q K^T / sqrt(d)) V, per
+    batch entry.  Q [B,M,d], K [B,N,d], V [B,N,dv]  ->  float64 [nrows, dv];
+    rows index the B*M flattened query rows (None = all, in order)."""
+    lib = _load()
+    B, M, d = (int(s) for s in Q.shape)
+    N, dv = int(K.shape[1]), int(V.shape[2])
+    Qb, Kb, Vb = _bits(Q, (B, M, d)), _bits(K, (B, N, d)), _bits(V, (B, N, dv))
+    keep, rp, n = _rows(rows, B * M)
+    O = np.empty((n, dv), dtype=np.float64)
+    rc = lib.bb_oracle_attention(
+        _p16(Qb), _p16(Kb), _p16(Vb), O.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+        B, M, N, d, dv, rp, n)
+    del keep
+    if rc != 0:
+        raise RuntimeError("bb_oracle_attention failed")
+    return O

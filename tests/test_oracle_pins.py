@@ -372,3 +372,117 @@ def test_c1_regression_fixture():
     Y = orc.rmsnorm_swiglu_ffn(X, g, W1, W3, W2, 1e-6, rows=ur)
     got = np.array([Y[ur.index(r), c] for r, c in zip(rows, cols)])
     np.testing.assert_allclose(got, np.array(vals), rtol=1e-12)
+
+
+# --------------------------------------------------------------------------
+# Attention (Example 1): softmax(Q K^T / sqrt(d)) V
+# --------------------------------------------------------------------------
+def small_attn(B, M, N, d, dv, seed):
+    return tuple(bb_inputs.bits(t) for t in bb_inputs.make_attn(B, M, N, d, dv, seed))
+
+
+def attn_ref64(Qb, Kb, Vb):
+    """plain numpy fp64 composition per batch entry (library matmul / exp)"""
+    Q, K, V = f64(Qb), f64(Kb), f64(Vb)
+    out = []
+    for b in range(Q.shape[0]):
+        S = Q[b] @ K[b].T / math.sqrt(Q.shape[2])
+        P = np.exp(S - S.max(axis=1, keepdims=True))
+        out.append((P / P.sum(axis=1, keepdims=True)) @ V[b])
+    return np.concatenate(out, axis=0)
+
+
+def test_attention_closed_form_two_keys():
+    O = orc.attention(bf16([[[2, 0, 0, 0]]]), bf16([[[1, 0, 0, 0], [-1, 0, 0, 0]]]), bf16([[[1, 0], [0, 1]]]))
+    np.testing.assert_allclose(O[0], golden()["attn_two_keys"], rtol=1e-14)
+
+
+def test_attention_closed_form_scale_is_inverse_sqrt_d():
+    q = np.zeros((1, 1, 16)); q[0, 0, 0] = 4
+    K = np.zeros((1, 3, 16)); K[0, :, 0] = [1, 0, -1]
+    O = orc.attention(bf16(q), bf16(K), bf16([[[1, 2], [3, -1], [0, 4]]]))
+    np.testing.assert_allclose(O[0], golden()["attn_scale"], rtol=1e-14)
+
+
+def test_attention_zero_queries_average_the_values():
+    Q, K, V = small_attn(2, 5, 9, 8, 6, 1)
+    O = orc.attention(np.zeros_like(Q), K, V)
+    for b in range(2):
+        np.testing.assert_allclose(O[5 * b:5 * b + 5], np.tile(f64(V)[b].mean(axis=0), (5, 1)), rtol=1e-13)
+
+
+def test_attention_single_key_returns_its_value_row():
+    Q, K, V = small_attn(1, 4, 1, 8, 5, 2)
+    np.testing.assert_allclose(orc.attention(Q, K, V), np.tile(f64(V)[0, 0], (4, 1)), rtol=1e-15)
+
+
+def test_attention_brute_force_decimal():
+    """independent scalar evaluation with 50-digit decimals, different loop order"""
+    getcontext().prec = 50
+    Qb, Kb, Vb = small_attn(1, 3, 4, 2, 3, 3)
+    Q, K, V = f64(Qb)[0], f64(Kb)[0], f64(Vb)[0]
+    O = orc.attention(Qb, Kb, Vb)
+    rd = Decimal(2).sqrt()
+    for i in range(3):
+        e = []
+        for j in range(4):
+            s = sum(Decimal(float(Q[i, c])) * Decimal(float(K[j, c])) for c in reversed(range(2))) / rd
+            e.append(s.exp())
+        den = sum(e)
+        for c in range(3):
+            want = sum(e[j] * Decimal(float(V[j, c])) for j in range(4)) / den
+            assert abs(Decimal(float(O[i, c])) - want) <= Decimal(10) ** -14 * (1 + abs(want))
+
+
+def test_attention_matches_library_composition_and_torch():
+    Qb, Kb, Vb = small_attn(3, 17, 33, 16, 24, 4)
+    O = orc.attention(Qb, Kb, Vb)
+    np.testing.assert_allclose(O, attn_ref64(Qb, Kb, Vb), rtol=1e-12, atol=1e-14)
+    t = lambda a: torch.as_tensor(f64(a))
+    want = torch.nn.functional.scaled_dot_product_attention(t(Qb), t(Kb), t(Vb)).reshape(-1, 24).numpy()
+    np.testing.assert_allclose(O, want, rtol=1e-11, atol=1e-13)
+
+
+def test_attention_invariants():
+    Qb, Kb, Vb = small_attn(2, 6, 10, 8, 4, 5)
+    O = orc.attention(Qb, Kb, Vb)
+    # permuting the keys together with their values changes nothing
+    perm = np.random.default_rng(0).permutation(10)
+    np.testing.assert_allclose(orc.attention(Qb, Kb[:, perm], Vb[:, perm]), O, rtol=1e-12, atol=1e-15)
+    # linear in V; rows are convex combinations of value rows
+    np.testing.assert_allclose(orc.attention(Qb, Kb, bf16(2 * f64(Vb))), 2 * O, rtol=1e-13)
+    V = f64(Vb)
+    for b in range(2):
+        blk = O[6 * b:6 * b + 6]
+        assert np.all(blk <= V[b].max(axis=0) + 1e-12) and np.all(blk >= V[b].min(axis=0) - 1e-12)
+    # adding the same vector to every key shifts all scores of a query equally: softmax unchanged
+    # (keys on a 1/16 grid so that the shifted keys are exactly representable in bf16)
+    Kq = np.clip(np.round(f64(Kb) * 16) / 16, -2, 2)
+    c = np.zeros(8); c[3] = 1.0
+    np.testing.assert_allclose(orc.attention(Qb, bf16(Kq + c), Vb), orc.attention(Qb, bf16(Kq), Vb),
+                               rtol=1e-11, atol=1e-13)
+    # row subset / batch independence
+    rows = [11, 0, 7]
+    np.testing.assert_allclose(orc.attention(Qb, Kb, Vb, rows=rows), O[rows], rtol=0, atol=0)
+    np.testing.assert_allclose(orc.attention(Qb[1:], Kb[1:], Vb[1:]), O[6:], rtol=0, atol=0)
+
+
+@pytest.mark.parametrize("split", [dict(), dict(nM=2, nN=3, nD=4, nL=2), dict(nM=5, nN=11, nD=8, nL=3)])
+def test_attention_fused_nest_agrees_for_every_block_splitting(split):
+    Qb, Kb, Vb = small_attn(1, 5, 11, 8, 3, 6)
+    O = orc.attention(Qb, Kb, Vb)
+    np.testing.assert_allclose(lo.fused_attention(f64(Qb)[0], f64(Kb)[0], f64(Vb)[0], **split), O, rtol=1e-12)
+
+
+@pytest.mark.parametrize("split", [dict(), dict(nM=2, nN=4), dict(nM=5, nN=11)])
+def test_attention_significand_exponent_pairs_agree_and_do_not_overflow(split):
+    Qb, Kb, Vb = small_attn(1, 5, 11, 8, 3, 7)
+    O = orc.attention(Qb, Kb, Vb)
+    np.testing.assert_allclose(lo.safe_attention(f64(Qb)[0], f64(Kb)[0], f64(Vb)[0], **split), O, rtol=1e-12)
+    # scores of several hundred: plain exp overflows, the pairs and the oracle do not
+    big = bf16(f64(Qb) * 256)
+    Ob = orc.attention(big, Kb, Vb)
+    assert np.all(np.isfinite(Ob))
+    np.testing.assert_allclose(lo.safe_attention(f64(big)[0], f64(Kb)[0], f64(Vb)[0], **split), Ob, rtol=1e-11, atol=1e-14)
+    with np.errstate(over="ignore", invalid="ignore"):
+        assert not np.all(np.isfinite(lo.fused_attention(f64(big)[0] * 8, f64(Kb)[0], f64(Vb)[0])))
