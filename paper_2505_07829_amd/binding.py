@@ -21,7 +21,7 @@ OP_FFN, OP_LN, OP_FFN_UNFUSED, OP_LN_UNFUSED = 0, 1, 2, 3
 EXPORTS = [
     "bb_rmsnorm_swiglu_ffn", "bb_layernorm_matmul",
     "bb_rmsnorm_swiglu_ffn_unfused", "bb_layernorm_matmul_unfused",
-    "bb_rmsnorm_swiglu_ffn_t", "bb_layernorm_matmul_t",
+    "bb_rmsnorm_swiglu_ffn_t", "bb_layernorm_matmul_t", "bb_attention",
     "bb_workspace_bytes", "bb_set_workspace", "bb_set_variant", "bb_get_variant",
     "bb_shutdown", "bb_status_string", "bb_version", "bb_last_hip_error",
     "bb_calib_copy", "bb_calib_read", "bb_calib_mfma", "bb_calib_mfma_data",
@@ -53,6 +53,7 @@ def load() -> ctypes.CDLL:
     lib.bb_layernorm_matmul_t.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
     lib.bb_layernorm_matmul.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
     lib.bb_layernorm_matmul_unfused.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
+    lib.bb_attention.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, vp]
     lib.bb_workspace_bytes.argtypes = [ci, i64, i64, i64]
     lib.bb_workspace_bytes.restype = sz
     lib.bb_set_workspace.argtypes = [vp, sz]
@@ -130,6 +131,20 @@ def bb_rmsnorm_swiglu_ffn_t(X, g, W1t, W3t, W2t, eps: float, Y=None):
     _check(lib.bb_rmsnorm_swiglu_ffn_t(_ptr(X), _ptr(g), _ptr(W1t), _ptr(W3t), _ptr(W2t), _ptr(Y), M, D, F,
                                        float(eps), _stream()), "bb_rmsnorm_swiglu_ffn_t")
     return Y
+
+
+def bb_attention(Q, K, V, O=None):
+    """O = softmax(Q K^T / sqrt(d)) V per problem; Q [B,M,d], K [B,N,d], V [B,N,dv].  Returns O [B,M,dv]."""
+    import torch
+    lib = load()
+    B, M, d = Q.shape
+    N, dv = V.shape[1], V.shape[2]
+    _require(Q, (B, M, d), "Q"); _require(K, (B, N, d), "K"); _require(V, (B, N, dv), "V")
+    if O is None:
+        O = torch.empty((B, M, dv), dtype=torch.bfloat16, device=Q.device)
+    _require(O, (B, M, dv), "O")
+    _check(lib.bb_attention(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), B, M, N, d, dv, _stream()), "bb_attention")
+    return O
 
 
 def bb_layernorm_matmul_t(X, gamma, beta, Wt, eps: float, Y=None):

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbb.so")
 SOURCES = ["bb_api.hip"]
-HEADERS = ["bb_common.h", "bb_gemm.h", "bb_stream.h", "bb_misc.h"]
+HEADERS = ["bb_common.h", "bb_gemm.h", "bb_stream.h", "bb_misc.h", "bb_attn.h"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -9,6 +9,7 @@
 #include <mutex>
 
 #include "../../include/bb.h"
+#include "bb_attn.h"
 #include "bb_gemm.h"
 #include "bb_misc.h"
 #include "bb_stream.h"
@@ -541,6 +542,45 @@ int bb_layernorm_matmul_t(const void* X, const void* gamma, const void* beta, co
     prof_mark("colvec", st);
     return launch_gemm<MODE_LN, true>((const u16*)X, (int)D, (const u16*)Wt, nullptr, (int)D, (u16*)Y, (int)N,
                                       (const u16*)gamma, colc, colb, (int)M, (int)N, (int)D, eps, dev->cus, st);
+}
+
+int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B, int64_t M, int64_t N,
+                 int64_t d, int64_t dv, void* stream) {
+    if (B < 0 || M < 0 || N < 1) return BB_ERR_SHAPE;
+    if ((d != 64 && d != 128) || (dv != 64 && dv != 128)) return BB_ERR_SHAPE;
+    if (M > (1 << 24) || N > (1 << 24)) return BB_ERR_SHAPE;
+    const int64_t tiles_q = (M + ATTN_BQ - 1) / ATTN_BQ;
+    if (B * tiles_q > 0x7fffffffLL) return BB_ERR_SHAPE;            // one workgroup per (problem, query block)
+    if (B == 0 || M == 0) return BB_OK;
+    if (!Q || !K || !V || !O) return BB_ERR_NULL;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O)) return BB_ERR_ALIGN;
+    const size_t no = (size_t)B * M * dv * 2;
+    if (overlaps(O, no, Q, (size_t)B * M * d * 2) || overlaps(O, no, K, (size_t)B * N * d * 2) ||
+        overlaps(O, no, V, (size_t)B * N * dv * 2))
+        return BB_ERR_ALIAS;
+    std::lock_guard<std::mutex> lk(g_mu);
+    const DeviceInfo* dev = nullptr;
+    if (int rc = current_device_info(&dev)) return rc;
+    hipStream_t st = as_stream(stream);
+    AttnArgs a;
+    a.Q = (const u16*)Q;
+    a.K = (const u16*)K;
+    a.V = (const u16*)V;
+    a.O = (u16*)O;
+    a.B = (int)B;
+    a.M = (int)M;
+    a.N = (int)N;
+    a.tiles_q = (int)tiles_q;
+    a.c = (float)(1.4426950408889634 / std::sqrt((double)d));
+    const dim3 grid((unsigned)(B * tiles_q)), block(ATTN_THREADS);
+    prof_begin(st);
+    if (d == 64 && dv == 64) hipLaunchKernelGGL((attention_kernel<64, 64>), grid, block, 0, st, a);
+    else if (d == 64) hipLaunchKernelGGL((attention_kernel<64, 128>), grid, block, 0, st, a);
+    else if (dv == 64) hipLaunchKernelGGL((attention_kernel<128, 64>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((attention_kernel<128, 128>), grid, block, 0, st, a);
+    BB_HIP(hipGetLastError());
+    prof_mark("attention", st);
+    return BB_OK;
 }
 
 int bb_rmsnorm_swiglu_ffn_unfused(const void* X, const void* g, const void* W1, const void* W3,

@@ -1,0 +1,240 @@
+// Attention forward for gfx950: O = softmax(Q K^T / sqrt(d)) V  (Example 1).
+//
+// This is the loop nest the fusion algorithm ends with for Example 1 (its last
+// step, with the feature and value dimensions unsplit, D = L = 1, the setting
+// the epilogue names as the original Flash Attention): per block of queries
+// one serial loop over key blocks that accumulates the dot with the value
+// block and the row sums of the exponentiated scores, and a division by the
+// row sums at the end.  Numerical safety is added the way the paper's Appendix
+// describes, in its row-wise form: the exponentiated score block of a step is
+// a pair (significands, one exponent per query row), accumulators carry a
+// running exponent per row and are brought to the larger exponent before a
+// block is added.
+//
+// Layouts: Q [B, M, DK], K [B, N, DK], V [B, N, DV], O [B, M, DV], bf16,
+// row-major, B independent problems (heads).
+//
+// Tiling: one workgroup (4 wavefronts) per 128 queries of one problem, 32
+// queries per wavefront; key blocks of 64.  Scores are computed TRANSPOSED,
+// S^T = K Q^T, with 32x32x16 matrix instructions: a lane then holds one query
+// (column) and 16 of every 32 keys (rows), so the row-wise maximum and sum of
+// the softmax are in-lane reductions plus one exchange with lane ^ 32.  The
+// second product is computed transposed too, O^T = V^T P^T: the probabilities
+// leave the first product already in the register layout the second one wants
+// as its B operand (8 consecutive accumulator registers = 8 contraction slots;
+// the contraction order is free as long as both operands agree), and V^T comes
+// out of LDS with the transposing read, like the weight tiles of the GEMM.
+//   Q fragments stay in registers for the whole kernel (loaded from global
+// memory in operand layout).  K and V blocks go global -> LDS with load-to-LDS
+// instructions, double buffered, one barrier per key block.
+#pragma once
+#include "bb_gemm.h"
+
+namespace bb {
+
+struct AttnArgs {
+    const u16* Q;
+    const u16* K;
+    const u16* V;
+    u16* O;
+    int B, M, N;
+    int tiles_q;        // ceil(M / 128)
+    float c;            // log2(e) / sqrt(DK)
+};
+
+constexpr int ATTN_THREADS = 256;
+constexpr int ATTN_BQ = 128;      // queries per workgroup
+constexpr int ATTN_BK = 64;       // keys per step
+
+// chunk position of (row, chunk) in an LDS tile with CPR 16-byte chunks per row,
+// for reads that take 16 consecutive rows at one chunk index (128-bit fragment
+// reads): 16 different 16-byte slots of the 256-byte bank line
+template <int CPR>
+__device__ __forceinline__ int attn_pos_rows16(int row, int kc) {
+    return CPR == 16 ? row * 16 + (kc ^ (row & 15)) : row * 8 + (kc ^ ((row >> 1) & 7));
+}
+// swizzle of the chunk index for transposing reads (4 consecutive rows x 64
+// bytes per pass): the four rows must take the four 64-byte quarters of a bank line
+template <int CPR>
+__device__ __forceinline__ int attn_swz_tr(int row) {
+    return CPR == 16 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
+}
+
+template <int DK, int DV>
+__global__ __launch_bounds__(ATTN_THREADS) void attention_kernel(const AttnArgs p) {
+    constexpr int CK = DK / 8, CV = DV / 8;          // 16-byte chunks per K / V row
+    constexpr int NKS = DK / 16;                     // contraction slices of the first product
+    constexpr int NDS = DV / 32;                     // 32-row subtiles of O^T
+    static_assert((DK == 64 || DK == 128) && (DV == 64 || DV == 128), "head dimensions 64 or 128");
+    __shared__ u32x4 sK0[ATTN_BK * CK], sK1[ATTN_BK * CK];
+    __shared__ u32x4 sV0[ATTN_BK * CV], sV1[ATTN_BK * CV];
+
+    const int t = threadIdx.x, lane = t & 63;
+    const int w = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int l32 = lane & 31, g = lane >> 5;
+    const int b = blockIdx.x / p.tiles_q, qt = blockIdx.x % p.tiles_q;
+    const int q = qt * ATTN_BQ + 32 * w + l32;          // this lane's query
+    const u16* const Kb = p.K + (size_t)b * p.N * DK;
+    const u16* const Vb = p.V + (size_t)b * p.N * DV;
+    const u16* const zsrc = reinterpret_cast<const u16*>(&gemm_zero_chunk);
+
+    // Q fragments: B operand of S^T = K Q^T: column = query, 8 consecutive features
+    Chunk qf[NKS];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks)
+        qf[ks].u = (q < p.M) ? ldg16(p.Q + ((size_t)b * p.M + q) * DK + 16 * ks + 8 * g) : zero4();
+
+    // load-to-LDS roles: an instruction fills 64 chunks = 64 / CPR rows
+    auto dma_tile = [&](int kt, u32x4* dK, u32x4* dV) {
+        const int key0 = kt * ATTN_BK;
+        {
+            constexpr int RPI = 64 / CK, NI = ATTN_BK / RPI / 4;     // rows per instruction, instructions per wavefront
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int row = RPI * (NI * w + j) + lane / CK;       // key row of the tile
+                const int pos = lane % CK;
+                const int chunk = CK == 16 ? (pos ^ (row & 15)) : (pos ^ ((row >> 1) & 7));
+                const u16* src = (key0 + row < p.N) ? Kb + (size_t)(key0 + row) * DK + 8 * chunk : zsrc;
+                load_to_lds16(src, dK + (NI * w + j) * 64);
+            }
+        }
+        {
+            constexpr int RPI = 64 / CV, NI = ATTN_BK / RPI / 4;
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int row = RPI * (NI * w + j) + lane / CV;
+                const int pos = lane % CV;
+                const int chunk = pos ^ attn_swz_tr<CV>(row);
+                const u16* src = (key0 + row < p.N) ? Vb + (size_t)(key0 + row) * DV + 8 * chunk : zsrc;
+                load_to_lds16(src, dV + (NI * w + j) * 64);
+            }
+        }
+    };
+
+    // transposing-read role for V^T fragments: group blk = lane / 16 covers key
+    // rows 4 (blk / 2) + (0..3) (+ 8 for the second read) and value columns
+    // 16 (blk % 2) + (0..15) of a 32-column subtile; lane i' = lane % 16 supplies
+    // the address of row i' / 4, 4-column piece i' % 4.
+    const int blk = lane >> 4, ip = lane & 15;
+    const int trow = 4 * (blk >> 1) + (ip >> 2);                 // + 32 st + 16 kk (+ 8)
+    const int tchunk = 2 * (blk & 1) + ((ip & 3) >> 1);          // + 4 dsub
+    const int tbyte = 8 * (ip & 1);
+
+    f32x16 oacc[NDS];
+#pragma unroll
+    for (int ds = 0; ds < NDS; ++ds)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[ds][v] = 0.f;
+    float m_run = -INFINITY;      // running exponent of this query's row (in score units)
+    float l_run = 0.f;            // this lane's share of the row sum, at exponent m_run
+
+    const int nt = (p.N + ATTN_BK - 1) / ATTN_BK;
+
+    auto step = [&](int kt, const u32x4* cK, const u32x4* cV) {
+        // ---- S^T = K Q^T for the 64 keys of this block
+        f32x16 sacc[2];
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sacc[st][v] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+                Chunk kf;
+                kf.u = cK[attn_pos_rows16<CK>(32 * st + l32, 2 * ks + g)];
+                sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, sacc[st], 0, 0, 0);
+            }
+        }
+        // keys past the end of the sequence do not take part
+        if ((kt + 1) * ATTN_BK > p.N) {
+#pragma unroll
+            for (int st = 0; st < 2; ++st)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = kt * ATTN_BK + 32 * st + 8 * (v >> 2) + 4 * g + (v & 3);
+                    if (key >= p.N) sacc[st][v] = -INFINITY;
+                }
+        }
+        // ---- exponentiate as (significands, row exponent): exponent = running maximum
+        float mloc = -INFINITY;
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mloc = fmaxf(mloc, sacc[st][v]);
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+        const float m_new = fmaxf(m_run, mloc);
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * p.c);     // brings the accumulators to the new exponent
+        const float mc = m_new * p.c;
+        float lsum = 0.f;
+        Chunk pb[2][2];
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                for (int h = 0; h < 4; ++h) {
+                    const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[st][8 * kk + 2 * h], p.c, -mc));
+                    const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[st][8 * kk + 2 * h + 1], p.c, -mc));
+                    lsum += p0 + p1;
+                    pb[st][kk].u[h] = pack_bf16(p0, p1);
+                }
+        l_run = fmaf(l_run, alpha, lsum);
+        m_run = m_new;
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) oacc[ds][v] *= alpha;
+        // ---- O^T += V^T P^T
+        const char* vb = reinterpret_cast<const char*>(cV);
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                const int r0 = 32 * st + 16 * kk + trow;
+#pragma unroll
+                for (int ds = 0; ds < NDS; ++ds) {
+                    const int ch = 4 * ds + tchunk;
+                    const char* a0 = vb + r0 * (CV * 16) + ((ch ^ attn_swz_tr<CV>(r0)) << 4) + tbyte;
+                    const char* a1 = vb + (r0 + 8) * (CV * 16) + ((ch ^ attn_swz_tr<CV>(r0 + 8)) << 4) + tbyte;
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0));
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a1));
+                    const u32x2 l2 = *reinterpret_cast<const u32x2*>(&lo), h2 = *reinterpret_cast<const u32x2*>(&hi);
+                    Chunk vf;
+                    vf.u = u32x4{l2[0], l2[1], h2[0], h2[1]};
+                    oacc[ds] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pb[st][kk].v, oacc[ds], 0, 0, 0);
+                }
+            }
+    };
+
+    // ---- main loop over key blocks, double buffered
+    dma_tile(0, sK0, sV0);
+    for (int kt = 0; kt < nt; kt += 2) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        __syncthreads();                                   // block kt has landed; everyone is done with block kt - 1
+        if (kt + 1 < nt) dma_tile(kt + 1, sK1, sV1);
+        step(kt, sK0, sV0);
+        if (kt + 1 < nt) {
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            __syncthreads();
+            if (kt + 2 < nt) dma_tile(kt + 2, sK0, sV0);
+            step(kt + 1, sK1, sV1);
+        }
+    }
+
+    // ---- divide by the row sums and store: register v of subtile ds is value
+    // column 32 ds + 8 (v / 4) + 4 g + v % 4 of this lane's query
+    const float l = l_run + __shfl_xor(l_run, 32);
+    const float inv = 1.0f / l;
+    if (q < p.M) {
+        u16* const orow = p.O + ((size_t)b * p.M + q) * DV;
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds)
+#pragma unroll
+            for (int vg = 0; vg < 4; ++vg) {
+                const u32x2 o = {pack_bf16(oacc[ds][4 * vg] * inv, oacc[ds][4 * vg + 1] * inv),
+                                 pack_bf16(oacc[ds][4 * vg + 2] * inv, oacc[ds][4 * vg + 3] * inv)};
+                *reinterpret_cast<u32x2*>(orow + 32 * ds + 8 * vg + 4 * g) = o;
+            }
+    }
+}
+
+}  // namespace bb

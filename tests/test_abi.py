@@ -88,6 +88,28 @@ def test_ln_argument_errors(lib, unfused):
     assert ln(lib, fn=fn, Y=4 * A) == -5
 
 
+def attn(lib, Q=A, K=2 * A, V=3 * A, O=6 * A, B=2, M=16, N=16, d=64, dv=64):
+    return lib.bb_attention(Q, K, V, O, B, M, N, d, dv, None)
+
+
+def test_attention_argument_errors(lib):
+    assert attn(lib, B=0) == 0 and attn(lib, M=0) == 0      # nothing to do
+    assert attn(lib, B=0, Q=None, O=None) == 0
+    assert attn(lib, B=-1) == -2 and attn(lib, M=-1) == -2
+    assert attn(lib, N=0) == -2                             # softmax over no keys
+    for bad in (0, 32, 96, 72, 256):
+        assert attn(lib, d=bad) == -2
+        assert attn(lib, dv=bad) == -2
+    assert attn(lib, M=(1 << 24) + 1) == -2
+    assert attn(lib, B=1 << 30, M=1024) == -2               # more workgroups than a launch takes
+    for k in ("Q", "K", "V", "O"):
+        assert attn(lib, **{k: None}) == -1
+        assert attn(lib, **{k: A * 7 + 2}) == -3
+    assert attn(lib, O=A) == -5
+    assert attn(lib, O=2 * A + 32) == -5
+    assert attn(lib, O=3 * A - 64) == -5                    # tail of O runs into V
+
+
 def test_variant_and_workspace_queries(lib):
     assert bb.bb_get_variant() in (0, 1, 2)
     old = bb.bb_get_variant()
