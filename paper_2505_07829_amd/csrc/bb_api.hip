@@ -574,10 +574,18 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
     a.c = (float)(1.4426950408889634 / std::sqrt((double)d));
     const dim3 grid((unsigned)(B * tiles_q)), block(ATTN_THREADS);
     prof_begin(st);
-    if (d == 64 && dv == 64) hipLaunchKernelGGL((attention_kernel<64, 64>), grid, block, 0, st, a);
-    else if (d == 64) hipLaunchKernelGGL((attention_kernel<64, 128>), grid, block, 0, st, a);
-    else if (dv == 64) hipLaunchKernelGGL((attention_kernel<128, 64>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((attention_kernel<128, 128>), grid, block, 0, st, a);
+    const bool odd = ((N + ATTN_BK - 1) / ATTN_BK) & 1;
+    auto go = [&](auto DKC, auto DVC) {
+        constexpr int DK = decltype(DKC)::value, DV = decltype(DVC)::value;
+        if (odd) hipLaunchKernelGGL((attention_kernel<DK, DV, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((attention_kernel<DK, DV, false>), grid, block, 0, st, a);
+    };
+    using I64 = std::integral_constant<int, 64>;
+    using I128 = std::integral_constant<int, 128>;
+    if (d == 64 && dv == 64) go(I64{}, I64{});
+    else if (d == 64) go(I64{}, I128{});
+    else if (dv == 64) go(I128{}, I64{});
+    else go(I128{}, I128{});
     BB_HIP(hipGetLastError());
     prof_mark("attention", st);
     return BB_OK;

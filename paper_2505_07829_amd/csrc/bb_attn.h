@@ -28,6 +28,8 @@
 // memory in operand layout).  K and V blocks go global -> LDS with load-to-LDS
 // instructions, double buffered, one barrier per key block.
 #pragma once
+#include <type_traits>
+
 #include "bb_gemm.h"
 
 namespace bb {
@@ -60,8 +62,10 @@ __device__ __forceinline__ int attn_swz_tr(int row) {
     return CPR == 16 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
 }
 
-template <int DK, int DV>
-__global__ __launch_bounds__(ATTN_THREADS) void attention_kernel(const AttnArgs p) {
+// ODD: the number of key blocks is odd (a template parameter, so that the
+// double-buffered loop below has no branch that merges the accumulators).
+template <int DK, int DV, bool ODD>
+__global__ __launch_bounds__(ATTN_THREADS, 2) void attention_kernel(const AttnArgs p) {
     constexpr int CK = DK / 8, CV = DV / 8;          // 16-byte chunks per K / V row
     constexpr int NKS = DK / 16;                     // contraction slices of the first product
     constexpr int NDS = DV / 32;                     // 32-row subtiles of O^T
@@ -130,7 +134,21 @@ __global__ __launch_bounds__(ATTN_THREADS) void attention_kernel(const AttnArgs 
 
     const int nt = (p.N + ATTN_BK - 1) / ATTN_BK;
 
-    auto step = [&](int kt, const u32x4* cK, const u32x4* cV) {
+    // byte offsets of this lane's fragment reads inside a K / V buffer (the XOR
+    // swizzles do not depend on the 32-key subtile or the 16-key slice, which
+    // are plain displacements)
+    int offK[NKS], offV[NDS];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) offK[ks] = attn_pos_rows16<CK>(l32, 2 * ks + g) * 16;
+#pragma unroll
+    for (int ds = 0; ds < NDS; ++ds)
+        offV[ds] = trow * (CV * 16) + (((4 * ds + tchunk) ^ attn_swz_tr<CV>(trow)) << 4) + tbyte;
+
+    using MaskNo = std::integral_constant<bool, false>;
+    using MaskYes = std::integral_constant<bool, true>;
+    auto step = [&](int kt, const u32x4* cK, const u32x4* cV, auto MASKC) {
+        constexpr bool MASK = decltype(MASKC)::value;
+        const char* const kb = reinterpret_cast<const char*>(cK);
         // ---- S^T = K Q^T for the 64 keys of this block
         f32x16 sacc[2];
 #pragma unroll
@@ -140,12 +158,12 @@ __global__ __launch_bounds__(ATTN_THREADS) void attention_kernel(const AttnArgs 
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) {
                 Chunk kf;
-                kf.u = cK[attn_pos_rows16<CK>(32 * st + l32, 2 * ks + g)];
+                kf.u = *reinterpret_cast<const u32x4*>(kb + offK[ks] + st * (32 * CK * 16));
                 sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, sacc[st], 0, 0, 0);
             }
         }
         // keys past the end of the sequence do not take part
-        if ((kt + 1) * ATTN_BK > p.N) {
+        if (MASK) {
 #pragma unroll
             for (int st = 0; st < 2; ++st)
 #pragma unroll
@@ -189,12 +207,10 @@ __global__ __launch_bounds__(ATTN_THREADS) void attention_kernel(const AttnArgs 
         for (int st = 0; st < 2; ++st)
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                const int r0 = 32 * st + 16 * kk + trow;
 #pragma unroll
                 for (int ds = 0; ds < NDS; ++ds) {
-                    const int ch = 4 * ds + tchunk;
-                    const char* a0 = vb + r0 * (CV * 16) + ((ch ^ attn_swz_tr<CV>(r0)) << 4) + tbyte;
-                    const char* a1 = vb + (r0 + 8) * (CV * 16) + ((ch ^ attn_swz_tr<CV>(r0 + 8)) << 4) + tbyte;
+                    const char* a0 = vb + offV[ds] + (32 * st + 16 * kk) * (CV * 16);
+                    const char* a1 = a0 + 8 * (CV * 16);
                     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0));
                     const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a1));
                     const u32x2 l2 = *reinterpret_cast<const u32x2*>(&lo), h2 = *reinterpret_cast<const u32x2*>(&hi);
@@ -205,19 +221,34 @@ __global__ __launch_bounds__(ATTN_THREADS) void attention_kernel(const AttnArgs 
             }
     };
 
-    // ---- main loop over key blocks, double buffered
-    dma_tile(0, sK0, sV0);
-    for (int kt = 0; kt < nt; kt += 2) {
+    // ---- main loop over key blocks, double buffered.  Before each step: wait
+    // for the own loads of block kt, barrier (block kt has landed for everyone
+    // and everyone is done with block kt - 1), then start the loads of block
+    // kt + 1 into the buffer block kt - 1 was in.  Only the last block can hold
+    // keys past the end.
+    auto sync = [&]() {
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        __syncthreads();                                   // block kt has landed; everyone is done with block kt - 1
-        if (kt + 1 < nt) dma_tile(kt + 1, sK1, sV1);
-        step(kt, sK0, sV0);
-        if (kt + 1 < nt) {
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-            __syncthreads();
-            if (kt + 2 < nt) dma_tile(kt + 2, sK0, sV0);
-            step(kt + 1, sK1, sV1);
-        }
+        __syncthreads();
+    };
+    dma_tile(0, sK0, sV0);
+    int kt = 0;
+    for (; kt + 2 < nt; kt += 2) {
+        sync();
+        dma_tile(kt + 1, sK1, sV1);
+        step(kt, sK0, sV0, MaskNo{});
+        sync();
+        dma_tile(kt + 2, sK0, sV0);
+        step(kt + 1, sK1, sV1, MaskNo{});
+    }
+    if (ODD) {
+        sync();
+        step(kt, sK0, sV0, MaskYes{});
+    } else {
+        sync();
+        dma_tile(kt + 1, sK1, sV1);
+        step(kt, sK0, sV0, MaskNo{});
+        sync();
+        step(kt + 1, sK1, sV1, MaskYes{});
     }
 
     // ---- divide by the row sums and store: register v of subtile ds is value
