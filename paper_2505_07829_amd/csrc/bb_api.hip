@@ -550,7 +550,7 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
     if ((d != 64 && d != 128) || (dv != 64 && dv != 128)) return BB_ERR_SHAPE;
     if (M > (1 << 24) || N > (1 << 24)) return BB_ERR_SHAPE;
     const int64_t tiles_q = (M + ATTN_BQ - 1) / ATTN_BQ;
-    if (B * tiles_q > 0x7fffffffLL) return BB_ERR_SHAPE;            // one workgroup per (problem, query block)
+    if (B * tiles_q > 0x7ffffff0LL) return BB_ERR_SHAPE;            // one workgroup per (problem, query block)
     if (B == 0 || M == 0) return BB_OK;
     if (!Q || !K || !V || !O) return BB_ERR_NULL;
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O)) return BB_ERR_ALIGN;
@@ -571,8 +571,9 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
     a.M = (int)M;
     a.N = (int)N;
     a.tiles_q = (int)tiles_q;
+    a.wgs_per_xcd = (int)((B * tiles_q + 7) / 8);
     a.c = (float)(1.4426950408889634 / std::sqrt((double)d));
-    const dim3 grid((unsigned)(B * tiles_q)), block(ATTN_THREADS);
+    const dim3 grid((unsigned)(8 * a.wgs_per_xcd)), block(ATTN_THREADS);
     prof_begin(st);
     const bool odd = ((N + ATTN_BK - 1) / ATTN_BK) & 1;
     auto go = [&](auto DKC, auto DVC) {

@@ -41,12 +41,14 @@ struct AttnArgs {
     u16* O;
     int B, M, N;
     int tiles_q;        // ceil(M / 128)
+    int wgs_per_xcd;    // ceil(B * tiles_q / 8)
     float c;            // log2(e) / sqrt(DK)
 };
 
 constexpr int ATTN_THREADS = 256;
 constexpr int ATTN_BQ = 128;      // queries per workgroup
 constexpr int ATTN_BK = 64;       // keys per step
+constexpr float ATTN_SLACK = 8.f; // log2 of the largest significand a row keeps before its exponent moves
 
 // chunk position of (row, chunk) in an LDS tile with CPR 16-byte chunks per row,
 // for reads that take 16 consecutive rows at one chunk index (128-bit fragment
@@ -76,7 +78,12 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attention_kernel(const AttnAr
     const int t = threadIdx.x, lane = t & 63;
     const int w = __builtin_amdgcn_readfirstlane(t >> 6);
     const int l32 = lane & 31, g = lane >> 5;
-    const int b = blockIdx.x / p.tiles_q, qt = blockIdx.x % p.tiles_q;
+    // workgroup id -> XCD (id % 8) -> a contiguous range of (problem, query
+    // block) pairs per XCD: the workgroups resident on one XCD then work on
+    // the same one or two problems and share their K and V blocks in its L2
+    const int lin = (blockIdx.x & 7) * p.wgs_per_xcd + (blockIdx.x >> 3);
+    if (lin >= p.B * p.tiles_q) return;
+    const int b = lin / p.tiles_q, qt = lin % p.tiles_q;
     const int q = qt * ATTN_BQ + 32 * w + l32;          // this lane's query
     const u16* const Kb = p.K + (size_t)b * p.N * DK;
     const u16* const Vb = p.V + (size_t)b * p.N * DV;
@@ -146,22 +153,52 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attention_kernel(const AttnAr
 
     using MaskNo = std::integral_constant<bool, false>;
     using MaskYes = std::integral_constant<bool, true>;
+    // One key block.  The instruction stream is laid out by hand in three
+    // regions: (A) the score product, fragment reads running PDK matrix
+    // instructions ahead; (B) the first value fragments are requested, then the
+    // softmax arithmetic runs while they arrive; (C) the output product, its
+    // fragment reads PDV matrix instructions ahead.  A second workgroup on the
+    // same compute unit fills the matrix pipeline during (B).
+    constexpr int NS = 2 * NKS, NPV = 4 * NDS;        // matrix instructions of (A) and (C)
+    constexpr int PDK = 4, PDV = 4;
     auto step = [&](int kt, const u32x4* cK, const u32x4* cV, auto MASKC) {
         constexpr bool MASK = decltype(MASKC)::value;
         const char* const kb = reinterpret_cast<const char*>(cK);
-        // ---- S^T = K Q^T for the 64 keys of this block
+        const char* const vb = reinterpret_cast<const char*>(cV);
+        // ---- (A) S^T = K Q^T for the 64 keys of this block
+        Chunk kf[NS];
+#pragma unroll
+        for (int i = 0; i < NS; ++i)
+            kf[i].u = *reinterpret_cast<const u32x4*>(kb + offK[i % NKS] + (i / NKS) * (32 * CK * 16));
         f32x16 sacc[2];
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) sacc[st][v] = 0.f;
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) {
-                Chunk kf;
-                kf.u = *reinterpret_cast<const u32x4*>(kb + offK[ks] + st * (32 * CK * 16));
-                sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, sacc[st], 0, 0, 0);
-            }
+            for (int ks = 0; ks < NKS; ++ks)
+                sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[st * NKS + ks].v, qf[ks].v, sacc[st], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_group_barrier(0x100, PDK, 0);
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i + PDK < NS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- (B) first value fragments, then the softmax arithmetic
+        Chunk vf[NPV];
+        auto vread = [&](int i) {           // fragment of matrix instruction i = (st, kk, ds)
+            const char* a0 = vb + offV[i % NDS] + (16 * (i / NDS)) * (CV * 16);
+            const char* a1 = a0 + 8 * (CV * 16);
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a1));
+            const u32x2 l2 = *reinterpret_cast<const u32x2*>(&lo), h2 = *reinterpret_cast<const u32x2*>(&hi);
+            vf[i].u = u32x4{l2[0], l2[1], h2[0], h2[1]};
+        };
+#pragma unroll
+        for (int i = 0; i < PDV; ++i) vread(i);
+        __builtin_amdgcn_sched_barrier(0);
         // keys past the end of the sequence do not take part
         if (MASK) {
 #pragma unroll
@@ -172,15 +209,28 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attention_kernel(const AttnAr
                     if (key >= p.N) sacc[st][v] = -INFINITY;
                 }
         }
-        // ---- exponentiate as (significands, row exponent): exponent = running maximum
+        // exponentiate as (significands, row exponent): exponent = running maximum
         float mloc = -INFINITY;
 #pragma unroll
         for (int st = 0; st < 2; ++st)
 #pragma unroll
             for (int v = 0; v < 16; ++v) mloc = fmaxf(mloc, sacc[st][v]);
         mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-        const float m_new = fmaxf(m_run, mloc);
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * p.c);     // brings the accumulators to the new exponent
+        // The row exponent moves only when the block maximum exceeds it by more
+        // than ATTN_SLACK binary orders of magnitude (significands then stay
+        // below 2^ATTN_SLACK, far inside fp32 and bf16 range); a wavefront
+        // none of whose rows moves skips the rescaling of its accumulators.
+        const bool moves = mloc * p.c > m_run * p.c + ATTN_SLACK;       // false for NaN-free equal/lower maxima
+        const float m_new = moves ? mloc : m_run;
+        if (__builtin_amdgcn_ballot_w64(moves) != 0) {
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * p.c);   // brings the accumulators to the new exponent; 1 where the row stays
+            l_run *= alpha;
+#pragma unroll
+            for (int ds = 0; ds < NDS; ++ds)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) oacc[ds][v] *= alpha;
+        }
+        m_run = m_new;
         const float mc = m_new * p.c;
         float lsum = 0.f;
         Chunk pb[2][2];
@@ -195,30 +245,21 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attention_kernel(const AttnAr
                     lsum += p0 + p1;
                     pb[st][kk].u[h] = pack_bf16(p0, p1);
                 }
-        l_run = fmaf(l_run, alpha, lsum);
-        m_run = m_new;
+        l_run += lsum;
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- (C) O^T += V^T P^T
 #pragma unroll
-        for (int ds = 0; ds < NDS; ++ds)
+        for (int i = PDV; i < NPV; ++i) vread(i);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) oacc[ds][v] *= alpha;
-        // ---- O^T += V^T P^T
-        const char* vb = reinterpret_cast<const char*>(cV);
+        for (int i = 0; i < NPV; ++i)
+            oacc[i % NDS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i].v, pb[i / (2 * NDS)][(i / NDS) & 1].v,
+                                                                    oacc[i % NDS], 0, 0, 0);
 #pragma unroll
-        for (int st = 0; st < 2; ++st)
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-#pragma unroll
-                for (int ds = 0; ds < NDS; ++ds) {
-                    const char* a0 = vb + offV[ds] + (32 * st + 16 * kk) * (CV * 16);
-                    const char* a1 = a0 + 8 * (CV * 16);
-                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0));
-                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a1));
-                    const u32x2 l2 = *reinterpret_cast<const u32x2*>(&lo), h2 = *reinterpret_cast<const u32x2*>(&hi);
-                    Chunk vf;
-                    vf.u = u32x4{l2[0], l2[1], h2[0], h2[1]};
-                    oacc[ds] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pb[st][kk].v, oacc[ds], 0, 0, 0);
-                }
-            }
+        for (int i = 0; i < NPV; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i + PDV < NPV) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     // ---- main loop over key blocks, double buffered.  Before each step: wait
