@@ -188,6 +188,61 @@ def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
     return res
 
 
+ATTN_WORKLOAD = dict(B=32, M=4096, N=4096, d=128, dv=128)   # 32 heads, 4096 x 4096, head dimension 128
+
+
+def run_attention(steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
+    """bb_attention on ATTN_WORKLOAD (synthetic N(0,1) Q, K, V): time per call from
+    HIP events on the launch stream, roofline against the bf16 matrix peak with
+    4 B M N d useful flops, and parity on sampled query rows against the oracle."""
+    w = ATTN_WORKLOAD
+    cpu = bb_inputs.make_attn(w["B"], w["M"], w["N"], w["d"], w["dv"], seed=0)
+    Q, K, V = [t.cuda() for t in cpu]
+    O = torch.empty((w["B"], w["M"], w["dv"]), dtype=torch.bfloat16, device="cuda")
+    for _ in range(warmup):
+        bb.bb_attention(Q, K, V, O)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        bb.bb_attention(Q, K, V, O)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    bb.bb_profile_enable(True)
+    per = []
+    for _ in range(steps):
+        bb.bb_attention(Q, K, V, O)
+        per.append(dict(bb.bb_profile_last())["attention"])
+    bb.bb_profile_enable(False)
+    k_ms = float(np.mean(per))
+    flops = 2.0 * w["B"] * w["M"] * w["N"] * (w["d"] + w["dv"])
+    achieved = flops / (k_ms * 1e-3) / 1e12
+    res = {
+        "workload": "attention B=%(B)d M=%(M)d N=%(N)d d=%(d)d dv=%(dv)d" % w, "op": "attention",
+        "ms_per_step": ms, "tflops": flops / (ms * 1e-3) / 1e12, "kernels_ms": {"attention": k_ms},
+        "roofline": {"kernel": "attention", "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "algorithmic": flops},
+    }
+    if with_cpu:
+        rng = np.random.default_rng(0)
+        rows = sorted(set(int(r) for r in rng.integers(0, w["B"] * w["M"], size=65536)))
+        t0 = time.perf_counter()
+        ref = orc.attention(*cpu, rows=rows)
+        sec = time.perf_counter() - t0
+        o = O.reshape(-1, w["dv"])[rows].float().cpu().numpy().astype(np.float64)
+        err = float((np.linalg.norm(o - ref, axis=1) / np.linalg.norm(ref, axis=1)).max())
+        res["parity"] = {"max_row_rel_err": err, "rows_checked": len(rows), "tolerance": 2e-2}
+        row_flops = flops / (w["B"] * w["M"])
+        res["cpu_baseline"] = {"value": row_flops * len(rows) / sec / 1e12, "unit": "TFLOP/s",
+                               "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": f"{len(rows)} of {w['B'] * w['M']} query rows, {sec:.2f} s"}
+    del Q, K, V, O
+    torch.cuda.empty_cache()
+    return res
+
+
 def _oracle(orc, cfg, cpu, rows):
     if cfg.op == "ffn":
         return orc.rmsnorm_swiglu_ffn(*cpu, cfg.eps, rows=rows)
@@ -231,6 +286,7 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--also", default="c2", help="comma list of further workloads reported in 'others' "
                     "(the decode shape c2 is reported as 'decode')")
+    ap.add_argument("--no-attention", action="store_true", help="skip the attention workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing / parity sample")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -254,6 +310,8 @@ def main():
     others = {}
     for name in [w for w in args.also.split(",") if w and w != args.workload]:
         others[name] = run_workload(name, args.steps, args.warmup, not args.no_cpu, torch, bb, bb_inputs, orc, np)
+    attn = None if args.no_attention else run_attention(args.steps, args.warmup, not args.no_cpu, torch, bb,
+                                                        bb_inputs, orc, np)
     peaks = calibrate(torch, bb)
     bb.bb_shutdown()
 
@@ -284,6 +342,8 @@ def main():
             "roofline": d["roofline"], "cpu_baseline": d.get("cpu_baseline"), "parity": d.get("parity"),
             "kernels_ms": d["kernels_ms"], "unfused_ms_per_step": d["unfused_ms_per_step"],
         }
+    if attn is not None:
+        line["attention"] = attn
     if others:
         line["others"] = others
     print(json.dumps(line))

@@ -575,11 +575,13 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
     a.c = (float)(1.4426950408889634 / std::sqrt((double)d));
     const dim3 grid((unsigned)(8 * a.wgs_per_xcd)), block(ATTN_THREADS);
     prof_begin(st);
-    const bool odd = ((N + ATTN_BK - 1) / ATTN_BK) & 1;
+    const int64_t nt = (N + ATTN_BK - 1) / ATTN_BK;
+    const int tail = nt == 1 ? 1 : ((nt & 1) ? 3 : 2);
     auto go = [&](auto DKC, auto DVC) {
         constexpr int DK = decltype(DKC)::value, DV = decltype(DVC)::value;
-        if (odd) hipLaunchKernelGGL((attention_kernel<DK, DV, true>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((attention_kernel<DK, DV, false>), grid, block, 0, st, a);
+        if (tail == 1) hipLaunchKernelGGL((attention_kernel<DK, DV, 1>), grid, block, 0, st, a);
+        else if (tail == 2) hipLaunchKernelGGL((attention_kernel<DK, DV, 2>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((attention_kernel<DK, DV, 3>), grid, block, 0, st, a);
     };
     using I64 = std::integral_constant<int, 64>;
     using I128 = std::integral_constant<int, 128>;

@@ -64,9 +64,11 @@ __device__ __forceinline__ int attn_swz_tr(int row) {
     return CPR == 16 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
 }
 
-// ODD: the number of key blocks is odd (a template parameter, so that the
-// double-buffered loop below has no branch that merges the accumulators).
-template <int DK, int DV, bool ODD>
+// TAIL: key blocks left after the double-buffered loop, which runs while a
+// pair of blocks AND a complete block to prefetch remain: 1 (one block in
+// all), 2 (even count) or 3 (odd count).  A template parameter, so that no
+// branch merges the accumulators and only the tail handles keys past the end.
+template <int DK, int DV, int TAIL>
 __global__ __launch_bounds__(ATTN_THREADS, 2) void attention_kernel(const AttnArgs p) {
     constexpr int CK = DK / 8, CV = DV / 8;          // 16-byte chunks per K / V row
     constexpr int NKS = DK / 16;                     // contraction slices of the first product
@@ -87,7 +89,6 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attention_kernel(const AttnAr
     const int q = qt * ATTN_BQ + 32 * w + l32;          // this lane's query
     const u16* const Kb = p.K + (size_t)b * p.N * DK;
     const u16* const Vb = p.V + (size_t)b * p.N * DV;
-    const u16* const zsrc = reinterpret_cast<const u16*>(&gemm_zero_chunk);
 
     // Q fragments: B operand of S^T = K Q^T: column = query, 8 consecutive features
     Chunk qf[NKS];
@@ -95,30 +96,48 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attention_kernel(const AttnAr
     for (int ks = 0; ks < NKS; ++ks)
         qf[ks].u = (q < p.M) ? ldg16(p.Q + ((size_t)b * p.M + q) * DK + 16 * ks + 8 * g) : zero4();
 
-    // load-to-LDS roles: an instruction fills 64 chunks = 64 / CPR rows
-    auto dma_tile = [&](int kt, u32x4* dK, u32x4* dV) {
+    // load-to-LDS roles: an instruction fills 64 chunks = 64 / CPR rows of a
+    // tile; instruction j of this wavefront fills LDS chunks (NI w + j) 64 ...
+    // Lane offsets inside a complete block are loop constants; the block's base
+    // advances as a uniform pointer.  In the last block rows past the end of
+    // the sequence load the last valid row instead (their scores are masked,
+    // their probabilities exactly zero).
+    constexpr int RPK = 64 / CK, NIK = ATTN_BK / RPK / 4;     // rows per instruction, instructions per wavefront
+    constexpr int RPV = 64 / CV, NIV = ATTN_BK / RPV / 4;
+    constexpr int NDMA = NIK + NIV;
+    int rowKd[NIK], rowVd[NIV];
+    u32 offKd[NIK], offVd[NIV];
+#pragma unroll
+    for (int j = 0; j < NIK; ++j) {
+        const int row = RPK * (NIK * w + j) + lane / CK, pos = lane % CK;
+        const int chunk = CK == 16 ? (pos ^ (row & 15)) : (pos ^ ((row >> 1) & 7));
+        rowKd[j] = row;
+        offKd[j] = (u32)(row * DK + 8 * chunk);
+    }
+#pragma unroll
+    for (int j = 0; j < NIV; ++j) {
+        const int row = RPV * (NIV * w + j) + lane / CV, pos = lane % CV;
+        const int chunk = pos ^ attn_swz_tr<CV>(row);
+        rowVd[j] = row;
+        offVd[j] = (u32)(row * DV + 8 * chunk);
+    }
+    using LastNo = std::integral_constant<bool, false>;
+    using LastYes = std::integral_constant<bool, true>;
+    auto dma_tile = [&](int kt, u32x4* dK, u32x4* dV, auto LASTC) {
+        constexpr bool LAST = decltype(LASTC)::value;
         const int key0 = kt * ATTN_BK;
-        {
-            constexpr int RPI = 64 / CK, NI = ATTN_BK / RPI / 4;     // rows per instruction, instructions per wavefront
+        const u16* const kbase = Kb + (size_t)key0 * DK;
+        const u16* const vbase = Vb + (size_t)key0 * DV;
+        const int rmax = p.N - 1 - key0;                  // last valid row of the block
 #pragma unroll
-            for (int j = 0; j < NI; ++j) {
-                const int row = RPI * (NI * w + j) + lane / CK;       // key row of the tile
-                const int pos = lane % CK;
-                const int chunk = CK == 16 ? (pos ^ (row & 15)) : (pos ^ ((row >> 1) & 7));
-                const u16* src = (key0 + row < p.N) ? Kb + (size_t)(key0 + row) * DK + 8 * chunk : zsrc;
-                load_to_lds16(src, dK + (NI * w + j) * 64);
-            }
+        for (int j = 0; j < NIK; ++j) {
+            const u32 off = LAST ? offKd[j] - (u32)(max(rowKd[j] - rmax, 0) * DK) : offKd[j];
+            load_to_lds16(kbase + off, dK + (NIK * w + j) * 64);
         }
-        {
-            constexpr int RPI = 64 / CV, NI = ATTN_BK / RPI / 4;
 #pragma unroll
-            for (int j = 0; j < NI; ++j) {
-                const int row = RPI * (NI * w + j) + lane / CV;
-                const int pos = lane % CV;
-                const int chunk = pos ^ attn_swz_tr<CV>(row);
-                const u16* src = (key0 + row < p.N) ? Vb + (size_t)(key0 + row) * DV + 8 * chunk : zsrc;
-                load_to_lds16(src, dV + (NI * w + j) * 64);
-            }
+        for (int j = 0; j < NIV; ++j) {
+            const u32 off = LAST ? offVd[j] - (u32)(max(rowVd[j] - rmax, 0) * DV) : offVd[j];
+            load_to_lds16(vbase + off, dV + (NIV * w + j) * 64);
         }
     };
 
@@ -184,6 +203,9 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attention_kernel(const AttnAr
         for (int i = 0; i < NS; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             if (i + PDK < NS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            // the load-to-LDS instructions of the next block (issued by the
+            // caller just before this step) spread evenly between them
+            if ((i * NDMA) / NS != ((i + 1) * NDMA) / NS) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
         // ---- (B) first value fragments, then the softmax arithmetic
@@ -266,30 +288,39 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attention_kernel(const AttnAr
     // for the own loads of block kt, barrier (block kt has landed for everyone
     // and everyone is done with block kt - 1), then start the loads of block
     // kt + 1 into the buffer block kt - 1 was in.  Only the last block can hold
-    // keys past the end.
+    // keys past the end: it is loaded and processed in the tail.
     auto sync = [&]() {
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
         __syncthreads();
     };
-    dma_tile(0, sK0, sV0);
+    if (TAIL == 1) dma_tile(0, sK0, sV0, LastYes{}); else dma_tile(0, sK0, sV0, LastNo{});
     int kt = 0;
-    for (; kt + 2 < nt; kt += 2) {
+    for (; kt + 3 < nt; kt += 2) {
         sync();
-        dma_tile(kt + 1, sK1, sV1);
+        dma_tile(kt + 1, sK1, sV1, LastNo{});
         step(kt, sK0, sV0, MaskNo{});
         sync();
-        dma_tile(kt + 2, sK0, sV0);
+        dma_tile(kt + 2, sK0, sV0, LastNo{});
         step(kt + 1, sK1, sV1, MaskNo{});
     }
-    if (ODD) {
+    if (TAIL == 1) {
         sync();
         step(kt, sK0, sV0, MaskYes{});
-    } else {
+    } else if (TAIL == 2) {
         sync();
-        dma_tile(kt + 1, sK1, sV1);
+        dma_tile(kt + 1, sK1, sV1, LastYes{});
         step(kt, sK0, sV0, MaskNo{});
         sync();
         step(kt + 1, sK1, sV1, MaskYes{});
+    } else {
+        sync();
+        dma_tile(kt + 1, sK1, sV1, LastNo{});
+        step(kt, sK0, sV0, MaskNo{});
+        sync();
+        dma_tile(kt + 2, sK0, sV0, LastYes{});
+        step(kt + 1, sK1, sV1, MaskNo{});
+        sync();
+        step(kt + 2, sK0, sV0, MaskYes{});
     }
 
     // ---- divide by the row sums and store: register v of subtile ds is value
