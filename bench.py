@@ -287,6 +287,8 @@ def main():
     ap.add_argument("--also", default="c2", help="comma list of further workloads reported in 'others' "
                     "(the decode shape c2 is reported as 'decode')")
     ap.add_argument("--no-attention", action="store_true", help="skip the attention workload")
+    ap.add_argument("--attention-only", action="store_true",
+                    help="time only the attention workload and print its block as the line (for profiler runs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing / parity sample")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -306,6 +308,16 @@ def main():
         sys.exit(1)
     bb.load()          # fails loudly if the HIP library has not been built
 
+    if args.attention_only:
+        attn = run_attention(args.steps, args.warmup, not args.no_cpu, torch, bb, bb_inputs, orc, np)
+        bb.bb_shutdown()
+        print(json.dumps({"metric": "attention TFLOP/s", "value": attn["tflops"], "unit": "TFLOP/s", "n_gpus": 1,
+                          "steps": args.steps, "warmup": args.warmup, "ms_per_step": attn["ms_per_step"],
+                          "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+                          "data": "synthetic", "config": {"workload": attn["workload"]},
+                          "roofline": attn["roofline"], "cpu_baseline": attn.get("cpu_baseline"),
+                          "parity": attn.get("parity")}))
+        return
     primary = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu, torch, bb, bb_inputs, orc, np)
     others = {}
     for name in [w for w in args.also.split(",") if w and w != args.workload]:

@@ -184,18 +184,21 @@ int bb_layernorm_matmul_unfused(const void* X, const void* gamma,
  * and the row sums of the exponentiated scores, then the division), with the
  * feature and value dimensions unsplit.  The exponentiated score blocks are
  * the Appendix's significand-exponent pairs in row-wise form: one exponent per
- * query row (the running maximum of its scaled scores), accumulators rescaled
- * to the larger exponent before a block is added, so large scores neither
- * overflow nor lose the row.
+ * query row, accumulators rescaled to the larger exponent before a block is
+ * added, so large scores neither overflow nor lose the row.  A row's exponent
+ * is a running maximum of its scaled scores that moves only when a block's
+ * maximum exceeds it by more than 8 binary orders of magnitude (significands
+ * stay below 2^8).
  *
  *   Q [B, M, d], K [B, N, d], V [B, N, dv], O [B, M, dv]   bf16, row-major,
  *   densely packed, device pointers, 16-byte aligned; O overlaps no input.
  *
- * d and dv are 64 or 128; B, M >= 0 (zero: nothing is done), N >= 1.  Scores
- * are accumulated in fp32, scaled and exponentiated in fp32 (base-2
- * exponential of score * log2(e)/sqrt(d)), rounded to bf16 as the operand of
- * the second product; output sums and row sums in fp32, the quotient rounded
- * to bf16 once.  No workspace.  Errors as for the other operators.
+ * d and dv are 64 or 128; B, M >= 0 (zero: nothing is done), 1 <= N < 2^24,
+ * M <= 2^24.  Scores are accumulated in fp32, scaled and exponentiated in
+ * fp32 (base-2 exponential of score * log2(e)/sqrt(d)), rounded to bf16 as
+ * the operand of the second product; output sums and row sums in fp32, the
+ * quotient rounded to bf16 once.  No workspace.  Errors as for the other
+ * operators.
  */
 int bb_attention(const void* Q, const void* K, const void* V, void* O,
                  int64_t B, int64_t M, int64_t N, int64_t d, int64_t dv,

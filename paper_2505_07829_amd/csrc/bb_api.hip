@@ -548,7 +548,7 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
                  int64_t d, int64_t dv, void* stream) {
     if (B < 0 || M < 0 || N < 1) return BB_ERR_SHAPE;
     if ((d != 64 && d != 128) || (dv != 64 && dv != 128)) return BB_ERR_SHAPE;
-    if (M > (1 << 24) || N > (1 << 24)) return BB_ERR_SHAPE;
+    if (M > (1 << 24) || N >= (1 << 24)) return BB_ERR_SHAPE;   // 32-bit byte offsets inside one problem's K and V
     const int64_t tiles_q = (M + ATTN_BQ - 1) / ATTN_BQ;
     if (B * tiles_q > 0x7ffffff0LL) return BB_ERR_SHAPE;            // one workgroup per (problem, query block)
     if (B == 0 || M == 0) return BB_OK;
@@ -576,12 +576,13 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
     const dim3 grid((unsigned)(8 * a.wgs_per_xcd)), block(ATTN_THREADS);
     prof_begin(st);
     const int64_t nt = (N + ATTN_BK - 1) / ATTN_BK;
-    const int tail = nt == 1 ? 1 : ((nt & 1) ? 3 : 2);
+    const int tail = nt <= 4 ? (int)nt : ((nt & 1) ? 3 : 4);     // iterations left after the main loop
     auto go = [&](auto DKC, auto DVC) {
         constexpr int DK = decltype(DKC)::value, DV = decltype(DVC)::value;
         if (tail == 1) hipLaunchKernelGGL((attention_kernel<DK, DV, 1>), grid, block, 0, st, a);
         else if (tail == 2) hipLaunchKernelGGL((attention_kernel<DK, DV, 2>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((attention_kernel<DK, DV, 3>), grid, block, 0, st, a);
+        else if (tail == 3) hipLaunchKernelGGL((attention_kernel<DK, DV, 3>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((attention_kernel<DK, DV, 4>), grid, block, 0, st, a);
     };
     using I64 = std::integral_constant<int, 64>;
     using I128 = std::integral_constant<int, 128>;

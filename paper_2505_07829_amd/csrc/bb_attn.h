@@ -64,10 +64,10 @@ __device__ __forceinline__ int attn_swz_tr(int row) {
     return CPR == 16 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
 }
 
-// TAIL: key blocks left after the double-buffered loop, which runs while a
-// pair of blocks AND a complete block to prefetch remain: 1 (one block in
-// all), 2 (even count) or 3 (odd count).  A template parameter, so that no
-// branch merges the accumulators and only the tail handles keys past the end.
+// TAIL: iterations left after the main loop (1 .. 4; the loop takes two
+// complete iterations per trip while at least five key blocks remain).  A
+// template parameter, so that no branch merges the accumulators and only the
+// unrolled tail loads and masks the last key block.
 template <int DK, int DV, int TAIL>
 __global__ __launch_bounds__(ATTN_THREADS, 2) void attention_kernel(const AttnArgs p) {
     constexpr int CK = DK / 8, CV = DV / 8;          // 16-byte chunks per K / V row
@@ -77,8 +77,8 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attention_kernel(const AttnAr
     __shared__ u32x4 sK0[ATTN_BK * CK], sK1[ATTN_BK * CK];
     __shared__ u32x4 sV0[ATTN_BK * CV], sV1[ATTN_BK * CV];
 
-    const int t = threadIdx.x, lane = t & 63;
-    const int w = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, g = lane >> 5;
     // workgroup id -> XCD (id % 8) -> a contiguous range of (problem, query
     // block) pairs per XCD: the workgroups resident on one XCD then work on
@@ -121,23 +121,27 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attention_kernel(const AttnAr
         rowVd[j] = row;
         offVd[j] = (u32)(row * DV + 8 * chunk);
     }
-    using LastNo = std::integral_constant<bool, false>;
-    using LastYes = std::integral_constant<bool, true>;
-    auto dma_tile = [&](int kt, u32x4* dK, u32x4* dV, auto LASTC) {
-        constexpr bool LAST = decltype(LASTC)::value;
+    // which: 0 nothing, 1 a complete block, 2 the last block
+    auto dma_k = [&](int kt, u32x4* dK, auto WHICH) {
+        constexpr int W = decltype(WHICH)::value;
+        if (W == 0) return;
         const int key0 = kt * ATTN_BK;
-        const u16* const kbase = Kb + (size_t)key0 * DK;
-        const u16* const vbase = Vb + (size_t)key0 * DV;
         const int rmax = p.N - 1 - key0;                  // last valid row of the block
 #pragma unroll
         for (int j = 0; j < NIK; ++j) {
-            const u32 off = LAST ? offKd[j] - (u32)(max(rowKd[j] - rmax, 0) * DK) : offKd[j];
-            load_to_lds16(kbase + off, dK + (NIK * w + j) * 64);
+            const u32 off = W == 2 ? offKd[j] - (u32)(max(rowKd[j] - rmax, 0) * DK) : offKd[j];
+            load_to_lds16(reinterpret_cast<const char*>(Kb) + (u32)(2 * (off + (u32)(key0 * DK))), dK + (NIK * w + j) * 64);
         }
+    };
+    auto dma_v = [&](int kt, u32x4* dV, auto WHICH) {
+        constexpr int W = decltype(WHICH)::value;
+        if (W == 0) return;
+        const int key0 = kt * ATTN_BK;
+        const int rmax = p.N - 1 - key0;
 #pragma unroll
         for (int j = 0; j < NIV; ++j) {
-            const u32 off = LAST ? offVd[j] - (u32)(max(rowVd[j] - rmax, 0) * DV) : offVd[j];
-            load_to_lds16(vbase + off, dV + (NIV * w + j) * 64);
+            const u32 off = W == 2 ? offVd[j] - (u32)(max(rowVd[j] - rmax, 0) * DV) : offVd[j];
+            load_to_lds16(reinterpret_cast<const char*>(Vb) + (u32)(2 * (off + (u32)(key0 * DV))), dV + (NIV * w + j) * 64);
         }
     };
 
@@ -170,82 +174,72 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attention_kernel(const AttnAr
     for (int ds = 0; ds < NDS; ++ds)
         offV[ds] = trow * (CV * 16) + (((4 * ds + tchunk) ^ attn_swz_tr<CV>(trow)) << 4) + tbyte;
 
-    using MaskNo = std::integral_constant<bool, false>;
-    using MaskYes = std::integral_constant<bool, true>;
-    // One key block.  The instruction stream is laid out by hand in three
-    // regions: (A) the score product, fragment reads running PDK matrix
-    // instructions ahead; (B) the first value fragments are requested, then the
-    // softmax arithmetic runs while they arrive; (C) the output product, its
-    // fragment reads PDV matrix instructions ahead.  A second workgroup on the
-    // same compute unit fills the matrix pipeline during (B).
-    constexpr int NS = 2 * NKS, NPV = 4 * NDS;        // matrix instructions of (A) and (C)
-    constexpr int PDK = 4, PDV = 4;
-    auto step = [&](int kt, const u32x4* cK, const u32x4* cV, auto MASKC) {
-        constexpr bool MASK = decltype(MASKC)::value;
-        const char* const kb = reinterpret_cast<const char*>(cK);
-        const char* const vb = reinterpret_cast<const char*>(cV);
-        // ---- (A) S^T = K Q^T for the 64 keys of this block
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    constexpr int NS = 2 * NKS, NPV = 4 * NDS;        // matrix instructions of the two products
+    constexpr int PDK = 2, PDV = 2;                   // fragment reads run this many matrix instructions ahead
+
+    f32x16 sc[2][2];                                  // scores of the blocks of even / odd index, two 32-key subtiles each
+    float mloc = -INFINITY;                           // maximum of the block whose scores were computed last
+    Chunk pb[2][2];                                   // exponentiated scores of a block as matrix operands
+    Chunk vf[NPV];
+
+    auto kread = [&](const char* kb, int i) -> u32x4 {
+        return *reinterpret_cast<const u32x4*>(kb + offK[i % NKS] + (i / NKS) * (32 * CK * 16));
+    };
+    auto vread = [&](const char* vb, int i) {          // fragment of matrix instruction i = (st, kk, ds)
+        const char* a0 = vb + offV[i % NDS] + (16 * (i / NDS)) * (CV * 16);
+        const char* a1 = a0 + 8 * (CV * 16);
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a1));
+        const u32x2 l2 = *reinterpret_cast<const u32x2*>(&lo), h2 = *reinterpret_cast<const u32x2*>(&hi);
+        vf[i].u = u32x4{l2[0], l2[1], h2[0], h2[1]};
+    };
+    // scores of one block: S^T = K Q^T into sc[PAR]
+    auto scores = [&](const char* kb, auto PARC) {
+        constexpr int PAR = decltype(PARC)::value;
         Chunk kf[NS];
 #pragma unroll
-        for (int i = 0; i < NS; ++i)
-            kf[i].u = *reinterpret_cast<const u32x4*>(kb + offK[i % NKS] + (i / NKS) * (32 * CK * 16));
-        f32x16 sacc[2];
+        for (int i = 0; i < NS; ++i) kf[i].u = kread(kb, i);
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) sacc[st][v] = 0.f;
+            for (int v = 0; v < 16; ++v) sc[PAR][st][v] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks)
-                sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[st * NKS + ks].v, qf[ks].v, sacc[st], 0, 0, 0);
+                sc[PAR][st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[st * NKS + ks].v, qf[ks].v, sc[PAR][st], 0, 0, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x100, PDK, 0);
-#pragma unroll
-        for (int i = 0; i < NS; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (i + PDK < NS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            // the load-to-LDS instructions of the next block (issued by the
-            // caller just before this step) spread evenly between them
-            if ((i * NDMA) / NS != ((i + 1) * NDMA) / NS) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        // ---- (B) first value fragments, then the softmax arithmetic
-        Chunk vf[NPV];
-        auto vread = [&](int i) {           // fragment of matrix instruction i = (st, kk, ds)
-            const char* a0 = vb + offV[i % NDS] + (16 * (i / NDS)) * (CV * 16);
-            const char* a1 = a0 + 8 * (CV * 16);
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a1));
-            const u32x2 l2 = *reinterpret_cast<const u32x2*>(&lo), h2 = *reinterpret_cast<const u32x2*>(&hi);
-            vf[i].u = u32x4{l2[0], l2[1], h2[0], h2[1]};
-        };
-#pragma unroll
-        for (int i = 0; i < PDV; ++i) vread(i);
-        __builtin_amdgcn_sched_barrier(0);
-        // keys past the end of the sequence do not take part
-        if (MASK) {
-#pragma unroll
-            for (int st = 0; st < 2; ++st)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int key = kt * ATTN_BK + 32 * st + 8 * (v >> 2) + 4 * g + (v & 3);
-                    if (key >= p.N) sacc[st][v] = -INFINITY;
-                }
-        }
-        // exponentiate as (significands, row exponent): exponent = running maximum
-        float mloc = -INFINITY;
+    };
+    // keys past the end of the sequence do not take part
+    auto mask = [&](int kt, auto PARC) {
+        constexpr int PAR = decltype(PARC)::value;
 #pragma unroll
         for (int st = 0; st < 2; ++st)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) mloc = fmaxf(mloc, sacc[st][v]);
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-        // The row exponent moves only when the block maximum exceeds it by more
-        // than ATTN_SLACK binary orders of magnitude (significands then stay
-        // below 2^ATTN_SLACK, far inside fp32 and bf16 range); a wavefront
-        // none of whose rows moves skips the rescaling of its accumulators.
-        const bool moves = mloc * p.c > m_run * p.c + ATTN_SLACK;       // false for NaN-free equal/lower maxima
+            for (int v = 0; v < 16; ++v) {
+                const int key = kt * ATTN_BK + 32 * st + 8 * (v >> 2) + 4 * g + (v & 3);
+                if (key >= p.N) sc[PAR][st][v] = -INFINITY;
+            }
+    };
+    auto block_max = [&](auto PARC) {
+        constexpr int PAR = decltype(PARC)::value;
+        float m = -INFINITY;
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) m = fmaxf(m, sc[PAR][st][v]);
+        mloc = fmaxf(m, __shfl_xor(m, 32));
+    };
+    // The row exponent moves only when the block maximum exceeds it by more
+    // than ATTN_SLACK binary orders of magnitude (significands then stay below
+    // 2^ATTN_SLACK, far inside fp32 and bf16 range); a wavefront none of whose
+    // rows moves skips the rescaling of its accumulators.
+    auto decide = [&]() {
+        const bool moves = mloc * p.c > m_run * p.c + ATTN_SLACK;
         const float m_new = moves ? mloc : m_run;
         if (__builtin_amdgcn_ballot_w64(moves) != 0) {
-            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * p.c);   // brings the accumulators to the new exponent; 1 where the row stays
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * p.c);   // 1 where the row stays
             l_run *= alpha;
 #pragma unroll
             for (int ds = 0; ds < NDS; ++ds)
@@ -253,74 +247,125 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attention_kernel(const AttnAr
                 for (int v = 0; v < 16; ++v) oacc[ds][v] *= alpha;
         }
         m_run = m_new;
-        const float mc = m_new * p.c;
+    };
+    // exponentiate the scores of a block as (significands, row exponent m_run)
+    auto exponentiate = [&](auto PARC) {
+        constexpr int PAR = decltype(PARC)::value;
+        const float mc = m_run * p.c;
         float lsum = 0.f;
-        Chunk pb[2][2];
 #pragma unroll
         for (int st = 0; st < 2; ++st)
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
                 for (int h = 0; h < 4; ++h) {
-                    const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[st][8 * kk + 2 * h], p.c, -mc));
-                    const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[st][8 * kk + 2 * h + 1], p.c, -mc));
+                    const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[PAR][st][8 * kk + 2 * h], p.c, -mc));
+                    const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[PAR][st][8 * kk + 2 * h + 1], p.c, -mc));
                     lsum += p0 + p1;
                     pb[st][kk].u[h] = pack_bf16(p0, p1);
                 }
         l_run += lsum;
-        __builtin_amdgcn_sched_barrier(0);
-        // ---- (C) O^T += V^T P^T
-#pragma unroll
-        for (int i = PDV; i < NPV; ++i) vread(i);
+    };
+    auto output_mfma = [&]() {
 #pragma unroll
         for (int i = 0; i < NPV; ++i)
             oacc[i % NDS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i].v, pb[i / (2 * NDS)][(i / NDS) & 1].v,
                                                                     oacc[i % NDS], 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < NPV; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (i + PDV < NPV) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
     };
-
-    // ---- main loop over key blocks, double buffered.  Before each step: wait
-    // for the own loads of block kt, barrier (block kt has landed for everyone
-    // and everyone is done with block kt - 1), then start the loads of block
-    // kt + 1 into the buffer block kt - 1 was in.  Only the last block can hold
-    // keys past the end: it is loaded and processed in the tail.
     auto sync = [&]() {
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
         __syncthreads();
     };
-    if (TAIL == 1) dma_tile(0, sK0, sV0, LastYes{}); else dma_tile(0, sK0, sV0, LastNo{});
-    int kt = 0;
-    for (; kt + 3 < nt; kt += 2) {
+
+    // One iteration t of the software pipeline (PAR = t % 2).  After the
+    // barrier (K block t + 1 and V block t have landed; everyone is done with
+    // K block t and V block t - 1, whose buffers the new loads overwrite):
+    //   region X: the matrix instructions of the NEXT block's scores,
+    //             S(t + 1) = K(t + 1) Q^T, interleaved with the exponentiation
+    //             of THIS block's scores (vector arithmetic) and with the
+    //             load-to-LDS instructions of K(t + 2) and V(t + 1);
+    //   region Y: the matrix instructions of O += P(t) V(t), interleaved with
+    //             the maximum of S(t + 1);
+    //   then the row exponents take S(t + 1) into account (rarely: rescaling).
+    // NEXT: block t + 1 exists; MASKN: it is the last one (keys past the end);
+    // KW / VW: what to load (0 nothing, 1 complete block, 2 last block).
+    auto iteration = [&](int t, auto PARC, auto NEXTC, auto MASKNC, auto KWC, auto VWC) {
+        constexpr int PAR = decltype(PARC)::value;
+        constexpr bool NEXT = decltype(NEXTC)::value != 0, MASKN = decltype(MASKNC)::value != 0;
+        constexpr int KW = decltype(KWC)::value, VW = decltype(VWC)::value;
+        constexpr int ND = (KW ? NIK : 0) + (VW ? NIV : 0);
+        using PARN = std::integral_constant<int, PAR ^ 1>;
+        const char* const kb = reinterpret_cast<const char*>(PAR ? sK0 : sK1);     // K(t + 1)
+        const char* const vb = reinterpret_cast<const char*>(PAR ? sV1 : sV0);     // V(t)
         sync();
-        dma_tile(kt + 1, sK1, sV1, LastNo{});
-        step(kt, sK0, sV0, MaskNo{});
-        sync();
-        dma_tile(kt + 2, sK0, sV0, LastNo{});
-        step(kt + 1, sK1, sV1, MaskNo{});
+        dma_k(t + 2, PAR ? sK1 : sK0, KWC);
+        dma_v(t + 1, PAR ? sV0 : sV1, VWC);
+        // ---- region X
+        if (NEXT) scores(kb, PARN{});
+        exponentiate(PARC);
+#pragma unroll
+        for (int i = 0; i < PDV; ++i) vread(vb, i);
+        {
+            // 7 vector instructions per matrix instruction: 32 x (fma, exp, add) + 16 conversions
+            if (NEXT) __builtin_amdgcn_sched_group_barrier(0x100, PDK, 0);
+#pragma unroll
+            for (int i = 0; i < NS; ++i) {
+                if (NEXT) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (NEXT && i + PDK < NS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                if ((i * ND) / NS != ((i + 1) * ND) / NS) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 112 / NS, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * PDV, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (MASKN) mask(t + 1, PARN{});
+        // ---- region Y
+#pragma unroll
+        for (int i = PDV; i < NPV; ++i) vread(vb, i);
+        output_mfma();
+        if (NEXT) block_max(PARN{});
+#pragma unroll
+        for (int i = 0; i < NPV; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i + PDV < NPV) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            if (NEXT) __builtin_amdgcn_sched_group_barrier(0x002, (16 + NPV - 1) / NPV, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (NEXT) decide();
+    };
+
+    // ---- prologue: K(0), V(0), K(1); scores, maximum and exponents of block 0
+    dma_k(0, sK0, std::integral_constant<int, (TAIL == 1 ? 2 : 1)>{});
+    dma_v(0, sV0, std::integral_constant<int, (TAIL == 1 ? 2 : 1)>{});
+    dma_k(1, sK1, std::integral_constant<int, (TAIL == 1 ? 0 : (TAIL == 2 ? 2 : 1))>{});
+    sync();
+    scores(reinterpret_cast<const char*>(sK0), I0{});
+    if (TAIL == 1) mask(0, I0{});
+    block_max(I0{});
+    decide();
+
+    // ---- main loop: complete iterations (blocks t + 1 and t + 2 exist and are
+    // not the last one), two per trip so that buffers and score registers are
+    // named statically; the last one to four iterations follow unrolled.
+    int t = 0;
+    for (; t + 5 <= nt; t += 2) {
+        iteration(t, I0{}, I1{}, I0{}, I1{}, I1{});
+        iteration(t + 1, I1{}, I1{}, I0{}, I1{}, I1{});
     }
     if (TAIL == 1) {
-        sync();
-        step(kt, sK0, sV0, MaskYes{});
+        iteration(t, I0{}, I0{}, I0{}, I0{}, I0{});
     } else if (TAIL == 2) {
-        sync();
-        dma_tile(kt + 1, sK1, sV1, LastYes{});
-        step(kt, sK0, sV0, MaskNo{});
-        sync();
-        step(kt + 1, sK1, sV1, MaskYes{});
+        iteration(t, I0{}, I1{}, I1{}, I0{}, I2{});
+        iteration(t + 1, I1{}, I0{}, I0{}, I0{}, I0{});
+    } else if (TAIL == 3) {
+        iteration(t, I0{}, I1{}, I0{}, I2{}, I1{});
+        iteration(t + 1, I1{}, I1{}, I1{}, I0{}, I2{});
+        iteration(t + 2, I0{}, I0{}, I0{}, I0{}, I0{});
     } else {
-        sync();
-        dma_tile(kt + 1, sK1, sV1, LastNo{});
-        step(kt, sK0, sV0, MaskNo{});
-        sync();
-        dma_tile(kt + 2, sK0, sV0, LastYes{});
-        step(kt + 1, sK1, sV1, MaskNo{});
-        sync();
-        step(kt + 2, sK0, sV0, MaskYes{});
+        iteration(t, I0{}, I1{}, I0{}, I1{}, I1{});
+        iteration(t + 1, I1{}, I1{}, I0{}, I2{}, I1{});
+        iteration(t + 2, I0{}, I1{}, I1{}, I0{}, I2{});
+        iteration(t + 3, I1{}, I0{}, I0{}, I0{}, I0{});
     }
 
     // ---- divide by the row sums and store: register v of subtile ds is value

@@ -101,6 +101,7 @@ def test_attention_argument_errors(lib):
         assert attn(lib, d=bad) == -2
         assert attn(lib, dv=bad) == -2
     assert attn(lib, M=(1 << 24) + 1) == -2
+    assert attn(lib, N=1 << 24) == -2
     assert attn(lib, B=1 << 30, M=1024) == -2               # more workgroups than a launch takes
     for k in ("Q", "K", "V", "O"):
         assert attn(lib, **{k: None}) == -1
