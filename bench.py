@@ -35,6 +35,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
 MEASURED_TRAFFIC_BYTES = {
     ("c2", "ffn_stream"): 281.2e6 + 16.2e6,
     ("c3", "gemm_gateup"): 621.5e6 + 45.2e6,
+    ("attention", "attention"): 103.0e6 + 35.7e6,
 }
 
 
@@ -222,7 +223,8 @@ def run_attention(steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
         "workload": "attention B=%(B)d M=%(M)d N=%(N)d d=%(d)d dv=%(dv)d" % w, "op": "attention",
         "ms_per_step": ms, "tflops": flops / (ms * 1e-3) / 1e12, "kernels_ms": {"attention": k_ms},
         "roofline": {"kernel": "attention", "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(("attention", "attention")),
                      "algorithmic": flops},
     }
     if with_cpu:

@@ -45,6 +45,10 @@ def load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise FileNotFoundError(
             f"{LIB_PATH} not found: build it with `python -m paper_2505_07829_amd.build`")
+    # torch first: libbb.so must bind to the HIP runtime torch has loaded (same soname), so that
+    # both work in one device context; loaded the other way round the process ends up with two
+    # runtimes and this library's sees no device.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, i64, f32, sz, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t, ctypes.c_int
     lib.bb_rmsnorm_swiglu_ffn.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]

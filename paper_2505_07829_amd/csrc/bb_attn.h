@@ -26,7 +26,10 @@
 // out of LDS with the transposing read, like the weight tiles of the GEMM.
 //   Q fragments stay in registers for the whole kernel (loaded from global
 // memory in operand layout).  K and V blocks go global -> LDS with load-to-LDS
-// instructions, double buffered, one barrier per key block.
+// instructions, double buffered, one barrier per key block.  The loop is a
+// software pipeline: the matrix instructions of block t + 1's scores run
+// between the vector instructions that exponentiate block t's scores, and
+// those of block t's output product between the maximum of block t + 1.
 #pragma once
 #include <type_traits>
 
