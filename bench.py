@@ -245,6 +245,29 @@ def run_attention(steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
     return res
 
 
+def run_selection(torch, bb, bb_inputs):
+    """Measured selection between the candidate programs (bb_*_tune) over the row counts between
+    decode and prefill for the Llama-shaped FFN, and for the c5 LN->matmul shape."""
+    names = {bb.VARIANT_STREAM: "stream", bb.VARIANT_SNAPSHOT1: "snapshot1", bb.VARIANT_UNFUSED: "unfused"}
+    out = []
+    full = [t.cuda() for t in bb_inputs.make_ffn(2048, 4096, 11008, seed=0)]
+    for M in (8, 16, 32, 64, 128, 256, 512, 1024, 2048):
+        X = full[0][:M].contiguous()
+        chosen, ms = bb.bb_rmsnorm_swiglu_ffn_tune(X, *full[1:], 1e-5, reps=10)
+        out.append({"op": "ffn", "M": M, "D": 4096, "F": 11008, "chosen": names[chosen],
+                    "ms": {names[v]: t for v, t in ms.items()}})
+    del full
+    c5 = bb_inputs.CONFIGS["c5"]
+    ln = [t.cuda() for t in bb_inputs.make_config("c5")]
+    chosen, ms = bb.bb_layernorm_matmul_tune(*ln, c5.eps, reps=10)
+    out.append({"op": "ln", "M": c5.M, "D": c5.D, "N": c5.F, "chosen": names[chosen],
+                "ms": {names[v]: t for v, t in ms.items()}})
+    del ln
+    bb.bb_tune_clear()
+    torch.cuda.empty_cache()
+    return out
+
+
 def _oracle(orc, cfg, cpu, rows):
     if cfg.op == "ffn":
         return orc.rmsnorm_swiglu_ffn(*cpu, cfg.eps, rows=rows)
@@ -289,6 +312,7 @@ def main():
     ap.add_argument("--also", default="c2", help="comma list of further workloads reported in 'others' "
                     "(the decode shape c2 is reported as 'decode')")
     ap.add_argument("--no-attention", action="store_true", help="skip the attention workload")
+    ap.add_argument("--no-selection", action="store_true", help="skip the measured-selection table")
     ap.add_argument("--attention-only", action="store_true",
                     help="time only the attention workload and print its block as the line (for profiler runs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing / parity sample")
@@ -326,6 +350,7 @@ def main():
         others[name] = run_workload(name, args.steps, args.warmup, not args.no_cpu, torch, bb, bb_inputs, orc, np)
     attn = None if args.no_attention else run_attention(args.steps, args.warmup, not args.no_cpu, torch, bb,
                                                         bb_inputs, orc, np)
+    selection = None if args.no_selection else run_selection(torch, bb, bb_inputs)
     peaks = calibrate(torch, bb)
     bb.bb_shutdown()
 
@@ -358,6 +383,8 @@ def main():
         }
     if attn is not None:
         line["attention"] = attn
+    if selection is not None:
+        line["selection"] = selection
     if others:
         line["others"] = others
     print(json.dumps(line))

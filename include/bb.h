@@ -69,12 +69,17 @@ typedef enum bb_status {
  *                      K-map) through per-workgroup partial-sum slots that a
  *                      short phase adds up.  The hidden block (16 x F) passes
  *                      through a cache-resident scratch between the phases.
- * BB_VARIANT_AUTO      STREAM for M <= 16, SNAPSHOT1 otherwise.
+ * BB_VARIANT_UNFUSED   the initial block program (what the *_unfused entry points
+ *                       run); a candidate of the measured selection below.
+ * BB_VARIANT_AUTO      the measured selection for exactly this shape if
+ *                       bb_*_tune has recorded one, else STREAM for M <= 16 and
+ *                       SNAPSHOT1 otherwise.
  */
 typedef enum bb_variant {
     BB_VARIANT_AUTO = 0,
     BB_VARIANT_STREAM = 1,
-    BB_VARIANT_SNAPSHOT1 = 2
+    BB_VARIANT_SNAPSHOT1 = 2,
+    BB_VARIANT_UNFUSED = 3
 } bb_variant;
 
 typedef enum bb_op {
@@ -205,18 +210,54 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O,
                  void* stream);
 
 /* ------------------------------------------------------------------------
+ * Measured selection (Section 4: the fusion algorithm returns several
+ * snapshots of a candidate, partially and fully fused, and a selection step
+ * keeps the one that runs fastest; Example 3's epilogue lists the forms).
+ *
+ * bb_*_tune run every candidate program of the operator on the caller's
+ * operands (same arguments as the operator): STREAM (FFN, M <= 16 only),
+ * SNAPSHOT1, UNFUSED; each once untimed and then `reps` (1..1000) times between
+ * two events on `stream`, which the call waits for.  The fastest is recorded
+ * for exactly this (operator, M, D, F or N) in a process-wide table that
+ * BB_VARIANT_AUTO consults, so later calls of bb_rmsnorm_swiglu_ffn /
+ * bb_layernorm_matmul with that shape run it.  Y holds the result of the last
+ * candidate run (all candidates compute the same operator).
+ *   chosen (host, may be NULL): the recorded variant.
+ *   ms (host, 4 floats, may be NULL): ms[v] = mean milliseconds of variant v,
+ *     -1 where v is not a candidate; ms[0] = the fastest.
+ * A candidate that does not fit a caller-provided workspace is skipped.
+ * bb_set_workspace and bb_tune_clear empty the table.  bb_tuned_variant returns
+ * the recorded variant of a shape, BB_VARIANT_AUTO (0) if none.
+ * The *_t entry points and bb_attention have one program each and no selection.
+ */
+int bb_rmsnorm_swiglu_ffn_tune(const void* X, const void* g, const void* W1,
+                               const void* W3, const void* W2, void* Y,
+                               int64_t M, int64_t D, int64_t F, float eps,
+                               void* stream, int reps, int* chosen, float* ms);
+int bb_layernorm_matmul_tune(const void* X, const void* gamma,
+                             const void* beta, const void* W, void* Y,
+                             int64_t M, int64_t D, int64_t N, float eps,
+                             void* stream, int reps, int* chosen, float* ms);
+int bb_tuned_variant(int op, int64_t M, int64_t D, int64_t F_or_N);
+int bb_tune_clear(void);
+
+/* ------------------------------------------------------------------------
  * Workspace and variant control.
  *
  * bb_workspace_bytes: bytes of device scratch `op` needs for the given sizes
- *   (third size is F for the FFN ops, N for the LN ops); the maximum over the
- *   variants that AUTO may choose.  Returns 0 for invalid sizes.
+ *   (third size is F for the FFN ops, N for the LN ops); the maximum over
+ *   STREAM and SNAPSHOT1.  The UNFUSED candidate needs
+ *   bb_workspace_bytes(BB_OP_*_UNFUSED, ...): a caller who provides the
+ *   workspace and wants it considered by bb_*_tune sizes for the larger of the
+ *   two.  Returns 0 for invalid sizes.
  * bb_set_workspace: hand the library a device buffer (256-byte aligned) to use
  *   instead of its own allocation; (NULL, 0) returns to the internal one.  The
  *   buffer must be ZERO-FILLED when it is handed over (the streaming variant
  *   keeps all-zero accumulators between calls) and stays owned by the caller.
  * bb_set_variant / bb_get_variant: process-wide choice for
  *   bb_rmsnorm_swiglu_ffn (default BB_VARIANT_AUTO, or the BB_VARIANT
- *   environment variable: "auto", "stream", "snapshot1").
+ *   environment variable: "auto", "stream", "snapshot1", "unfused");
+ *   BB_VARIANT_UNFUSED also applies to bb_layernorm_matmul.
  * bb_shutdown: frees the library's own workspace (synchronises the device).
  */
 size_t bb_workspace_bytes(int op, int64_t M, int64_t D, int64_t F_or_N);

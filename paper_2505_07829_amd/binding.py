@@ -15,13 +15,14 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libbb.so")
 
 BB_OK = 0
-VARIANT_AUTO, VARIANT_STREAM, VARIANT_SNAPSHOT1 = 0, 1, 2
+VARIANT_AUTO, VARIANT_STREAM, VARIANT_SNAPSHOT1, VARIANT_UNFUSED = 0, 1, 2, 3
 OP_FFN, OP_LN, OP_FFN_UNFUSED, OP_LN_UNFUSED = 0, 1, 2, 3
 
 EXPORTS = [
     "bb_rmsnorm_swiglu_ffn", "bb_layernorm_matmul",
     "bb_rmsnorm_swiglu_ffn_unfused", "bb_layernorm_matmul_unfused",
     "bb_rmsnorm_swiglu_ffn_t", "bb_layernorm_matmul_t", "bb_attention",
+    "bb_rmsnorm_swiglu_ffn_tune", "bb_layernorm_matmul_tune", "bb_tuned_variant", "bb_tune_clear",
     "bb_workspace_bytes", "bb_set_workspace", "bb_set_variant", "bb_get_variant",
     "bb_shutdown", "bb_status_string", "bb_version", "bb_last_hip_error",
     "bb_calib_copy", "bb_calib_read", "bb_calib_mfma", "bb_calib_mfma_data",
@@ -57,6 +58,10 @@ def load() -> ctypes.CDLL:
     lib.bb_layernorm_matmul_t.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
     lib.bb_layernorm_matmul.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
     lib.bb_layernorm_matmul_unfused.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
+    pi, pf = ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)
+    lib.bb_rmsnorm_swiglu_ffn_tune.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp, ci, pi, pf]
+    lib.bb_layernorm_matmul_tune.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, vp, ci, pi, pf]
+    lib.bb_tuned_variant.argtypes = [ci, i64, i64, i64]
     lib.bb_attention.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, vp]
     lib.bb_workspace_bytes.argtypes = [ci, i64, i64, i64]
     lib.bb_workspace_bytes.restype = sz
@@ -135,6 +140,52 @@ def bb_rmsnorm_swiglu_ffn_t(X, g, W1t, W3t, W2t, eps: float, Y=None):
     _check(lib.bb_rmsnorm_swiglu_ffn_t(_ptr(X), _ptr(g), _ptr(W1t), _ptr(W3t), _ptr(W2t), _ptr(Y), M, D, F,
                                        float(eps), _stream()), "bb_rmsnorm_swiglu_ffn_t")
     return Y
+
+
+def bb_rmsnorm_swiglu_ffn_tune(X, g, W1, W3, W2, eps: float, reps: int = 5, Y=None):
+    """Times the candidate programs of the FFN operator on these operands and records the fastest
+    for this shape.  Returns (variant, {variant: ms})."""
+    import torch
+    lib = load()
+    M, D = X.shape
+    F = W1.shape[1]
+    _require(X, (M, D), "X"); _require(g, (D,), "g")
+    _require(W1, (D, F), "W1"); _require(W3, (D, F), "W3"); _require(W2, (F, D), "W2")
+    if Y is None:
+        Y = torch.empty((M, D), dtype=torch.bfloat16, device=X.device)
+    _require(Y, (M, D), "Y")
+    chosen, ms = ctypes.c_int(0), (ctypes.c_float * 4)()
+    _check(lib.bb_rmsnorm_swiglu_ffn_tune(_ptr(X), _ptr(g), _ptr(W1), _ptr(W3), _ptr(W2), _ptr(Y), M, D, F,
+                                          float(eps), _stream(), int(reps), ctypes.byref(chosen), ms),
+           "bb_rmsnorm_swiglu_ffn_tune")
+    return chosen.value, {v: float(ms[v]) for v in (1, 2, 3) if ms[v] >= 0}
+
+
+def bb_layernorm_matmul_tune(X, gamma, beta, W, eps: float, reps: int = 5, Y=None):
+    """Times the candidate programs of LN->matmul on these operands and records the fastest for this
+    shape.  Returns (variant, {variant: ms})."""
+    import torch
+    lib = load()
+    M, D = X.shape
+    N = W.shape[1]
+    _require(X, (M, D), "X"); _require(gamma, (D,), "gamma"); _require(beta, (D,), "beta")
+    _require(W, (D, N), "W")
+    if Y is None:
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device)
+    _require(Y, (M, N), "Y")
+    chosen, ms = ctypes.c_int(0), (ctypes.c_float * 4)()
+    _check(lib.bb_layernorm_matmul_tune(_ptr(X), _ptr(gamma), _ptr(beta), _ptr(W), _ptr(Y), M, D, N, float(eps),
+                                        _stream(), int(reps), ctypes.byref(chosen), ms),
+           "bb_layernorm_matmul_tune")
+    return chosen.value, {v: float(ms[v]) for v in (1, 2, 3) if ms[v] >= 0}
+
+
+def bb_tuned_variant(op: int, M: int, D: int, F_or_N: int) -> int:
+    return int(load().bb_tuned_variant(op, M, D, F_or_N))
+
+
+def bb_tune_clear() -> None:
+    _check(load().bb_tune_clear(), "bb_tune_clear")
 
 
 def bb_attention(Q, K, V, O=None):

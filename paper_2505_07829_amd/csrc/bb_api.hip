@@ -6,7 +6,9 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <map>
 #include <mutex>
+#include <tuple>
 
 #include "../../include/bb.h"
 #include "bb_attn.h"
@@ -92,10 +94,39 @@ int read_variant() {
         if (const char* e = std::getenv("BB_VARIANT")) {
             if (!std::strcmp(e, "stream")) g_variant = BB_VARIANT_STREAM;
             else if (!std::strcmp(e, "snapshot1")) g_variant = BB_VARIANT_SNAPSHOT1;
+            else if (!std::strcmp(e, "unfused")) g_variant = BB_VARIANT_UNFUSED;
         }
     }
     return g_variant;
 }
+
+// measured selections (bb_*_tune): (op, M, D, F or N) -> variant
+struct TuneKey {
+    int op;
+    int64_t M, D, FN;
+    bool operator<(const TuneKey& o) const {
+        return std::tie(op, M, D, FN) < std::tie(o.op, o.M, o.D, o.FN);
+    }
+};
+std::map<TuneKey, int> g_tuned;
+
+// AUTO: a measured selection for exactly this shape if there is one, else the rule of thumb
+// (weight-streaming kernel up to kStreamMaxM rows, tiled kernels beyond; LN always fused)
+int auto_variant(int op, int64_t M, int64_t D, int64_t FN) {
+    auto it = g_tuned.find(TuneKey{op, M, D, FN});
+    if (it != g_tuned.end()) return it->second;
+    if (op == BB_OP_RMSNORM_SWIGLU_FFN) return (M <= kStreamMaxM) ? BB_VARIANT_STREAM : BB_VARIANT_SNAPSHOT1;
+    return BB_VARIANT_SNAPSHOT1;
+}
+
+int ffn_locked(int variant, const void* X, const void* g, const void* W1, const void* W3, const void* W2,
+               void* Y, int64_t M, int64_t D, int64_t F, float eps, void* stream);
+int ffn_unfused_locked(const void* X, const void* g, const void* W1, const void* W3, const void* W2, void* Y,
+                       int64_t M, int64_t D, int64_t F, float eps, void* stream);
+int ln_locked(int variant, const void* X, const void* gamma, const void* beta, const void* W, void* Y,
+              int64_t M, int64_t D, int64_t N, float eps, void* stream);
+int ln_unfused_locked(const void* X, const void* gamma, const void* beta, const void* W, void* Y, int64_t M,
+                      int64_t D, int64_t N, float eps, void* stream);
 
 void prof_begin(hipStream_t st) {
     if (!g_prof.on) return;
@@ -400,7 +431,7 @@ const char* bb_status_string(int s) {
 }
 
 int bb_set_variant(int v) {
-    if (v != BB_VARIANT_AUTO && v != BB_VARIANT_STREAM && v != BB_VARIANT_SNAPSHOT1) return BB_ERR_VARIANT;
+    if (v < BB_VARIANT_AUTO || v > BB_VARIANT_UNFUSED) return BB_ERR_VARIANT;
     std::lock_guard<std::mutex> lk(g_mu);
     g_variant = v;
     return BB_OK;
@@ -421,6 +452,7 @@ int bb_set_workspace(void* dptr, size_t bytes) {
     std::lock_guard<std::mutex> lk(g_mu);
     if ((dptr == nullptr) != (bytes == 0)) return BB_ERR_WORKSPACE;
     if ((uintptr_t)dptr & (kAlign - 1)) return BB_ERR_WORKSPACE;
+    g_tuned.clear();                   // selections were measured with the previous workspace arrangement
     if (g_ws.ptr && !g_ws.user) {
         BB_HIP(hipDeviceSynchronize());
         BB_HIP(hipFree(g_ws.ptr));
@@ -452,7 +484,18 @@ int bb_rmsnorm_swiglu_ffn(const void* X, const void* g, const void* W1, const vo
     std::lock_guard<std::mutex> lk(g_mu);
     int variant = read_variant();
     if (variant == BB_VARIANT_STREAM && M > kStreamMaxM) return BB_ERR_VARIANT;
-    if (variant == BB_VARIANT_AUTO) variant = (M <= kStreamMaxM) ? BB_VARIANT_STREAM : BB_VARIANT_SNAPSHOT1;
+    if (variant == BB_VARIANT_AUTO) variant = auto_variant(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F);
+    return ffn_locked(variant, X, g, W1, W3, W2, Y, M, D, F, eps, stream);
+}
+
+} // extern "C"
+
+namespace {
+
+// the operators with the library lock held and arguments validated
+int ffn_locked(int variant, const void* X, const void* g, const void* W1, const void* W3, const void* W2,
+               void* Y, int64_t M, int64_t D, int64_t F, float eps, void* stream) {
+    if (variant == BB_VARIANT_UNFUSED) return ffn_unfused_locked(X, g, W1, W3, W2, Y, M, D, F, eps, stream);
     const DeviceInfo* dev = nullptr;
     if (int rc = current_device_info(&dev)) return rc;
     const size_t zone = zone_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F);
@@ -475,11 +518,9 @@ int bb_rmsnorm_swiglu_ffn(const void* X, const void* g, const void* W1, const vo
                                    (int)M, (int)D, (int)F, 0.f, pcus, st, split);
 }
 
-int bb_layernorm_matmul(const void* X, const void* gamma, const void* beta, const void* W, void* Y,
-                        int64_t M, int64_t D, int64_t N, float eps, void* stream) {
-    if (int rc = validate_ln(X, gamma, beta, W, Y, M, D, N, eps)) return rc;
-    if (M == 0) return BB_OK;
-    std::lock_guard<std::mutex> lk(g_mu);
+int ln_locked(int variant, const void* X, const void* gamma, const void* beta, const void* W, void* Y,
+              int64_t M, int64_t D, int64_t N, float eps, void* stream) {
+    if (variant == BB_VARIANT_UNFUSED) return ln_unfused_locked(X, gamma, beta, W, Y, M, D, N, eps, stream);
     const DeviceInfo* dev = nullptr;
     if (int rc = current_device_info(&dev)) return rc;
     if (int rc = ensure_workspace(scratch_bytes(BB_OP_LAYERNORM_MATMUL, M, D, N))) return rc;
@@ -498,6 +539,20 @@ int bb_layernorm_matmul(const void* X, const void* gamma, const void* beta, cons
     prof_mark("colvec", st);
     return launch_gemm<MODE_LN>((const u16*)X, (int)D, (const u16*)W, nullptr, (int)N, (u16*)Y, (int)N,
                                 (const u16*)gamma, colc, colb, (int)M, (int)N, (int)D, eps, dev->cus, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int bb_layernorm_matmul(const void* X, const void* gamma, const void* beta, const void* W, void* Y,
+                        int64_t M, int64_t D, int64_t N, float eps, void* stream) {
+    if (int rc = validate_ln(X, gamma, beta, W, Y, M, D, N, eps)) return rc;
+    if (M == 0) return BB_OK;
+    std::lock_guard<std::mutex> lk(g_mu);
+    int variant = read_variant();
+    if (variant != BB_VARIANT_UNFUSED) variant = auto_variant(BB_OP_LAYERNORM_MATMUL, M, D, N);
+    return ln_locked(variant, X, gamma, beta, W, Y, M, D, N, eps, stream);
 }
 
 int bb_rmsnorm_swiglu_ffn_t(const void* X, const void* g, const void* W1t, const void* W3t, const void* W2t,
@@ -601,6 +656,23 @@ int bb_rmsnorm_swiglu_ffn_unfused(const void* X, const void* g, const void* W1, 
     if (int rc = validate_ffn(X, g, W1, W3, W2, Y, M, D, F, eps)) return rc;
     if (M == 0) return BB_OK;
     std::lock_guard<std::mutex> lk(g_mu);
+    return ffn_unfused_locked(X, g, W1, W3, W2, Y, M, D, F, eps, stream);
+}
+
+int bb_layernorm_matmul_unfused(const void* X, const void* gamma, const void* beta, const void* W, void* Y,
+                                int64_t M, int64_t D, int64_t N, float eps, void* stream) {
+    if (int rc = validate_ln(X, gamma, beta, W, Y, M, D, N, eps)) return rc;
+    if (M == 0) return BB_OK;
+    std::lock_guard<std::mutex> lk(g_mu);
+    return ln_unfused_locked(X, gamma, beta, W, Y, M, D, N, eps, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+int ffn_unfused_locked(const void* X, const void* g, const void* W1, const void* W3, const void* W2, void* Y,
+                       int64_t M, int64_t D, int64_t F, float eps, void* stream) {
     const DeviceInfo* dev = nullptr;
     if (int rc = current_device_info(&dev)) return rc;
     if (int rc = ensure_workspace(scratch_bytes(BB_OP_RMSNORM_SWIGLU_FFN_UNFUSED, M, D, F))) return rc;
@@ -634,11 +706,8 @@ int bb_rmsnorm_swiglu_ffn_unfused(const void* X, const void* g, const void* W1, 
                                    nullptr, nullptr, (int)M, (int)D, (int)F, 0.f, pcus, st, split);
 }
 
-int bb_layernorm_matmul_unfused(const void* X, const void* gamma, const void* beta, const void* W, void* Y,
-                                int64_t M, int64_t D, int64_t N, float eps, void* stream) {
-    if (int rc = validate_ln(X, gamma, beta, W, Y, M, D, N, eps)) return rc;
-    if (M == 0) return BB_OK;
-    std::lock_guard<std::mutex> lk(g_mu);
+int ln_unfused_locked(const void* X, const void* gamma, const void* beta, const void* W, void* Y, int64_t M,
+                      int64_t D, int64_t N, float eps, void* stream) {
     const DeviceInfo* dev = nullptr;
     if (int rc = current_device_info(&dev)) return rc;
     if (int rc = ensure_workspace(scratch_bytes(BB_OP_LAYERNORM_MATMUL_UNFUSED, M, D, N))) return rc;
@@ -652,6 +721,100 @@ int bb_layernorm_matmul_unfused(const void* X, const void* gamma, const void* be
     prof_mark("layernorm_rows", st);
     return launch_gemm<MODE_PLAIN>(Z, (int)D, (const u16*)W, nullptr, (int)N, (u16*)Y, (int)N, nullptr, nullptr,
                                    nullptr, (int)M, (int)N, (int)D, 0.f, dev->cus, st);
+}
+
+// Times fn() `reps` times on the stream after one untimed call; mean milliseconds, or < 0 on error.
+template <class Fn>
+int time_candidate(Fn fn, int reps, hipStream_t st, float* ms) {
+    hipEvent_t e0, e1;
+    BB_HIP(hipEventCreate(&e0));
+    BB_HIP(hipEventCreate(&e1));
+    int rc = fn();
+    if (rc == BB_OK) {
+        (void)hipEventRecord(e0, st);
+        for (int i = 0; i < reps && rc == BB_OK; ++i) rc = fn();
+        (void)hipEventRecord(e1, st);
+        const hipError_t e = hipEventSynchronize(e1);
+        if (rc == BB_OK && e != hipSuccess) rc = hip_fail(e);
+        if (rc == BB_OK) {
+            (void)hipEventElapsedTime(ms, e0, e1);
+            *ms /= (float)reps;
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return rc;
+}
+
+// Measured selection: runs every candidate program of the operator on the caller's operands, records
+// the fastest for this (op, M, D, F or N) in the table AUTO consults, reports the times.
+template <class Run>
+int tune_locked(int op, int64_t M, int64_t D, int64_t FN, int reps, hipStream_t st, int* chosen, float* ms_out,
+                Run run) {
+    if (reps < 1 || reps > 1000) return BB_ERR_SHAPE;
+    const bool prof = g_prof.on;
+    g_prof.on = false;
+    int best = 0;
+    float best_ms = 0.f;
+    int rc = BB_OK;
+    for (int v = BB_VARIANT_STREAM; v <= BB_VARIANT_UNFUSED && rc == BB_OK; ++v) {
+        if (ms_out) ms_out[v] = -1.f;
+        if (op == BB_OP_LAYERNORM_MATMUL && v == BB_VARIANT_STREAM) continue;
+        if (v == BB_VARIANT_STREAM && M > kStreamMaxM) continue;
+        float ms = 0.f;
+        rc = time_candidate([&]() { return run(v); }, reps, st, &ms);
+        if (rc == BB_ERR_WORKSPACE && g_ws.user) {      // does not fit the caller's workspace: not a candidate
+            rc = BB_OK;
+            continue;
+        }
+        if (rc != BB_OK) break;
+        if (ms_out) ms_out[v] = ms;
+        if (!best || ms < best_ms) best = v, best_ms = ms;
+    }
+    g_prof.on = prof;
+    if (rc != BB_OK) return rc;
+    g_tuned[TuneKey{op, M, D, FN}] = best;
+    if (ms_out) ms_out[0] = best_ms;
+    if (chosen) *chosen = best;
+    if (log_on()) std::fprintf(stderr, "[bb] tuned op %d M %lld D %lld F/N %lld -> variant %d (%.4f ms)\n", op,
+                               (long long)M, (long long)D, (long long)FN, best, best_ms);
+    return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+int bb_rmsnorm_swiglu_ffn_tune(const void* X, const void* g, const void* W1, const void* W3, const void* W2,
+                               void* Y, int64_t M, int64_t D, int64_t F, float eps, void* stream, int reps,
+                               int* chosen, float* ms) {
+    if (int rc = validate_ffn(X, g, W1, W3, W2, Y, M, D, F, eps)) return rc;
+    if (M == 0) return BB_ERR_SHAPE;
+    std::lock_guard<std::mutex> lk(g_mu);
+    return tune_locked(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F, reps, as_stream(stream), chosen, ms,
+                       [&](int v) { return ffn_locked(v, X, g, W1, W3, W2, Y, M, D, F, eps, stream); });
+}
+
+int bb_layernorm_matmul_tune(const void* X, const void* gamma, const void* beta, const void* W, void* Y,
+                             int64_t M, int64_t D, int64_t N, float eps, void* stream, int reps, int* chosen,
+                             float* ms) {
+    if (int rc = validate_ln(X, gamma, beta, W, Y, M, D, N, eps)) return rc;
+    if (M == 0) return BB_ERR_SHAPE;
+    std::lock_guard<std::mutex> lk(g_mu);
+    return tune_locked(BB_OP_LAYERNORM_MATMUL, M, D, N, reps, as_stream(stream), chosen, ms,
+                       [&](int v) { return ln_locked(v, X, gamma, beta, W, Y, M, D, N, eps, stream); });
+}
+
+int bb_tuned_variant(int op, int64_t M, int64_t D, int64_t F_or_N) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    auto it = g_tuned.find(TuneKey{op, M, D, F_or_N});
+    return it == g_tuned.end() ? BB_VARIANT_AUTO : it->second;
+}
+
+int bb_tune_clear(void) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_tuned.clear();
+    return BB_OK;
 }
 
 // ---------------------------------------------------------------- profiling

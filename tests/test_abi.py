@@ -111,11 +111,34 @@ def test_attention_argument_errors(lib):
     assert attn(lib, O=3 * A - 64) == -5                    # tail of O runs into V
 
 
+def test_tune_argument_errors(lib):
+    import ctypes as C
+    f = lib.bb_rmsnorm_swiglu_ffn_tune
+    args = [A, 2 * A, 3 * A, 4 * A, 5 * A, 6 * A, 4, 64, 128, 1e-6, None]
+    assert f(*args, 0, None, None) == -2                    # reps out of range
+    assert f(*args, 1001, None, None) == -2
+    bad = list(args); bad[6] = 0
+    assert f(*bad, 3, None, None) == -2                     # nothing to measure on an empty input
+    bad = list(args); bad[0] = None
+    assert f(*bad, 3, None, None) == -1
+    bad = list(args); bad[5] = A
+    assert f(*bad, 3, None, None) == -5
+    h = lib.bb_layernorm_matmul_tune
+    largs = [A, 2 * A, 3 * A, 4 * A, 6 * A, 4, 64, 128, 1e-6, None]
+    assert h(*largs, 0, None, None) == -2
+    bad = list(largs); bad[7] = 12
+    assert h(*bad, 3, None, None) == -2
+    assert lib.bb_tuned_variant(0, 4, 64, 128) == 0         # nothing recorded
+    assert lib.bb_tune_clear() == 0
+
+
 def test_variant_and_workspace_queries(lib):
     assert bb.bb_get_variant() in (0, 1, 2)
     old = bb.bb_get_variant()
     with pytest.raises(bb.BBError):
         bb.bb_set_variant(7)
+    bb.bb_set_variant(bb.VARIANT_UNFUSED)
+    assert bb.bb_get_variant() == bb.VARIANT_UNFUSED
     bb.bb_set_variant(bb.VARIANT_SNAPSHOT1)
     assert bb.bb_get_variant() == bb.VARIANT_SNAPSHOT1
     bb.bb_set_variant(old)

@@ -270,3 +270,57 @@ def test_c5_ln_sampled_rows():
     err = row_rel_err(Y[rows], ref)
     print("c5 rel err", err, "rows", len(rows))
     assert err <= TOL
+
+
+# ---------------------------------------------------------------- measured selection
+def test_tune_records_fastest_candidate_and_auto_follows():
+    bb.bb_tune_clear()
+    cpu = bb_inputs.make_ffn(96, 512, 1408, seed=4)
+    d = dev(cpu)
+    M, D, F = 96, 512, 1408
+    assert bb.bb_tuned_variant(bb.OP_FFN, M, D, F) == bb.VARIANT_AUTO
+    chosen, ms = bb.bb_rmsnorm_swiglu_ffn_tune(*d, 1e-6, reps=3)
+    assert set(ms) == {bb.VARIANT_SNAPSHOT1, bb.VARIANT_UNFUSED}          # STREAM is no candidate above 16 rows
+    assert chosen == min(ms, key=ms.get) and all(v > 0 for v in ms.values())
+    assert bb.bb_tuned_variant(bb.OP_FFN, M, D, F) == chosen
+    assert bb.bb_tuned_variant(bb.OP_FFN, M + 1, D, F) == bb.VARIANT_AUTO  # exact shapes only
+    # AUTO now runs the recorded program: its kernel list is that program's
+    bb.bb_profile_enable(True)
+    Y = bb.bb_rmsnorm_swiglu_ffn(*d, 1e-6)
+    names = [k for k, _ in bb.bb_profile_last()]
+    bb.bb_profile_enable(False)
+    assert ("rmsnorm_rows" in names) == (chosen == bb.VARIANT_UNFUSED)
+    ref = orc.rmsnorm_swiglu_ffn(*cpu, 1e-6)
+    assert row_rel_err(Y, ref) <= TOL
+    bb.bb_tune_clear()
+    assert bb.bb_tuned_variant(bb.OP_FFN, M, D, F) == bb.VARIANT_AUTO
+
+
+def test_tune_decode_shape_has_three_candidates():
+    bb.bb_tune_clear()
+    cpu = bb_inputs.make_ffn(8, 512, 1408, seed=5)
+    chosen, ms = bb.bb_rmsnorm_swiglu_ffn_tune(*dev(cpu), 1e-6, reps=3)
+    assert set(ms) == {bb.VARIANT_STREAM, bb.VARIANT_SNAPSHOT1, bb.VARIANT_UNFUSED}
+    Y = bb.bb_rmsnorm_swiglu_ffn(*dev(cpu), 1e-6)
+    assert row_rel_err(Y, orc.rmsnorm_swiglu_ffn(*cpu, 1e-6)) <= TOL
+    bb.bb_tune_clear()
+
+
+def test_tune_layernorm_and_forced_unfused_variant():
+    bb.bb_tune_clear()
+    cpu = bb_inputs.make_ln(200, 512, 768, seed=6)
+    ref = orc.layernorm_matmul(*cpu, 1e-5)
+    chosen, ms = bb.bb_layernorm_matmul_tune(*dev(cpu), 1e-5, reps=3)
+    assert set(ms) == {bb.VARIANT_SNAPSHOT1, bb.VARIANT_UNFUSED} and chosen in ms
+    assert row_rel_err(bb.bb_layernorm_matmul(*dev(cpu), 1e-5), ref) <= TOL
+    bb.bb_tune_clear()
+    # the unfused program through the main entry points when forced
+    bb.bb_set_variant(bb.VARIANT_UNFUSED)
+    try:
+        bb.bb_profile_enable(True)
+        Y = bb.bb_layernorm_matmul(*dev(cpu), 1e-5)
+        names = [k for k, _ in bb.bb_profile_last()]
+        bb.bb_profile_enable(False)
+        assert "layernorm_rows" in names and row_rel_err(Y, ref) <= TOL
+    finally:
+        bb.bb_set_variant(bb.VARIANT_AUTO)
