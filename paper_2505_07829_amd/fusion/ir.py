@@ -263,27 +263,3 @@ def all_graphs(g: Graph) -> List[Graph]:
 
 def clone(g: Graph) -> Graph:
     return copy.deepcopy(g)
-
-
-def buffered_edges(g: Graph, include_io: bool = False) -> int:
-    """number of values that live in global memory (lists) and are produced by an operator,
-    i.e. intermediate results the program materialises; with include_io also the program's
-    inputs and outputs"""
-    count = 0
-    top_outs = {id(n.arg[0]): n.arg[1] for n in g.nodes if isinstance(n, Out)}
-    for gr in all_graphs(g):
-        for n in gr.nodes:
-            if isinstance(n, In) and gr is g and include_io:
-                count += 1
-            if isinstance(n, Map):
-                for k, o in enumerate(n.outs):
-                    if o.reduced:
-                        continue
-                    is_io = gr is g and top_outs.get(id(n)) == k
-                    # a list that is only passed on as the enclosing map's own output is the same buffer
-                    if gr.exported((n, k)) and not gr.consumers((n, k)):
-                        continue
-                    if is_io and not include_io:
-                        continue
-                    count += 1
-    return count
