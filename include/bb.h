@@ -162,6 +162,32 @@ int bb_layernorm_matmul_t(const void* X, const void* gamma, const void* beta,
                           int64_t N, float eps, void* stream);
 
 /* ------------------------------------------------------------------------
+ * The FFN operator with the residual connection of a decoder block fused into
+ * the last kernel's epilogue (the operator that follows Example 3's program in
+ * a Transformer block; Section 2 names fusing past operator boundaries as the
+ * point of block-level fusion):
+ *
+ *   Y = R + ( SiLU(Xh W1) * (Xh W3) ) W2          R [M, D] bf16, row-major
+ *
+ * The sum is formed in fp32 before the output's one rounding to bf16.  R may be
+ * X (the usual pre-norm block y = x + FFN(norm(x))).  Y may be R itself (in
+ * place), and then also X; otherwise Y must overlap no input.  Variants: as
+ * bb_rmsnorm_swiglu_ffn, except that a recorded or forced UNFUSED selection
+ * runs SNAPSHOT1 (the unfused program has no such epilogue).  _t: transposed
+ * weights as for bb_rmsnorm_swiglu_ffn_t.  Workspace and errors as for the
+ * operator without the residual.
+ */
+int bb_rmsnorm_swiglu_ffn_residual(const void* X, const void* g, const void* W1,
+                                   const void* W3, const void* W2, const void* R,
+                                   void* Y, int64_t M, int64_t D, int64_t F,
+                                   float eps, void* stream);
+int bb_rmsnorm_swiglu_ffn_residual_t(const void* X, const void* g,
+                                     const void* W1t, const void* W3t,
+                                     const void* W2t, const void* R, void* Y,
+                                     int64_t M, int64_t D, int64_t F, float eps,
+                                     void* stream);
+
+/* ------------------------------------------------------------------------
  * The UNFUSED block programs (Example 3 / Example 2, initial block programs):
  * one kernel per array operator, every intermediate materialised in global
  * memory.  Built from the same tile primitives; exported so that the cost of

@@ -119,6 +119,16 @@ def rmsnorm_swiglu_ffn(X, g, W1, W3, W2, eps: float,
     return Y
 
 
+def rmsnorm_swiglu_ffn_residual(X, g, W1, W3, W2, R, eps: float,
+                                rows: Optional[Sequence[int]] = None) -> np.ndarray:
+    """The operator above followed by the residual connection of a decoder
+    block: R + FFN(X), R [M,D] (bf16 values, added in float64)."""
+    Y = rmsnorm_swiglu_ffn(X, g, W1, W3, W2, eps, rows)
+    M, D = (int(s) for s in X.shape)
+    Rf = R.reshape(M, D).to(dtype=__import__("torch").float64).numpy()
+    return Y + (Rf if rows is None else Rf[np.asarray(list(rows), dtype=np.int64)])
+
+
 def layernorm_matmul(X, gamma, beta, W, eps: float,
                      rows: Optional[Sequence[int]] = None) -> np.ndarray:
     """Definition of Example 2's array program with gamma/beta/eps.

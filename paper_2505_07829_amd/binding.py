@@ -22,6 +22,7 @@ EXPORTS = [
     "bb_rmsnorm_swiglu_ffn", "bb_layernorm_matmul",
     "bb_rmsnorm_swiglu_ffn_unfused", "bb_layernorm_matmul_unfused",
     "bb_rmsnorm_swiglu_ffn_t", "bb_layernorm_matmul_t", "bb_attention",
+    "bb_rmsnorm_swiglu_ffn_residual", "bb_rmsnorm_swiglu_ffn_residual_t",
     "bb_rmsnorm_swiglu_ffn_tune", "bb_layernorm_matmul_tune", "bb_tuned_variant", "bb_tune_clear",
     "bb_workspace_bytes", "bb_set_workspace", "bb_set_variant", "bb_get_variant",
     "bb_shutdown", "bb_status_string", "bb_version", "bb_last_hip_error",
@@ -62,6 +63,8 @@ def load() -> ctypes.CDLL:
     lib.bb_rmsnorm_swiglu_ffn_tune.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp, ci, pi, pf]
     lib.bb_layernorm_matmul_tune.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, vp, ci, pi, pf]
     lib.bb_tuned_variant.argtypes = [ci, i64, i64, i64]
+    lib.bb_rmsnorm_swiglu_ffn_residual.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
+    lib.bb_rmsnorm_swiglu_ffn_residual_t.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
     lib.bb_attention.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, vp]
     lib.bb_workspace_bytes.argtypes = [ci, i64, i64, i64]
     lib.bb_workspace_bytes.restype = sz
@@ -139,6 +142,25 @@ def bb_rmsnorm_swiglu_ffn_t(X, g, W1t, W3t, W2t, eps: float, Y=None):
     _require(Y, (M, D), "Y")
     _check(lib.bb_rmsnorm_swiglu_ffn_t(_ptr(X), _ptr(g), _ptr(W1t), _ptr(W3t), _ptr(W2t), _ptr(Y), M, D, F,
                                        float(eps), _stream()), "bb_rmsnorm_swiglu_ffn_t")
+    return Y
+
+
+def bb_rmsnorm_swiglu_ffn_residual(X, g, W1, W3, W2, R, eps: float, Y=None, transposed: bool = False):
+    """Y = R + FFN(RMSNorm(X)); weights [D,F],[D,F],[F,D], or transposed [F,D],[F,D],[D,F].
+    Y may be R (in place).  Returns Y."""
+    import torch
+    lib = load()
+    M, D = X.shape
+    F = W1.shape[0] if transposed else W1.shape[1]
+    _require(X, (M, D), "X"); _require(g, (D,), "g"); _require(R, (M, D), "R")
+    wshape, w2shape = ((F, D), (D, F)) if transposed else ((D, F), (F, D))
+    _require(W1, wshape, "W1"); _require(W3, wshape, "W3"); _require(W2, w2shape, "W2")
+    if Y is None:
+        Y = torch.empty((M, D), dtype=torch.bfloat16, device=X.device)
+    _require(Y, (M, D), "Y")
+    fn = lib.bb_rmsnorm_swiglu_ffn_residual_t if transposed else lib.bb_rmsnorm_swiglu_ffn_residual
+    _check(fn(_ptr(X), _ptr(g), _ptr(W1), _ptr(W3), _ptr(W2), _ptr(R), _ptr(Y), M, D, F, float(eps), _stream()),
+           "bb_rmsnorm_swiglu_ffn_residual")
     return Y
 
 

@@ -120,11 +120,13 @@ int auto_variant(int op, int64_t M, int64_t D, int64_t FN) {
 }
 
 int ffn_locked(int variant, const void* X, const void* g, const void* W1, const void* W3, const void* W2,
-               void* Y, int64_t M, int64_t D, int64_t F, float eps, void* stream);
+               void* Y, int64_t M, int64_t D, int64_t F, float eps, void* stream, const void* R = nullptr);
 int ffn_unfused_locked(const void* X, const void* g, const void* W1, const void* W3, const void* W2, void* Y,
                        int64_t M, int64_t D, int64_t F, float eps, void* stream);
 int ln_locked(int variant, const void* X, const void* gamma, const void* beta, const void* W, void* Y,
               int64_t M, int64_t D, int64_t N, float eps, void* stream);
+int ffn_t_locked(const void* X, const void* g, const void* W1t, const void* W3t, const void* W2t, void* Y,
+                 int64_t M, int64_t D, int64_t F, float eps, void* stream, const void* R);
 int ln_unfused_locked(const void* X, const void* gamma, const void* beta, const void* W, void* Y, int64_t M,
                       int64_t D, int64_t N, float eps, void* stream);
 
@@ -167,6 +169,27 @@ int validate_ffn(const void* X, const void* g, const void* W1, const void* W3, c
     const size_t ny = (size_t)M * D * 2, nw = (size_t)D * F * 2;
     if (overlaps(Y, ny, X, ny) || overlaps(Y, ny, g, (size_t)D * 2) || overlaps(Y, ny, W1, nw) ||
         overlaps(Y, ny, W3, nw) || overlaps(Y, ny, W2, nw))
+        return BB_ERR_ALIAS;
+    return BB_OK;
+}
+
+// Y = R + FFN(X): R [M, D].  R may be X.  Y may be R itself (in place; then it may also be X, which
+// every kernel has finished reading before the last one writes), otherwise Y overlaps nothing.
+int validate_ffn_residual(const void* X, const void* g, const void* W1, const void* W3, const void* W2,
+                          const void* R, void* Y, int64_t M, int64_t D, int64_t F, float eps) {
+    if (int rc = check_dims(M, D, F)) return rc;
+    if (int rc = check_eps(eps)) return rc;
+    if (M == 0) return BB_OK;
+    if (!X || !g || !W1 || !W3 || !W2 || !R || !Y) return BB_ERR_NULL;
+    if (misaligned(X) || misaligned(g) || misaligned(W1) || misaligned(W3) || misaligned(W2) || misaligned(R) ||
+        misaligned(Y))
+        return BB_ERR_ALIGN;
+    const size_t ny = (size_t)M * D * 2, nw = (size_t)D * F * 2;
+    const bool in_place = (Y == R);
+    if (!in_place && overlaps(Y, ny, R, ny)) return BB_ERR_ALIAS;
+    if (!(in_place && R == X) && overlaps(Y, ny, X, ny)) return BB_ERR_ALIAS;
+    if (overlaps(Y, ny, g, (size_t)D * 2) || overlaps(Y, ny, W1, nw) || overlaps(Y, ny, W3, nw) ||
+        overlaps(Y, ny, W2, nw))
         return BB_ERR_ALIAS;
     return BB_OK;
 }
@@ -307,8 +330,9 @@ void mark_dirty(size_t off) {
 template <int MODE, bool BT = false>
 int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u16* C, int ldc,
                 const u16* gain, const float* colc, const float* colb, int M, int N, int K, float eps,
-                int cus, hipStream_t st, void* split = nullptr) {
+                int cus, hipStream_t st, void* split = nullptr, const u16* res = nullptr, int ldr = 0) {
     GemmArgs a;
+    a.res = res; a.ldr = ldr;
     a.nsplit = 1; a.nk_split = 0; a.ldp = 0; a.part = nullptr; a.ssqpart = nullptr;
     a.A = A; a.B0 = B0; a.B1 = B1; a.C = C; a.gain = gain; a.colc = colc; a.colb = colb;
     a.M = M; a.N = N; a.K = K; a.lda = lda; a.ldb = ldb; a.ldc = ldc; a.eps = eps;
@@ -354,7 +378,7 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
         BB_HIP(hipGetLastError());
         const size_t threads = (size_t)M * (N / 8);
         hipLaunchKernelGGL((splitk_reduce_kernel<SM>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
-                           (const float*)a.part, (const float*)a.ssqpart, C, M, N, K, a.ldp, ldc, nsplit, eps);
+                           (const float*)a.part, (const float*)a.ssqpart, C, M, N, K, a.ldp, ldc, nsplit, eps, res, ldr);
     } else if (big) {
         if (full) go2(std::integral_constant<int, 256>(), T()); else go2(std::integral_constant<int, 256>(), F_());
     } else {
@@ -365,7 +389,7 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
     return BB_OK;
 }
 
-int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u16* W2, u16* Y, int M,
+int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u16* W2, const u16* R, u16* Y, int M,
                int D, int F, float eps, int cus, hipStream_t st) {
     static int resident = -1;      // workgroups of the streaming kernel one compute unit can hold
     if (resident < 0) {
@@ -383,7 +407,7 @@ int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u
         g_ws.bar_count = 0;
     }
     StreamArgs a;
-    a.X = X; a.g = g; a.W1 = W1; a.W3 = W3; a.W2 = W2; a.Y = Y;
+    a.X = X; a.g = g; a.W1 = W1; a.W3 = W3; a.W2 = W2; a.Y = Y; a.R = R;
     a.ppart = (float*)(base + sp.ppart_off);
     a.spart = (float*)(base + sp.spart_off);
     a.H = (u16*)(base + sp.h_off);
@@ -493,9 +517,12 @@ int bb_rmsnorm_swiglu_ffn(const void* X, const void* g, const void* W1, const vo
 namespace {
 
 // the operators with the library lock held and arguments validated
+// R: residual added in the last kernel's epilogue, or null (the unfused program has no such epilogue)
 int ffn_locked(int variant, const void* X, const void* g, const void* W1, const void* W3, const void* W2,
-               void* Y, int64_t M, int64_t D, int64_t F, float eps, void* stream) {
-    if (variant == BB_VARIANT_UNFUSED) return ffn_unfused_locked(X, g, W1, W3, W2, Y, M, D, F, eps, stream);
+               void* Y, int64_t M, int64_t D, int64_t F, float eps, void* stream, const void* R) {
+    if (variant == BB_VARIANT_UNFUSED && R == nullptr)
+        return ffn_unfused_locked(X, g, W1, W3, W2, Y, M, D, F, eps, stream);
+    if (variant == BB_VARIANT_UNFUSED) variant = BB_VARIANT_SNAPSHOT1;
     const DeviceInfo* dev = nullptr;
     if (int rc = current_device_info(&dev)) return rc;
     const size_t zone = zone_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F);
@@ -504,7 +531,7 @@ int ffn_locked(int variant, const void* X, const void* g, const void* W1, const 
     const u16 *x = (const u16*)X, *gg = (const u16*)g, *w1 = (const u16*)W1, *w3 = (const u16*)W3,
               *w2 = (const u16*)W2;
     if (variant == BB_VARIANT_STREAM)
-        return run_stream(x, gg, w1, w3, w2, (u16*)Y, (int)M, (int)D, (int)F, eps, dev->cus, st);
+        return run_stream(x, gg, w1, w3, w2, (const u16*)R, (u16*)Y, (int)M, (int)D, (int)F, eps, dev->cus, st);
     // first snapshot: hidden written once (bf16), then contracted with W2
     u16* H = (u16*)((char*)g_ws.ptr + zone);
     void* split = (char*)H + align_up((size_t)M * F * 2);
@@ -515,7 +542,28 @@ int ffn_locked(int variant, const void* X, const void* g, const void* W1, const 
                                           (int)F, (int)D, eps, pcus, st, split))
         return rc;
     return launch_gemm<MODE_PLAIN>(H, (int)F, w2, nullptr, (int)D, (u16*)Y, (int)D, nullptr, nullptr, nullptr,
-                                   (int)M, (int)D, (int)F, 0.f, pcus, st, split);
+                                   (int)M, (int)D, (int)F, 0.f, pcus, st, split, (const u16*)R, (int)D);
+}
+
+int ffn_t_locked(const void* X, const void* g, const void* W1t, const void* W3t, const void* W2t, void* Y,
+                 int64_t M, int64_t D, int64_t F, float eps, void* stream, const void* R) {
+    const DeviceInfo* dev = nullptr;
+    if (int rc = current_device_info(&dev)) return rc;
+    const size_t zone = zone_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F);
+    if (int rc = ensure_workspace(zone + scratch_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F))) return rc;
+    hipStream_t st = as_stream(stream);
+    u16* H = (u16*)((char*)g_ws.ptr + zone);
+    void* split = (char*)H + align_up((size_t)M * F * 2);
+    const int pcus = std::min(dev->cus, kPlanCUs);
+    mark_dirty(zone);
+    prof_begin(st);
+    if (int rc = (launch_gemm<MODE_GATEUP, true>((const u16*)X, (int)D, (const u16*)W1t, (const u16*)W3t, (int)D, H,
+                                                 (int)F, (const u16*)g, nullptr, nullptr, (int)M, (int)F, (int)D,
+                                                 eps, pcus, st, split)))
+        return rc;
+    return launch_gemm<MODE_PLAIN, true>(H, (int)F, (const u16*)W2t, nullptr, (int)F, (u16*)Y, (int)D, nullptr,
+                                         nullptr, nullptr, (int)M, (int)D, (int)F, 0.f, pcus, st, split,
+                                         (const u16*)R, (int)D);
 }
 
 int ln_locked(int variant, const void* X, const void* gamma, const void* beta, const void* W, void* Y,
@@ -560,22 +608,28 @@ int bb_rmsnorm_swiglu_ffn_t(const void* X, const void* g, const void* W1t, const
     if (int rc = validate_ffn(X, g, W1t, W3t, W2t, Y, M, D, F, eps)) return rc;
     if (M == 0) return BB_OK;
     std::lock_guard<std::mutex> lk(g_mu);
-    const DeviceInfo* dev = nullptr;
-    if (int rc = current_device_info(&dev)) return rc;
-    const size_t zone = zone_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F);
-    if (int rc = ensure_workspace(zone + scratch_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F))) return rc;
-    hipStream_t st = as_stream(stream);
-    u16* H = (u16*)((char*)g_ws.ptr + zone);
-    void* split = (char*)H + align_up((size_t)M * F * 2);
-    const int pcus = std::min(dev->cus, kPlanCUs);
-    mark_dirty(zone);
-    prof_begin(st);
-    if (int rc = (launch_gemm<MODE_GATEUP, true>((const u16*)X, (int)D, (const u16*)W1t, (const u16*)W3t, (int)D, H,
-                                                 (int)F, (const u16*)g, nullptr, nullptr, (int)M, (int)F, (int)D,
-                                                 eps, pcus, st, split)))
-        return rc;
-    return launch_gemm<MODE_PLAIN, true>(H, (int)F, (const u16*)W2t, nullptr, (int)F, (u16*)Y, (int)D, nullptr,
-                                         nullptr, nullptr, (int)M, (int)D, (int)F, 0.f, pcus, st, split);
+    return ffn_t_locked(X, g, W1t, W3t, W2t, Y, M, D, F, eps, stream, nullptr);
+}
+
+int bb_rmsnorm_swiglu_ffn_residual(const void* X, const void* g, const void* W1, const void* W3,
+                                   const void* W2, const void* R, void* Y, int64_t M, int64_t D, int64_t F,
+                                   float eps, void* stream) {
+    if (int rc = validate_ffn_residual(X, g, W1, W3, W2, R, Y, M, D, F, eps)) return rc;
+    if (M == 0) return BB_OK;
+    std::lock_guard<std::mutex> lk(g_mu);
+    int variant = read_variant();
+    if (variant == BB_VARIANT_STREAM && M > kStreamMaxM) return BB_ERR_VARIANT;
+    if (variant == BB_VARIANT_AUTO) variant = auto_variant(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F);
+    return ffn_locked(variant, X, g, W1, W3, W2, Y, M, D, F, eps, stream, R);
+}
+
+int bb_rmsnorm_swiglu_ffn_residual_t(const void* X, const void* g, const void* W1t, const void* W3t,
+                                     const void* W2t, const void* R, void* Y, int64_t M, int64_t D,
+                                     int64_t F, float eps, void* stream) {
+    if (int rc = validate_ffn_residual(X, g, W1t, W3t, W2t, R, Y, M, D, F, eps)) return rc;
+    if (M == 0) return BB_OK;
+    std::lock_guard<std::mutex> lk(g_mu);
+    return ffn_t_locked(X, g, W1t, W3t, W2t, Y, M, D, F, eps, stream, R);
 }
 
 int bb_layernorm_matmul_t(const void* X, const void* gamma, const void* beta, const void* Wt, void* Y,

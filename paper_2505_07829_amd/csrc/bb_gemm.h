@@ -82,6 +82,8 @@ struct GemmArgs {
     int nsplit, nk_split, ldp;
     float* part;
     float* ssqpart;
+    const u16* res;     // PLAIN: residual added to the product before the one rounding ([M, N], row length ldr), or null
+    int ldr;
 };
 
 constexpr int GEMM_THREADS = 256;
@@ -123,6 +125,24 @@ __device__ __forceinline__ void quad_transpose(u32& d0, u32& d1, bool upper, u32
     const u32 yp = (u32)__builtin_amdgcn_update_dpp(0, (int)y, 0xB1, 0xF, 0xF, false);
     d0 = __builtin_amdgcn_perm(xp, x, sel);
     d1 = __builtin_amdgcn_perm(yp, y, sel);
+}
+
+// The same transposition for 32-bit values: in, quad lane e holds y[i] = E[i][e];
+// out, y[j] = E[e][j].  upper = (e & 2) != 0, odd = (e & 1) != 0.
+template <int CTRL>
+__device__ __forceinline__ float quad_swap(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+__device__ __forceinline__ void quad_transpose_f32(float (&y)[4], bool upper, bool odd) {
+    const float r0 = quad_swap<0x4E>(upper ? y[0] : y[2]), r1 = quad_swap<0x4E>(upper ? y[1] : y[3]);   // lane ^ 2
+    // rows 2h, 2h + 1 (h = upper) of columns e & 1 (x) and (e & 1) + 2 (z)
+    const float x0 = upper ? r0 : y[0], x1 = upper ? r1 : y[1];
+    const float z0 = upper ? y[2] : r0, z1 = upper ? y[3] : r1;
+    const float q0 = quad_swap<0xB1>(odd ? x0 : x1), q1 = quad_swap<0xB1>(odd ? z0 : z1);               // lane ^ 1
+    y[0] = odd ? q0 : x0;
+    y[1] = odd ? x1 : q0;
+    y[2] = odd ? q1 : z0;
+    y[3] = odd ? z1 : q1;
 }
 
 // FULL: every tile is complete (M % BM == 0, N % columns-per-tile == 0,
@@ -628,10 +648,22 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
                         y[i] = acc[s][tt][4 * vg + i];
                         if (MODE == MODE_LN) y[i] = fmaf(r[i], y[i] - mu[i] * cc[tt], cb[tt]);
                     }
+                    const int m = m0 + rl + eq, col = scol + 32 * tt;
+                    const bool inside = (FULL || m < p.M) && (FULL || col < p.N);
+                    if (MODE == MODE_PLAIN && p.res != nullptr) {
+                        // residual epilogue: transpose in fp32, add the residual's four values, round once
+                        quad_transpose_f32(y, tup, (eq & 1) != 0);
+                        if (inside) {
+                            const u32x2 rr = *reinterpret_cast<const u32x2*>(p.res + (size_t)m * p.ldr + col);
+                            u32x2 o = {pack_bf16(y[0] + bf_lo(rr[0]), y[1] + bf_hi(rr[0])),
+                                       pack_bf16(y[2] + bf_lo(rr[1]), y[3] + bf_hi(rr[1]))};
+                            *reinterpret_cast<u32x2*>(p.C + (size_t)m * p.ldc + col) = o;
+                        }
+                        continue;
+                    }
                     u32 d0 = pack_bf16(y[0], y[1]), d1 = pack_bf16(y[2], y[3]);
                     quad_transpose(d0, d1, tup, tsel);
-                    const int m = m0 + rl + eq, col = scol + 32 * tt;
-                    if ((FULL || m < p.M) && (FULL || col < p.N)) {
+                    if (inside) {
                         u32x2 o = {d0, d1};
                         *reinterpret_cast<u32x2*>(p.C + (size_t)m * p.ldc + col) = o;
                     }
@@ -642,13 +674,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
 }
 
 // Adds the nsplit partial results of a split contraction in fixed order and
-// applies the epilogue: PLAIN C = bf16(sum); GATEUP h = SiLU(r P) (r Q) with
+// applies the epilogue: PLAIN C = bf16(sum [+ residual]); GATEUP h = SiLU(r P) (r Q) with
 // r = (sum of the partial sums of squares / K + eps)^-1/2.  One thread per row
 // and 8 consecutive output columns.
 template <int MODE>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* part, const float* ssqpart, u16* C,
                                                             int M, int N, int K, int ldp, int ldc, int nsplit,
-                                                            float eps) {
+                                                            float eps, const u16* res, int ldr) {
     const int groups = N / 8;
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (size_t)M * groups) return;
@@ -673,6 +705,11 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* part, c
                   pack_bf16(swiglu(r * a1[0], r * b1[0]), swiglu(r * a1[1], r * b1[1])),
                   pack_bf16(swiglu(r * a1[2], r * b1[2]), swiglu(r * a1[3], r * b1[3]))};
     } else {
+        if (res != nullptr) {           // residual added before the one rounding
+            const u32x4 rr = ldg16(res + (size_t)m * ldr + c0);
+            a0 += f32x4{bf_lo(rr[0]), bf_hi(rr[0]), bf_lo(rr[1]), bf_hi(rr[1])};
+            a1 += f32x4{bf_lo(rr[2]), bf_hi(rr[2]), bf_lo(rr[3]), bf_hi(rr[3])};
+        }
         o = u32x4{pack_bf16(a0[0], a0[1]), pack_bf16(a0[2], a0[3]), pack_bf16(a1[0], a1[1]), pack_bf16(a1[2], a1[3])};
     }
     *reinterpret_cast<u32x4*>(C + (size_t)m * ldc + c0) = o;

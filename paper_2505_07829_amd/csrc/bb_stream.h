@@ -49,6 +49,7 @@ struct StreamArgs {
     const u16* W3;     // [D, F]
     const u16* W2;     // [F, D]
     u16* Y;            // [M, D]
+    const u16* R;      // [M, D] residual added to the output before its one rounding, or null
     float* ppart;      // [nfb][S1][2][16][128] partial pre-activations (P then Q)
     float* spart;      // [S1][16] partial row sums of squares
     u16* H;            // [16][Fp] hidden block, bf16
@@ -465,6 +466,11 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
                 }
 #pragma unroll
                 for (int u = 0; u < 8; ++u) { y0 += v[u][0]; y1 += v[u][1]; }
+            }
+            if (p.R != nullptr) {
+                const u32x4 rr = ldg16(p.R + (size_t)row * p.D + c0);
+                y0 += f32x4{bf_lo(rr[0]), bf_hi(rr[0]), bf_lo(rr[1]), bf_hi(rr[1])};
+                y1 += f32x4{bf_lo(rr[2]), bf_hi(rr[2]), bf_lo(rr[3]), bf_hi(rr[3])};
             }
             const u32x4 o = {pack_bf16(y0[0], y0[1]), pack_bf16(y0[2], y0[3]), pack_bf16(y1[0], y1[1]),
                              pack_bf16(y1[2], y1[3])};

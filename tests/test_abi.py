@@ -111,6 +111,23 @@ def test_attention_argument_errors(lib):
     assert attn(lib, O=3 * A - 64) == -5                    # tail of O runs into V
 
 
+@pytest.mark.parametrize("suffix", ["", "_t"])
+def test_residual_argument_errors_and_aliasing(lib, suffix):
+    fn = getattr(lib, "bb_rmsnorm_swiglu_ffn_residual" + suffix)
+
+    def call(X=A, g=2 * A, W1=3 * A, W3=4 * A, W2=5 * A, R=7 * A, Y=6 * A, M=4, D=64, F=128, eps=1e-6):
+        return fn(X, g, W1, W3, W2, R, Y, M, D, F, eps, None)
+    assert call(M=0) == 0 and call(M=0, R=None) == 0
+    assert call(M=-1) == -2 and call(D=60) == -2 and call(eps=-1.0) == -4
+    for k in ("X", "g", "W1", "W3", "W2", "R", "Y"):
+        assert call(**{k: None}) == -1
+        assert call(**{k: A * 9 + 2}) == -3
+    assert call(Y=A) == -5                          # over X, not in place with R
+    assert call(Y=7 * A + 16) == -5                 # partial overlap with R
+    assert call(Y=5 * A) == -5                      # over a weight
+    assert call(R=A, Y=A + 16) == -5                # R is X, Y overlaps both partially
+
+
 def test_tune_argument_errors(lib):
     import ctypes as C
     f = lib.bb_rmsnorm_swiglu_ffn_tune

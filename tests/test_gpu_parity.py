@@ -324,3 +324,49 @@ def test_tune_layernorm_and_forced_unfused_variant():
         assert "layernorm_rows" in names and row_rel_err(Y, ref) <= TOL
     finally:
         bb.bb_set_variant(bb.VARIANT_AUTO)
+
+
+# ---------------------------------------------------------------- residual epilogue
+def residual_case(M, D, F, seed, transposed=False, in_place=None):
+    X, g, W1, W3, W2 = bb_inputs.make_ffn(M, D, F, seed=seed)
+    R = X if in_place == "x" else bb_inputs.make_ffn(M, D, F, seed=seed + 100)[0]
+    ref = orc.rmsnorm_swiglu_ffn_residual(X, g, W1, W3, W2, R, 1e-6)
+    ws = [w.t().contiguous() for w in (W1, W3, W2)] if transposed else [W1, W3, W2]
+    Xd, gd = X.cuda(), g.cuda()
+    Rd = Xd if in_place == "x" else R.cuda()
+    Yd = Rd if in_place else None
+    Y = bb.bb_rmsnorm_swiglu_ffn_residual(Xd, gd, *[w.cuda() for w in ws], Rd, 1e-6, Y=Yd, transposed=transposed)
+    torch.cuda.synchronize()
+    return row_rel_err(Y, ref)
+
+
+@pytest.mark.parametrize("M,D,F", [(1, 64, 64), (9, 264, 712), (16, 512, 1408),        # streaming kernel
+                                   (17, 72, 136), (96, 512, 1408), (130, 264, 712),     # split contraction / ragged tiles
+                                   (256, 512, 1024), (512, 1024, 2816), (300, 520, 1032)])
+def test_residual_epilogue(M, D, F):
+    assert residual_case(M, D, F, seed=M + F) <= TOL
+
+
+@pytest.mark.parametrize("M,D,F", [(130, 264, 712), (512, 1024, 2816), (16, 256, 704)])
+def test_residual_epilogue_transposed_weights(M, D, F):
+    assert residual_case(M, D, F, seed=7, transposed=True) <= TOL
+
+
+@pytest.mark.parametrize("M,D,F", [(8, 256, 704), (200, 512, 1408), (2048, 1024, 2816)])
+@pytest.mark.parametrize("mode", ["r", "x"])
+def test_residual_in_place(M, D, F, mode):
+    # Y written over R; in mode "x" R is X itself: y = x + FFN(norm(x)) in place
+    assert residual_case(M, D, F, seed=3, in_place=mode) <= TOL
+
+
+def test_residual_dominates_small_ffn_output():
+    # a residual 1000 times larger than the FFN output: the sum is rounded once, so the result is
+    # within half a bf16 step of the exact sum (a second rounding would show as up to a full step)
+    X, g, W1, W3, W2 = bb_inputs.make_ffn(64, 256, 704, seed=21)
+    R = (1000.0 * bb_inputs.make_ffn(64, 256, 704, seed=22)[0].float()).to(torch.bfloat16)
+    ref = orc.rmsnorm_swiglu_ffn_residual(X, g, W1, W3, W2, R, 1e-6)
+    Y = bb.bb_rmsnorm_swiglu_ffn_residual(*dev((X, g, W1, W3, W2, R)), 1e-6).float().cpu().numpy().astype(np.float64)
+    step = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 1e-30))) - 7)       # bf16 spacing at |ref|
+    ffn = ref - R.double().numpy()
+    slack = 2e-2 * np.sqrt((ffn ** 2).mean(axis=1, keepdims=True))               # error of the FFN part itself
+    assert np.all(np.abs(Y - ref) <= 0.5 * step + slack)

@@ -486,3 +486,16 @@ def test_attention_significand_exponent_pairs_agree_and_do_not_overflow(split):
     np.testing.assert_allclose(lo.safe_attention(f64(big)[0], f64(Kb)[0], f64(Vb)[0], **split), Ob, rtol=1e-11, atol=1e-14)
     with np.errstate(over="ignore", invalid="ignore"):
         assert not np.all(np.isfinite(lo.fused_attention(f64(big)[0] * 8, f64(Kb)[0], f64(Vb)[0])))
+
+
+# ---------------------------------------------------------------- residual connection
+def test_residual_is_the_operator_plus_r_and_exact_for_zero_w2():
+    X, g, W1, W3, W2 = bb_inputs.make_ffn(6, 64, 96, seed=12)
+    R = bb_inputs.make_ffn(6, 64, 96, seed=13)[0]
+    base = orc.rmsnorm_swiglu_ffn(X, g, W1, W3, W2, 1e-6)
+    got = orc.rmsnorm_swiglu_ffn_residual(X, g, W1, W3, W2, R, 1e-6)
+    assert np.array_equal(got - base, R.double().numpy() + 0 * base) or np.allclose(got - base, R.double().numpy(), rtol=0, atol=1e-12)
+    zero = torch.zeros_like(W2)
+    assert np.array_equal(orc.rmsnorm_swiglu_ffn_residual(X, g, W1, W3, zero, R, 1e-6), R.double().numpy())
+    rows = [4, 1]
+    assert np.array_equal(orc.rmsnorm_swiglu_ffn_residual(X, g, W1, W3, W2, R, 1e-6, rows=rows), got[rows])
