@@ -229,7 +229,10 @@ int bb_layernorm_matmul_unfused(const void* X, const void* gamma,
  * fp32 (base-2 exponential of score * log2(e)/sqrt(d)), rounded to bf16 as
  * the operand of the second product; output sums and row sums in fp32, the
  * quotient rounded to bf16 once.  No workspace.  Errors as for the other
- * operators.
+ * operators.  The environment variable BB_ATTN_WAVES=4|8 (read once) forces
+ * the number of wavefronts per workgroup (32 queries each) instead of the
+ * shape-driven choice; a query row is computed by one wavefront in the same
+ * order either way, so the results are bit-identical.
  */
 int bb_attention(const void* Q, const void* K, const void* V, void* O,
                  int64_t B, int64_t M, int64_t N, int64_t d, int64_t dv,

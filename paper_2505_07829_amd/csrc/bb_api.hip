@@ -658,8 +658,7 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
     if (B < 0 || M < 0 || N < 1) return BB_ERR_SHAPE;
     if ((d != 64 && d != 128) || (dv != 64 && dv != 128)) return BB_ERR_SHAPE;
     if (M > (1 << 24) || N >= (1 << 24)) return BB_ERR_SHAPE;   // 32-bit byte offsets inside one problem's K and V
-    const int64_t tiles_q = (M + ATTN_BQ - 1) / ATTN_BQ;
-    if (B * tiles_q > 0x7ffffff0LL) return BB_ERR_SHAPE;            // one workgroup per (problem, query block)
+    if (B * ((M + 127) / 128) > 0x7ffffff0LL) return BB_ERR_SHAPE;  // one workgroup per (problem, query block)
     if (B == 0 || M == 0) return BB_OK;
     if (!Q || !K || !V || !O) return BB_ERR_NULL;
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O)) return BB_ERR_ALIGN;
@@ -679,19 +678,30 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
     a.B = (int)B;
     a.M = (int)M;
     a.N = (int)N;
+    // eight wavefronts (256 queries) per workgroup when that still gives every compute unit a
+    // workgroup and wastes little on a ragged last query block; else four (128 queries)
+    static const int forced_waves = [] { const char* e = std::getenv("BB_ATTN_WAVES"); return e ? std::atoi(e) : 0; }();
+    // (measured: +2..7 % for head dimension 128, -4..8 % for 64, where the vector work per block dominates)
+    int nw = d == 128 && dv == 128 && (M % 256 == 0 || M >= 2048) && B * ((M + 255) / 256) >= dev->cus ? 8 : 4;
+    if (forced_waves == 4 || forced_waves == 8) nw = forced_waves;
+    const int64_t tiles_q = (M + 32 * nw - 1) / (32 * nw);
     a.tiles_q = (int)tiles_q;
     a.wgs_per_xcd = (int)((B * tiles_q + 7) / 8);
     a.c = (float)(1.4426950408889634 / std::sqrt((double)d));
-    const dim3 grid((unsigned)(8 * a.wgs_per_xcd)), block(ATTN_THREADS);
+    const dim3 grid((unsigned)(8 * a.wgs_per_xcd)), block((unsigned)(64 * nw));
     prof_begin(st);
     const int64_t nt = (N + ATTN_BK - 1) / ATTN_BK;
     const int tail = nt <= 4 ? (int)nt : ((nt & 1) ? 3 : 4);     // iterations left after the main loop
     auto go = [&](auto DKC, auto DVC) {
         constexpr int DK = decltype(DKC)::value, DV = decltype(DVC)::value;
-        if (tail == 1) hipLaunchKernelGGL((attention_kernel<DK, DV, 1>), grid, block, 0, st, a);
-        else if (tail == 2) hipLaunchKernelGGL((attention_kernel<DK, DV, 2>), grid, block, 0, st, a);
-        else if (tail == 3) hipLaunchKernelGGL((attention_kernel<DK, DV, 3>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((attention_kernel<DK, DV, 4>), grid, block, 0, st, a);
+        auto go_nw = [&](auto NWC) {
+            constexpr int NW = decltype(NWC)::value;
+            if (tail == 1) hipLaunchKernelGGL((attention_kernel<DK, DV, 1, NW>), grid, block, 0, st, a);
+            else if (tail == 2) hipLaunchKernelGGL((attention_kernel<DK, DV, 2, NW>), grid, block, 0, st, a);
+            else if (tail == 3) hipLaunchKernelGGL((attention_kernel<DK, DV, 3, NW>), grid, block, 0, st, a);
+            else hipLaunchKernelGGL((attention_kernel<DK, DV, 4, NW>), grid, block, 0, st, a);
+        };
+        if (nw == 8) go_nw(std::integral_constant<int, 8>{}); else go_nw(std::integral_constant<int, 4>{});
     };
     using I64 = std::integral_constant<int, 64>;
     using I128 = std::integral_constant<int, 128>;

@@ -43,13 +43,12 @@ struct AttnArgs {
     const u16* V;
     u16* O;
     int B, M, N;
-    int tiles_q;        // ceil(M / 128)
+    int tiles_q;        // ceil(M / (32 NW))
     int wgs_per_xcd;    // ceil(B * tiles_q / 8)
     float c;            // log2(e) / sqrt(DK)
 };
 
-constexpr int ATTN_THREADS = 256;
-constexpr int ATTN_BQ = 128;      // queries per workgroup
+// a workgroup has NW = 4 or 8 wavefronts of 32 queries each
 constexpr int ATTN_BK = 64;       // keys per step
 constexpr float ATTN_SLACK = 8.f; // log2 of the largest significand a row keeps before its exponent moves
 
@@ -71,8 +70,12 @@ __device__ __forceinline__ int attn_swz_tr(int row) {
 // complete iterations per trip while at least five key blocks remain).  A
 // template parameter, so that no branch merges the accumulators and only the
 // unrolled tail loads and masks the last key block.
-template <int DK, int DV, int TAIL>
-__global__ __launch_bounds__(ATTN_THREADS, 2) void attention_kernel(const AttnArgs p) {
+// NW: wavefronts per workgroup (4 or 8).  Eight share every K and V block among
+// twice as many queries: half the load-to-LDS instructions per wavefront and
+// half the L2 traffic, one workgroup per compute unit instead of two.
+template <int DK, int DV, int TAIL, int NW>
+__global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p) {
+    constexpr int ATTN_BQ = 32 * NW;
     constexpr int CK = DK / 8, CV = DV / 8;          // 16-byte chunks per K / V row
     constexpr int NKS = DK / 16;                     // contraction slices of the first product
     constexpr int NDS = DV / 32;                     // 32-row subtiles of O^T
@@ -105,8 +108,9 @@ __global__ __launch_bounds__(ATTN_THREADS, 2) void attention_kernel(const AttnAr
     // advances as a uniform pointer.  In the last block rows past the end of
     // the sequence load the last valid row instead (their scores are masked,
     // their probabilities exactly zero).
-    constexpr int RPK = 64 / CK, NIK = ATTN_BK / RPK / 4;     // rows per instruction, instructions per wavefront
-    constexpr int RPV = 64 / CV, NIV = ATTN_BK / RPV / 4;
+    constexpr int RPK = 64 / CK, NIK = ATTN_BK / RPK / NW;    // rows per instruction, instructions per wavefront
+    constexpr int RPV = 64 / CV, NIV = ATTN_BK / RPV / NW;
+    static_assert(NIK >= 1 && NIV >= 1, "every wavefront loads part of each block");
     constexpr int NDMA = NIK + NIV;
     int rowKd[NIK], rowVd[NIV];
     u32 offKd[NIK], offVd[NIV];

@@ -142,3 +142,10 @@ def test_bench_size_sampled_rows():
     err = run(Q, K, V, rows=rows)
     print("attention bench size rel err", err)
     assert err <= TOL
+
+
+def test_eight_wavefront_workgroups_on_the_shape_that_selects_them():
+    # head dimension 128, M a multiple of 256 and enough query blocks for every compute unit:
+    # 256 queries per workgroup; parity as everywhere else
+    Q, K, V = bb_inputs.make_attn(64, 1024, 384, 128, 128, seed=8)
+    assert run(Q, K, V, rows=list(range(0, 64 * 1024, 997))) <= TOL
