@@ -134,6 +134,23 @@ def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
         ms_transposed = e0.elapsed_time(e1) / steps
         del dt
 
+    # the FFN with the decoder block's residual connection fused into the last kernel's epilogue
+    ms_residual = None
+    if cfg.op == "ffn":
+        def stepr(i):
+            d = dev_sets[i % nsets]
+            bb.bb_rmsnorm_swiglu_ffn_residual(*d, d[0], cfg.eps, Y=out)
+        for i in range(warmup):
+            stepr(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(steps):
+            stepr(i)
+        e1.record()
+        torch.cuda.synchronize()
+        ms_residual = e0.elapsed_time(e1) / steps
+
     dom, work, bound = dominant_kernel(cfg, stream_variant)
     dom_ms = kernels_ms[dom]
     if bound == "mfma":
@@ -149,6 +166,7 @@ def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
         "kernels_ms": kernels_ms,
         "unfused_ms_per_step": ms_unfused,
         "transposed_weights_ms_per_step": ms_transposed,
+        "residual_ms_per_step": ms_residual,
         "roofline": {"kernel": dom, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
                      "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((name, dom)),
                      "algorithmic": work},
@@ -371,6 +389,7 @@ def main():
         "kernels_ms": primary["kernels_ms"],
         "unfused_ms_per_step": primary["unfused_ms_per_step"],
         "transposed_weights_ms_per_step": primary["transposed_weights_ms_per_step"],
+        "residual_ms_per_step": primary["residual_ms_per_step"],
         "measured_peaks": peaks,
     }
     if "c2" in others:
@@ -380,6 +399,7 @@ def main():
             "value": d["gbs"], "unit": "GB/s", "ms_per_step": d["ms_per_step"],
             "roofline": d["roofline"], "cpu_baseline": d.get("cpu_baseline"), "parity": d.get("parity"),
             "kernels_ms": d["kernels_ms"], "unfused_ms_per_step": d["unfused_ms_per_step"],
+            "residual_ms_per_step": d["residual_ms_per_step"],
         }
     if attn is not None:
         line["attention"] = attn

@@ -285,3 +285,52 @@ def test_other_programs_fuse_and_stay_correct():
         s.check()
         got = assemble(evaluate(s, {"Q": split(A, 2, 2), "KT": split(B, 2, 2)}, {})["O"])
         assert np.abs(got - want).max() < 1e-12
+
+
+# ---------------------------------------------------------------- numerical safety (Appendix)
+def _attention_blocks(scale, seed=0):
+    from paper_2505_07829_amd.fusion.interp import split
+    rng = np.random.default_rng(seed)
+    c, e = check.COUNTS, check.EDGE
+    Q = scale * rng.standard_normal((c["M"] * e["M"], c["D"] * e["D"]))
+    K = rng.standard_normal((c["N"] * e["N"], c["D"] * e["D"]))
+    V = rng.standard_normal((c["N"] * e["N"], c["L"] * e["L"]))
+    dd = Q.shape[1]
+    S = Q @ K.T / np.sqrt(dd)
+    P = np.exp(S - S.max(axis=1, keepdims=True))                 # the textbook stable softmax
+    want = (P / P.sum(axis=1, keepdims=True)) @ V
+    ins = {"Q": split(Q, c["M"], c["D"]), "KT": split(K, c["N"], c["D"]), "VT": split(V.T.copy(), c["L"], c["N"])}
+    return ins, {"DD": float(dd)}, want, S
+
+
+def test_safety_pass_agrees_with_plain_arithmetic_on_moderate_scores():
+    from paper_2505_07829_amd.fusion.interp import assemble, evaluate
+    ins, consts, want, _ = _attention_blocks(1.0)
+    for s in [lower.example1()] + fusion.fuse(lower.example1()):
+        plain = assemble(evaluate(s, ins, consts)["O"])
+        safe = assemble(evaluate(s, ins, consts, safe=True)["O"])
+        assert np.abs(plain - want).max() < 1e-12 and np.abs(safe - want).max() < 1e-12
+
+
+def test_safety_pass_survives_scores_that_overflow_the_plain_program():
+    # scores of several thousand: exp overflows float64 (709), the unsafe programs return inf/nan,
+    # the same programs evaluated with significand-exponent pairs match the stable softmax
+    from paper_2505_07829_amd.fusion.interp import assemble, evaluate
+    ins, consts, want, S = _attention_blocks(3000.0)
+    assert S.max() > 1000
+    for s in [lower.example1()] + fusion.fuse(lower.example1()):
+        with np.errstate(over="ignore", invalid="ignore"):
+            plain = assemble(evaluate(s, ins, consts)["O"])
+        assert not np.all(np.isfinite(plain))
+        safe = assemble(evaluate(s, ins, consts, safe=True)["O"])
+        assert np.all(np.isfinite(safe)) and np.abs(safe - want).max() < 1e-9
+
+
+def test_pair_addition_is_the_appendix_formula():
+    from paper_2505_07829_amd.fusion.interp import Pair, pair_add
+    a = Pair(np.array([[1.0, 2.0], [3.0, 4.0]]), np.array([5.0, -2.0]))
+    b = Pair(np.array([[0.5, 0.25], [1.0, 1.0]]), np.array([3.0, 1.0]))
+    c = pair_add(a, b)
+    assert np.array_equal(c.t, [5.0, 1.0])                         # z = max(t1, t2) per row
+    assert np.allclose(c.plain(), a.plain() + b.plain(), rtol=1e-15)
+    assert np.allclose(c.s[0], a.s[0] + b.s[0] * np.exp(-2.0)) and np.allclose(c.s[1], a.s[1] * np.exp(-3.0) + b.s[1])
