@@ -32,9 +32,11 @@ class Program:
     def output(self, name: str, v: Value) -> None:
         self.g.nodes.append(Out(name, v))
 
-    def _row_map(self, lists: List[Value], broadcast: List[Value], build) -> Map:
-        """a map over the row dimension of `lists` (iterated) with `broadcast` passed whole;
-        build(inner graph, iterated params, broadcast params) -> list of (inner value, reduced)"""
+    @staticmethod
+    def _make_map(lists: List[Value], broadcast: List[Value], build) -> Map:
+        """a map over the first dimension of `lists` (walked element by element) with `broadcast`
+        passed whole; build(inner graph, parameters of lists, parameters of broadcast) returns
+        the (inner value, reduced) pairs that become the map's outputs"""
         dim = dims_of(lists[0])[0]
         inner = Graph()
         m = Map(dim, inner)
@@ -54,25 +56,14 @@ class Program:
             m.outs.append(MapOut(v, red))
         return m
 
-    @staticmethod
-    def _sub_map(g: Graph, lists: List[Value], broadcast: List[Value], build) -> Map:
-        dim = dims_of(lists[0])[0]
-        inner = Graph()
-        m = Map(dim, inner)
-        inner.parent = m
-        ps, bs = [], []
-        for v in lists:
-            p = In("", dims_of(v)[1:])
-            inner.nodes.append(p)
-            m.ins.append(MapIn(v, p, True))
-            ps.append((p, 0))
-        for v in broadcast:
-            p = In("", dims_of(v))
-            inner.nodes.append(p)
-            m.ins.append(MapIn(v, p, False))
-            bs.append((p, 0))
-        for v, red in build(inner, ps, bs):
-            m.outs.append(MapOut(v, red))
+    def _row_map(self, lists: List[Value], broadcast: List[Value], build) -> Map:
+        """a top-level operator: the map over the row blocks (the caller appends it)"""
+        return self._make_map(lists, broadcast, build)
+
+    @classmethod
+    def _sub_map(cls, g: Graph, lists: List[Value], broadcast: List[Value], build) -> Map:
+        """a map appended to the inner graph g"""
+        m = cls._make_map(lists, broadcast, build)
         g.nodes.append(m)
         return m
 

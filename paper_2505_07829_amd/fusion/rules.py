@@ -184,11 +184,9 @@ def rule9_match(g: Graph) -> Optional[Match]:
 
 def _apply9(m: Match) -> str:
     g, (u, v) = m.graph, m.nodes
-    inner = u.expr
-    # f(g(x)): no extra parentheses when the placeholder is the whole argument of a call
-    bare = all(v.expr[i - 1] == "(" and v.expr[i + 3] == ")" for i in range(len(v.expr)) if v.expr.startswith("{0}", i) and i > 0 and i + 3 < len(v.expr)) \
-        and not v.expr.startswith("{0}") and not v.expr.endswith("{0}")
-    v.expr = v.expr.replace("{0}", inner if bare else "(" + inner + ")")
+    # f(g(x)): no extra parentheses where the placeholder already stands alone between parentheses
+    bare = v.expr.count("{0}") == v.expr.count("({0})")
+    v.expr = v.expr.replace("{0}", u.expr if bare else "(" + u.expr + ")")
     v.operands = list(u.operands)
     g.remove(u)
     return "fuse consecutive elementwise"
