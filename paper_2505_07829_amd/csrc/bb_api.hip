@@ -245,12 +245,23 @@ constexpr int kPlanCUs = 256;   // workgroups assumed by bb_workspace_bytes (one
 // Split contraction: with fewer 128-row tiles than half the compute units (few
 // rows), nsplit workgroups share a tile's contraction range.  Returns nsplit
 // (1 = no split) and the steps per workgroup.
-int plan_split(int mode, int M, int N, int K, int cus, int* nk_split) {
+// A second case (PLAIN only, *bm = 256): the shape has enough 128-row tiles to
+// occupy the chip but only half as many (or fewer) 256-row tiles, and a long
+// contraction: 256-row tiles, which need fewer loads per flop, with the
+// contraction split so that every compute unit gets one.
+int plan_split(int mode, int M, int N, int K, int cus, int* nk_split, int* bm = nullptr) {
     const int ncol = (mode == MODE_GATEUP) ? 128 : 256;
-    const int tiles = ((M + 127) / 128) * ((N + ncol - 1) / ncol);
+    int tiles = ((M + 127) / 128) * ((N + ncol - 1) / ncol);
     const int nk = (K + GEMM_BK - 1) / GEMM_BK;
     *nk_split = nk;
-    if (mode == MODE_LN || tiles * 2 > cus) return 1;
+    if (bm) *bm = 128;
+    if (mode == MODE_LN) return 1;
+    if (tiles * 2 > cus) {
+        const int tiles256 = ((M + 255) / 256) * ((N + ncol - 1) / ncol);
+        if (mode != MODE_PLAIN || M < 256 || tiles256 * 2 > cus || nk < 64) return 1;
+        tiles = tiles256;
+        if (bm) *bm = 256;
+    }
     int S = std::min(std::min(cus / tiles, 16), nk / 4);     // at least four steps per workgroup
     if (S < 2) return 1;
     const int per = (nk + S - 1) / S;
@@ -339,10 +350,10 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
     const int ncol = (MODE == MODE_GATEUP) ? 128 : 256;
     a.tiles_n = (N + ncol - 1) / ncol;
     const int tiles256 = ((M + 255) / 256) * a.tiles_n;
-    int nk_split = 0;
-    const int nsplit = split ? plan_split(MODE, M, N, K, cus, &nk_split) : 1;
+    int nk_split = 0, split_bm = 128;
+    const int nsplit = split ? plan_split(MODE, M, N, K, cus, &nk_split, &split_bm) : 1;
     const bool do_split = nsplit >= 2;
-    const bool big = !do_split && tiles256 >= cus;
+    const bool big = do_split ? split_bm == 256 : tiles256 >= cus;
     const int BM = big ? 256 : 128;
     a.tiles_m = (M + BM - 1) / BM;
     const int tiles = a.tiles_m * a.tiles_n;
@@ -373,8 +384,19 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
     auto go2 = [&](auto BMc, auto FULLc) { if (odd) go(BMc, FULLc, T()); else go(BMc, FULLc, F_()); };
     if (do_split) {
         constexpr int SM = (MODE == MODE_LN) ? MODE_PLAIN : MODE;     // (LN is never split)
-        if (odd) hipLaunchKernelGGL((gemm_kernel<SM, 128, false, true, true, BT>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((gemm_kernel<SM, 128, false, false, true, BT>), grid, block, 0, st, a);
+        if (big) {
+            // (PLAIN only) 256-row tiles; complete tiles and equal shares of the contraction run without bounds checks
+            constexpr int PM = MODE_PLAIN;
+            const bool sfull = full && ((K + GEMM_BK - 1) / GEMM_BK) % nsplit == 0;
+            if (sfull && odd) hipLaunchKernelGGL((gemm_kernel<PM, 256, true, true, true, BT>), grid, block, 0, st, a);
+            else if (sfull) hipLaunchKernelGGL((gemm_kernel<PM, 256, true, false, true, BT>), grid, block, 0, st, a);
+            else if (odd) hipLaunchKernelGGL((gemm_kernel<PM, 256, false, true, true, BT>), grid, block, 0, st, a);
+            else hipLaunchKernelGGL((gemm_kernel<PM, 256, false, false, true, BT>), grid, block, 0, st, a);
+        } else if (odd) {
+            hipLaunchKernelGGL((gemm_kernel<SM, 128, false, true, true, BT>), grid, block, 0, st, a);
+        } else {
+            hipLaunchKernelGGL((gemm_kernel<SM, 128, false, false, true, BT>), grid, block, 0, st, a);
+        }
         BB_HIP(hipGetLastError());
         const size_t threads = (size_t)M * (N / 8);
         hipLaunchKernelGGL((splitk_reduce_kernel<SM>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,

@@ -152,7 +152,8 @@ __device__ __forceinline__ void quad_transpose_f32(float (&y)[4], bool upper, bo
 // SPLIT (PLAIN, GATEUP; for shapes with fewer tiles than half the compute
 // units, i.e. few rows): nsplit workgroups share a tile, each contracts
 // nk_split steps of the contraction range (steps past the end load zeros, so
-// SPLIT kernels are built with FULL = false) and stores its fp32 accumulators
+// SPLIT kernels are built with FULL = false unless the steps divide evenly
+// among the workgroups) and stores its fp32 accumulators
 // (GATEUP: and its partial row sums of squares) instead of running the
 // epilogue; splitk_reduce_kernel adds the partial results in fixed order and
 // applies the epilogue.  This is Rule 3's parallel reduction over the
@@ -532,19 +533,25 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
 
     // ---- split contraction: store the partial results, no epilogue
     if (SPLIT) {
-        static_assert(!SPLIT || (MODE != MODE_LN && !FULL), "split kernels: PLAIN or GATEUP, with bounds checks");
+        static_assert(!SPLIT || MODE != MODE_LN, "split kernels: PLAIN or GATEUP");
         float* const part = p.part + (size_t)split * p.M * p.ldp;
+        const int eqs = l32 & 3;
 #pragma unroll
         for (int s = 0; s < MT; ++s)
 #pragma unroll
             for (int tt = 0; tt < NT; ++tt) {
-                // GATEUP: subtiles 0..3 are the W1 product of hidden units n0 + 32 tt + l32, 4..7 the W3 product
-                const int col = (MODE == MODE_GATEUP) ? n0 + 32 * (tt & 3) + l32 : n0 + WC * wn + 32 * tt + l32;
+                // GATEUP: subtiles 0..3 are the W1 product of hidden units n0 + 32 tt + ..., 4..7 the W3 product.
+                // Four registers (4 rows x this lane's column) are transposed within the quad: the lane then
+                // holds 4 consecutive columns of one row, a 16-byte store.
+                const int col = ((MODE == MODE_GATEUP) ? n0 + 32 * (tt & 3) : n0 + WC * wn + 32 * tt) + 4 * (l32 >> 2);
                 const int pcol = (MODE == MODE_GATEUP && tt >= 4) ? p.N + col : col;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = m0 + WR * wm + 32 * s + 8 * (v >> 2) + 4 * lhi + (v & 3);
-                    if (m < p.M && col < p.N) part[(size_t)m * p.ldp + pcol] = acc[s][tt][v];
+                for (int vg = 0; vg < 4; ++vg) {
+                    float y[4] = {acc[s][tt][4 * vg], acc[s][tt][4 * vg + 1], acc[s][tt][4 * vg + 2], acc[s][tt][4 * vg + 3]};
+                    quad_transpose_f32(y, (eqs & 2) != 0, (eqs & 1) != 0);
+                    const int m = m0 + WR * wm + 32 * s + 8 * vg + 4 * lhi + eqs;
+                    if (m < p.M && col < p.N)           // (N is a multiple of 8: four columns are inside together)
+                        *reinterpret_cast<f32x4*>(part + (size_t)m * p.ldp + pcol) = f32x4{y[0], y[1], y[2], y[3]};
                 }
             }
         if (MODE == MODE_GATEUP) {
