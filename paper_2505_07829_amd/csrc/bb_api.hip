@@ -245,10 +245,10 @@ constexpr int kPlanCUs = 256;   // workgroups assumed by bb_workspace_bytes (one
 // Split contraction: with fewer 128-row tiles than half the compute units (few
 // rows), nsplit workgroups share a tile's contraction range.  Returns nsplit
 // (1 = no split) and the steps per workgroup.
-// A second case (PLAIN only, *bm = 256): the shape has enough 128-row tiles to
-// occupy the chip but only half as many (or fewer) 256-row tiles, and a long
-// contraction: 256-row tiles, which need fewer loads per flop, with the
-// contraction split so that every compute unit gets one.
+// A second case (PLAIN only, *bm = 256): at most half as many 256-row tiles as
+// compute units, a long contraction, and either too many 128-row tiles for
+// the first case or at least 512 rows: 256-row tiles, which need fewer loads
+// per flop, with the contraction split so that every compute unit gets one.
 int plan_split(int mode, int M, int N, int K, int cus, int* nk_split, int* bm = nullptr) {
     const int ncol = (mode == MODE_GATEUP) ? 128 : 256;
     int tiles = ((M + 127) / 128) * ((N + ncol - 1) / ncol);
@@ -256,9 +256,11 @@ int plan_split(int mode, int M, int N, int K, int cus, int* nk_split, int* bm = 
     *nk_split = nk;
     if (bm) *bm = 128;
     if (mode == MODE_LN) return 1;
-    if (tiles * 2 > cus) {
-        const int tiles256 = ((M + 255) / 256) * ((N + ncol - 1) / ncol);
-        if (mode != MODE_PLAIN || M < 256 || tiles256 * 2 > cus || nk < 64) return 1;
+    const int tiles256 = ((M + 255) / 256) * ((N + ncol - 1) / ncol);
+    const bool can256 = mode == MODE_PLAIN && M >= 256 && tiles256 * 2 <= cus && nk >= 64;
+    // (measured on D=4096, F=11008: from 512 rows on the 256-row tiles win also where 128-row tiles could split)
+    if (tiles * 2 > cus || (can256 && M >= 512)) {
+        if (!can256) return 1;
         tiles = tiles256;
         if (bm) *bm = 256;
     }
