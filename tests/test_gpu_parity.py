@@ -370,3 +370,25 @@ def test_residual_dominates_small_ffn_output():
     ffn = ref - R.double().numpy()
     slack = 2e-2 * np.sqrt((ffn ** 2).mean(axis=1, keepdims=True))               # error of the FFN part itself
     assert np.all(np.abs(Y - ref) <= 0.5 * step + slack)
+
+
+# ---------------------------------------------------------------- split contraction with 256-row tiles
+@pytest.mark.parametrize("M,D,F", [(520, 1032, 4104),     # ragged rows, columns and contraction; odd steps per workgroup
+                                   (520, 1032, 6144),     # even steps per workgroup
+                                   (512, 1024, 8192),     # complete tiles: the variant without bounds checks
+                                   (768, 768, 4096)])
+def test_split_contraction_256_row_tiles(M, D, F):
+    # the down projection of these shapes has few 256-row tiles and a long contraction: 256-row
+    # tiles with the contraction split over workgroups (also through the transposed layout and
+    # with the residual added by the reduce kernel)
+    cpu = bb_inputs.make_ffn(M, D, F, seed=M + F)
+    rows = sample_rows(M, tile=256, extra=10, seed=1)
+    X, g, W1, W3, W2 = cpu
+    ref = orc.rmsnorm_swiglu_ffn(X, g, W1, W3, W2, 1e-6, rows=rows)
+    d = dev(cpu)
+    Y = bb.bb_rmsnorm_swiglu_ffn(*d, 1e-6)
+    assert row_rel_err(Y[rows], ref) <= TOL
+    Yt = bb.bb_rmsnorm_swiglu_ffn_t(d[0], d[1], *[w.t().contiguous() for w in d[2:]], 1e-6)
+    assert row_rel_err(Yt[rows], ref) <= TOL
+    Yr = bb.bb_rmsnorm_swiglu_ffn_residual(*d, d[0], 1e-6)
+    assert row_rel_err(Yr[rows], ref + X[rows].double().numpy()) <= TOL
