@@ -259,6 +259,34 @@ def run_attention(steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
                                "cores": orc.num_threads(), "kind": "oracle",
                                "sample": f"{len(rows)} of {w['B'] * w['M']} query rows, {sec:.2f} s"}
     del Q, K, V, O
+    # few queries (decoding): one query per head against the same keys, keys split over workgroups;
+    # bandwidth-bound: K and V are read once
+    wd = dict(w, M=1)
+    cpu_d = bb_inputs.make_attn(wd["B"], 1, wd["N"], wd["d"], wd["dv"], seed=1)
+    Qd, Kd, Vd = [t.cuda() for t in cpu_d]
+    Od = torch.empty((wd["B"], 1, wd["dv"]), dtype=torch.bfloat16, device="cuda")
+    for _ in range(warmup):
+        bb.bb_attention(Qd, Kd, Vd, Od)
+    bb.bb_profile_enable(True)
+    per = []
+    for _ in range(steps):
+        bb.bb_attention(Qd, Kd, Vd, Od)
+        per.append(dict(bb.bb_profile_last())["attention"])
+    bb.bb_profile_enable(False)
+    d_ms = float(np.mean(per))
+    d_bytes = 2.0 * wd["B"] * (wd["N"] * (wd["d"] + wd["dv"]) + wd["d"] + wd["dv"])
+    refd = orc.attention(*cpu_d)
+    od = Od.reshape(-1, wd["dv"]).float().cpu().numpy().astype(np.float64)
+    res["decode"] = {
+        "workload": "attention B=%(B)d M=1 N=%(N)d d=%(d)d dv=%(dv)d (keys split over workgroups + combine)" % wd,
+        "kernels_ms": {"attention": d_ms},
+        "roofline": {"kernel": "attention (split keys) + combine", "bound": "hbm",
+                     "achieved": d_bytes / (d_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": d_bytes / (d_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None, "algorithmic": d_bytes},
+        "parity": {"max_row_rel_err": float((np.linalg.norm(od - refd, axis=1) / np.linalg.norm(refd, axis=1)).max()),
+                   "rows_checked": wd["B"], "tolerance": 2e-2},
+    }
+    del Qd, Kd, Vd, Od
     torch.cuda.empty_cache()
     return res
 

@@ -228,8 +228,16 @@ int bb_layernorm_matmul_unfused(const void* X, const void* gamma,
  * M <= 2^24.  Scores are accumulated in fp32, scaled and exponentiated in
  * fp32 (base-2 exponential of score * log2(e)/sqrt(d)), rounded to bf16 as
  * the operand of the second product; output sums and row sums in fp32, the
- * quotient rounded to bf16 once.  No workspace.  Errors as for the other
- * operators.  The environment variable BB_ATTN_WAVES=4|8 (read once) forces
+ * quotient rounded to bf16 once.  Errors as for the other operators.
+ *
+ * Few queries (decoding: fewer (problem, 128-query block) pairs than half the
+ * compute units, and at least 8 blocks of 64 keys): the loop over the key
+ * blocks is cut into equal ranges that run in parallel workgroups (Rule 3's
+ * parallel form); each stores its unnormalised output and row sum with their
+ * row exponents, fp32, and a second kernel adds these significand-exponent
+ * pairs (Appendix: both terms brought to the larger exponent) and divides.
+ * This path uses bb_attention_workspace_bytes(B, M, N, d, dv) bytes of the
+ * library workspace (0 when the keys are not split; see bb_set_workspace).  The environment variable BB_ATTN_WAVES=4|8 (read once) forces
  * the number of wavefronts per workgroup (32 queries each) instead of the
  * shape-driven choice; a query row is computed by one wavefront in the same
  * order either way, so the results are bit-identical.
@@ -237,6 +245,8 @@ int bb_layernorm_matmul_unfused(const void* X, const void* gamma,
 int bb_attention(const void* Q, const void* K, const void* V, void* O,
                  int64_t B, int64_t M, int64_t N, int64_t d, int64_t dv,
                  void* stream);
+size_t bb_attention_workspace_bytes(int64_t B, int64_t M, int64_t N, int64_t d,
+                                    int64_t dv);
 
 /* ------------------------------------------------------------------------
  * Measured selection (Section 4: the fusion algorithm returns several

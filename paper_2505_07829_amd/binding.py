@@ -21,7 +21,7 @@ OP_FFN, OP_LN, OP_FFN_UNFUSED, OP_LN_UNFUSED = 0, 1, 2, 3
 EXPORTS = [
     "bb_rmsnorm_swiglu_ffn", "bb_layernorm_matmul",
     "bb_rmsnorm_swiglu_ffn_unfused", "bb_layernorm_matmul_unfused",
-    "bb_rmsnorm_swiglu_ffn_t", "bb_layernorm_matmul_t", "bb_attention",
+    "bb_rmsnorm_swiglu_ffn_t", "bb_layernorm_matmul_t", "bb_attention", "bb_attention_workspace_bytes",
     "bb_rmsnorm_swiglu_ffn_residual", "bb_rmsnorm_swiglu_ffn_residual_t",
     "bb_rmsnorm_swiglu_ffn_tune", "bb_layernorm_matmul_tune", "bb_tuned_variant", "bb_tune_clear",
     "bb_workspace_bytes", "bb_set_workspace", "bb_set_variant", "bb_get_variant",
@@ -66,6 +66,8 @@ def load() -> ctypes.CDLL:
     lib.bb_rmsnorm_swiglu_ffn_residual.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
     lib.bb_rmsnorm_swiglu_ffn_residual_t.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
     lib.bb_attention.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, vp]
+    lib.bb_attention_workspace_bytes.argtypes = [i64, i64, i64, i64, i64]
+    lib.bb_attention_workspace_bytes.restype = sz
     lib.bb_workspace_bytes.argtypes = [ci, i64, i64, i64]
     lib.bb_workspace_bytes.restype = sz
     lib.bb_set_workspace.argtypes = [vp, sz]
@@ -80,7 +82,7 @@ def load() -> ctypes.CDLL:
     lib.bb_profile_get.argtypes = [ci, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_char_p)]
     for name in EXPORTS:
         fn = getattr(lib, name)
-        if name not in ("bb_workspace_bytes", "bb_status_string"):
+        if name not in ("bb_workspace_bytes", "bb_status_string", "bb_attention_workspace_bytes"):
             fn.restype = ci
     _lib = lib
     return lib
@@ -222,6 +224,10 @@ def bb_attention(Q, K, V, O=None):
     _require(O, (B, M, dv), "O")
     _check(lib.bb_attention(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), B, M, N, d, dv, _stream()), "bb_attention")
     return O
+
+
+def bb_attention_workspace_bytes(B: int, M: int, N: int, d: int, dv: int) -> int:
+    return int(load().bb_attention_workspace_bytes(B, M, N, d, dv))
 
 
 def bb_layernorm_matmul_t(X, gamma, beta, Wt, eps: float, Y=None):

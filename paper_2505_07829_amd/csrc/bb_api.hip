@@ -281,6 +281,17 @@ size_t split_bytes(int mode, int64_t M, int64_t N, int64_t K, int cus) {
 }
 
 
+// Key splits of the attention kernel for `wgs` (problem, query block) pairs and nt key blocks:
+// the largest divisor of nt that keeps about two workgroups per compute unit and at least two
+// key blocks per workgroup; 1 = no split (enough workgroups already, or a short sequence).
+int attn_key_splits(int64_t wgs, int64_t nt, int cus) {
+    if (wgs * 2 > cus || nt < 8) return 1;
+    const int64_t target = std::min<int64_t>((2 * (int64_t)cus) / wgs, nt / 2);
+    for (int64_t s = target; s >= 2; --s)
+        if (nt % s == 0) return (int)s;
+    return 1;
+}
+
 size_t zone_bytes(int op, int64_t M, int64_t D, int64_t F) {
     if (op == BB_OP_RMSNORM_SWIGLU_FFN && M <= kStreamMaxM) return stream_plan(D, F, kPlanCUs).total_bytes;
     return 0;
@@ -702,19 +713,36 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
     a.B = (int)B;
     a.M = (int)M;
     a.N = (int)N;
+    // few queries (decoding): split the keys over workgroups so that the chip has about two per
+    // compute unit; equal numbers of key blocks per workgroup, at least two each
+    const int64_t nt_all = (N + ATTN_BK - 1) / ATTN_BK;
+    const int ksplit = attn_key_splits(B * ((M + 127) / 128), nt_all, std::min(dev->cus, kPlanCUs));
     // eight wavefronts (256 queries) per workgroup when that still gives every compute unit a
     // workgroup and wastes little on a ragged last query block; else four (128 queries)
     static const int forced_waves = [] { const char* e = std::getenv("BB_ATTN_WAVES"); return e ? std::atoi(e) : 0; }();
     // (measured: +2..7 % for head dimension 128, -4..8 % for 64, where the vector work per block dominates)
     int nw = d == 128 && dv == 128 && (M % 256 == 0 || M >= 2048) && B * ((M + 255) / 256) >= dev->cus ? 8 : 4;
     if (forced_waves == 4 || forced_waves == 8) nw = forced_waves;
+    if (ksplit > 1) nw = 4;
     const int64_t tiles_q = (M + 32 * nw - 1) / (32 * nw);
     a.tiles_q = (int)tiles_q;
-    a.wgs_per_xcd = (int)((B * tiles_q + 7) / 8);
+    a.wgs_per_xcd = (int)((B * tiles_q * ksplit + 7) / 8);
     a.c = (float)(1.4426950408889634 / std::sqrt((double)d));
+    a.nsplit = ksplit;
+    a.nt_split = (int)(nt_all / ksplit);
+    a.part = nullptr;
+    a.ml = nullptr;
+    if (ksplit > 1) {
+        const size_t rows = (size_t)B * M;
+        const size_t pbytes = align_up(rows * ksplit * dv * 4);
+        if (int rc = ensure_workspace(pbytes + align_up(rows * ksplit * 8))) return rc;
+        mark_dirty(0);
+        a.part = (float*)g_ws.ptr;
+        a.ml = (float*)((char*)g_ws.ptr + pbytes);
+    }
     const dim3 grid((unsigned)(8 * a.wgs_per_xcd)), block((unsigned)(64 * nw));
     prof_begin(st);
-    const int64_t nt = (N + ATTN_BK - 1) / ATTN_BK;
+    const int64_t nt = nt_all / ksplit;                            // key blocks per workgroup
     const int tail = nt <= 4 ? (int)nt : ((nt & 1) ? 3 : 4);     // iterations left after the main loop
     auto go = [&](auto DKC, auto DVC) {
         constexpr int DK = decltype(DKC)::value, DV = decltype(DVC)::value;
@@ -725,7 +753,19 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
             else if (tail == 3) hipLaunchKernelGGL((attention_kernel<DK, DV, 3, NW>), grid, block, 0, st, a);
             else hipLaunchKernelGGL((attention_kernel<DK, DV, 4, NW>), grid, block, 0, st, a);
         };
-        if (nw == 8) go_nw(std::integral_constant<int, 8>{}); else go_nw(std::integral_constant<int, 4>{});
+        if (ksplit > 1) {
+            if (tail == 1) hipLaunchKernelGGL((attention_kernel<DK, DV, 1, 4, true>), grid, block, 0, st, a);
+            else if (tail == 2) hipLaunchKernelGGL((attention_kernel<DK, DV, 2, 4, true>), grid, block, 0, st, a);
+            else if (tail == 3) hipLaunchKernelGGL((attention_kernel<DK, DV, 3, 4, true>), grid, block, 0, st, a);
+            else hipLaunchKernelGGL((attention_kernel<DK, DV, 4, 4, true>), grid, block, 0, st, a);
+            const size_t threads = (size_t)B * M * (DV / 8);
+            hipLaunchKernelGGL((attention_combine_kernel<DV>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0,
+                               st, (const float*)a.part, (const float*)a.ml, a.O, (size_t)B * M, ksplit, a.c);
+        } else if (nw == 8) {
+            go_nw(std::integral_constant<int, 8>{});
+        } else {
+            go_nw(std::integral_constant<int, 4>{});
+        }
     };
     using I64 = std::integral_constant<int, 64>;
     using I128 = std::integral_constant<int, 128>;
@@ -736,6 +776,14 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
     BB_HIP(hipGetLastError());
     prof_mark("attention", st);
     return BB_OK;
+}
+
+size_t bb_attention_workspace_bytes(int64_t B, int64_t M, int64_t N, int64_t d, int64_t dv) {
+    if (B < 0 || M < 0 || N < 1 || (d != 64 && d != 128) || (dv != 64 && dv != 128)) return 0;
+    const int s = attn_key_splits(B * ((M + 127) / 128), (N + ATTN_BK - 1) / ATTN_BK, kPlanCUs);
+    if (s < 2) return 0;
+    const size_t rows = (size_t)B * M;
+    return align_up(rows * s * dv * 4) + align_up(rows * s * 8);
 }
 
 int bb_rmsnorm_swiglu_ffn_unfused(const void* X, const void* g, const void* W1, const void* W3,

@@ -46,6 +46,11 @@ struct AttnArgs {
     int tiles_q;        // ceil(M / (32 NW))
     int wgs_per_xcd;    // ceil(B * tiles_q / 8)
     float c;            // log2(e) / sqrt(DK)
+    // split keys (KSPLIT kernels): nsplit workgroups per (problem, query block), each over
+    // nt_split key blocks; unnormalised outputs and (exponent, row sum) pairs go to part / ml
+    int nsplit, nt_split;
+    float* part;        // [B M][nsplit][DV]
+    float* ml;          // [B M][nsplit][2]
 };
 
 // a workgroup has NW = 4 or 8 wavefronts of 32 queries each
@@ -73,7 +78,12 @@ __device__ __forceinline__ int attn_swz_tr(int row) {
 // NW: wavefronts per workgroup (4 or 8).  Eight share every K and V block among
 // twice as many queries: half the load-to-LDS instructions per wavefront and
 // half the L2 traffic, one workgroup per compute unit instead of two.
-template <int DK, int DV, int TAIL, int NW>
+// KSPLIT (few queries, e.g. decoding): the serial loop over the key blocks is
+// cut into nsplit equal ranges that run in parallel workgroups (Rule 3's
+// parallel form); each stores its accumulators as significand-exponent pairs
+// (output sums and row sum at its own row exponents) and
+// attention_combine_kernel adds them the Appendix's way.
+template <int DK, int DV, int TAIL, int NW, bool KSPLIT = false>
 __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p) {
     constexpr int ATTN_BQ = 32 * NW;
     constexpr int CK = DK / 8, CV = DV / 8;          // 16-byte chunks per K / V row
@@ -89,12 +99,15 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p)
     // workgroup id -> XCD (id % 8) -> a contiguous range of (problem, query
     // block) pairs per XCD: the workgroups resident on one XCD then work on
     // the same one or two problems and share their K and V blocks in its L2
-    const int lin = (blockIdx.x & 7) * p.wgs_per_xcd + (blockIdx.x >> 3);
-    if (lin >= p.B * p.tiles_q) return;
+    const int lin0 = (blockIdx.x & 7) * p.wgs_per_xcd + (blockIdx.x >> 3);
+    if (lin0 >= p.B * p.tiles_q * (KSPLIT ? p.nsplit : 1)) return;
+    const int split = KSPLIT ? lin0 % p.nsplit : 0, lin = KSPLIT ? lin0 / p.nsplit : lin0;
     const int b = lin / p.tiles_q, qt = lin % p.tiles_q;
     const int q = qt * ATTN_BQ + 32 * w + l32;          // this lane's query
-    const u16* const Kb = p.K + (size_t)b * p.N * DK;
-    const u16* const Vb = p.V + (size_t)b * p.N * DV;
+    const int key_first = KSPLIT ? split * p.nt_split * ATTN_BK : 0;       // first key of this workgroup
+    const int nkeys = p.N - key_first;                                    // keys from there to the end of the sequence
+    const u16* const Kb = p.K + ((size_t)b * p.N + key_first) * DK;
+    const u16* const Vb = p.V + ((size_t)b * p.N + key_first) * DV;
 
     // Q fragments: B operand of S^T = K Q^T: column = query, 8 consecutive features
     Chunk qf[NKS];
@@ -133,7 +146,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p)
         constexpr int W = decltype(WHICH)::value;
         if (W == 0) return;
         const int key0 = kt * ATTN_BK;
-        const int rmax = p.N - 1 - key0;                  // last valid row of the block
+        const int rmax = nkeys - 1 - key0;                // last valid row of the block
 #pragma unroll
         for (int j = 0; j < NIK; ++j) {
             const u32 off = W == 2 ? offKd[j] - (u32)(max(rowKd[j] - rmax, 0) * DK) : offKd[j];
@@ -144,7 +157,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p)
         constexpr int W = decltype(WHICH)::value;
         if (W == 0) return;
         const int key0 = kt * ATTN_BK;
-        const int rmax = p.N - 1 - key0;
+        const int rmax = nkeys - 1 - key0;
 #pragma unroll
         for (int j = 0; j < NIV; ++j) {
             const u32 off = W == 2 ? offVd[j] - (u32)(max(rowVd[j] - rmax, 0) * DV) : offVd[j];
@@ -169,7 +182,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p)
     float m_run = -INFINITY;      // running exponent of this query's row (in score units)
     float l_run = 0.f;            // this lane's share of the row sum, at exponent m_run
 
-    const int nt = (p.N + ATTN_BK - 1) / ATTN_BK;
+    const int nt = KSPLIT ? p.nt_split : (p.N + ATTN_BK - 1) / ATTN_BK;
 
     // byte offsets of this lane's fragment reads inside a K / V buffer (the XOR
     // swizzles do not depend on the 32-key subtile or the 16-key slice, which
@@ -226,7 +239,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int key = kt * ATTN_BK + 32 * st + 8 * (v >> 2) + 4 * g + (v & 3);
-                if (key >= p.N) sc[PAR][st][v] = -INFINITY;
+                if (key >= nkeys) sc[PAR][st][v] = -INFINITY;
             }
     };
     auto block_max = [&](auto PARC) {
@@ -378,6 +391,20 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p)
     // ---- divide by the row sums and store: register v of subtile ds is value
     // column 32 ds + 8 (v / 4) + 4 g + v % 4 of this lane's query
     const float l = l_run + __shfl_xor(l_run, 32);
+    if (KSPLIT) {
+        if (q < p.M) {
+            const size_t slot = ((size_t)b * p.M + q) * p.nsplit + split;
+            float* const orow = p.part + slot * DV;
+#pragma unroll
+            for (int ds = 0; ds < NDS; ++ds)
+#pragma unroll
+                for (int vg = 0; vg < 4; ++vg)
+                    *reinterpret_cast<f32x4*>(orow + 32 * ds + 8 * vg + 4 * g) =
+                        f32x4{oacc[ds][4 * vg], oacc[ds][4 * vg + 1], oacc[ds][4 * vg + 2], oacc[ds][4 * vg + 3]};
+            if (g == 0) *reinterpret_cast<f32x2*>(p.ml + 2 * slot) = f32x2{m_run, l};
+        }
+        return;
+    }
     const float inv = 1.0f / l;
     if (q < p.M) {
         u16* const orow = p.O + ((size_t)b * p.M + q) * DV;
@@ -390,6 +417,35 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p)
                 *reinterpret_cast<u32x2*>(orow + 32 * ds + 8 * vg + 4 * g) = o;
             }
     }
+}
+
+// Adds the nsplit partial results of a query row: pairs (O_s, m_s) and (l_s, m_s)
+// are brought to the largest exponent, summed, and the quotient is rounded to
+// bf16.  One thread per row and 8 consecutive output columns.
+template <int DV>
+__global__ __launch_bounds__(256) void attention_combine_kernel(const float* part, const float* ml, u16* O,
+                                                                 size_t rows, int nsplit, float c) {
+    constexpr int G = DV / 8;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= rows * G) return;
+    const size_t row = idx / G;
+    const int c0 = 8 * (int)(idx % G);
+    float z = -INFINITY;
+    for (int sp = 0; sp < nsplit; ++sp) z = fmaxf(z, ml[2 * (row * nsplit + sp)]);
+    f32x4 a0 = {0, 0, 0, 0}, a1 = a0;
+    float l = 0.f;
+    for (int sp = 0; sp < nsplit; ++sp) {
+        const size_t slot = row * nsplit + sp;
+        const float wgt = __builtin_amdgcn_exp2f((ml[2 * slot] - z) * c);
+        l = fmaf(ml[2 * slot + 1], wgt, l);
+        const float* src = part + slot * DV + c0;
+        a0 += *reinterpret_cast<const f32x4*>(src) * wgt;
+        a1 += *reinterpret_cast<const f32x4*>(src + 4) * wgt;
+    }
+    const float inv = 1.0f / l;
+    const u32x4 o = {pack_bf16(a0[0] * inv, a0[1] * inv), pack_bf16(a0[2] * inv, a0[3] * inv),
+                     pack_bf16(a1[0] * inv, a1[1] * inv), pack_bf16(a1[2] * inv, a1[3] * inv)};
+    *reinterpret_cast<u32x4*>(O + row * DV + c0) = o;
 }
 
 }  // namespace bb

@@ -149,3 +149,50 @@ def test_eight_wavefront_workgroups_on_the_shape_that_selects_them():
     # 256 queries per workgroup; parity as everywhere else
     Q, K, V = bb_inputs.make_attn(64, 1024, 384, 128, 128, seed=8)
     assert run(Q, K, V, rows=list(range(0, 64 * 1024, 997))) <= TOL
+
+
+# ---------------------------------------------------------------- few queries: keys split over workgroups
+@pytest.mark.parametrize("B,M,N", [(32, 1, 4096), (8, 1, 8192), (4, 16, 2048), (2, 130, 4096), (1, 1, 777),
+                                   (3, 5, 64 * 13), (16, 1, 4096 + 17)])
+@pytest.mark.parametrize("d,dv", [(128, 128), (64, 128)])
+def test_split_keys_decode_shapes(B, M, N, d, dv):
+    # (several of these split the keys, the ones whose block count has no suitable divisor or that
+    # are short do not; bb_attention_workspace_bytes says which)
+    err = run(*bb_inputs.make_attn(B, M, N, d, dv, seed=B + N))
+    assert err <= TOL
+
+
+def test_split_keys_is_taken_and_needs_workspace():
+    assert bb.bb_attention_workspace_bytes(32, 1, 4096, 128, 128) > 0
+    assert bb.bb_attention_workspace_bytes(32, 4096, 4096, 128, 128) == 0      # enough query blocks
+    assert bb.bb_attention_workspace_bytes(32, 1, 256, 128, 128) == 0          # short sequence
+    assert bb.bb_attention_workspace_bytes(1, 1, 64 * 13, 128, 128) == 0       # 13 blocks: no divisor
+    assert bb.bb_attention_workspace_bytes(2, 2, 4096, 96, 128) == 0           # invalid head dimension
+
+
+def test_split_keys_large_scores_and_late_maximum():
+    # the maximum of a row sits in the last split for some queries and in the first for others, and
+    # the scores are large: the partial results carry very different exponents
+    Q, K, V = bb_inputs.make_attn(2, 8, 4096, 128, 128, seed=4, q_scale=30.0)
+    K = K.float()
+    K[0, 4090] = 4.0 * Q[0, 0].float()
+    K[1, 5] = 4.0 * Q[1, 3].float()
+    assert run(Q, K.to(torch.bfloat16), V) <= TOL
+
+
+def test_split_keys_with_caller_workspace_too_small_is_an_error():
+    Q, K, V = [t.cuda() for t in bb_inputs.make_attn(32, 1, 4096, 128, 128, seed=1)]
+    need = bb.bb_attention_workspace_bytes(32, 1, 4096, 128, 128)
+    ws = torch.zeros(need // 2 // 256 * 256, dtype=torch.uint8, device="cuda")
+    bb.bb_set_workspace(ws)
+    try:
+        with pytest.raises(bb.BBError) as e:
+            bb.bb_attention(Q, K, V)
+        assert e.value.status == -7
+        big = torch.zeros(need, dtype=torch.uint8, device="cuda")
+        bb.bb_set_workspace(big)
+        O = bb.bb_attention(Q, K, V)
+        torch.cuda.synchronize()
+        assert torch.isfinite(O.float()).all()
+    finally:
+        bb.bb_set_workspace(None)
