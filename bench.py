@@ -29,13 +29,13 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this same script (profiles/hbm_traffic_c2_c3.txt; FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 as
+# this same script (profiles/hbm_traffic_c2_c3_attention.txt; FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 as
 # calibrated against bb_calib_copy).  Counters cannot be read from inside a timed run, so the
 # figures are carried here; workloads without a counter run report null.
 MEASURED_TRAFFIC_BYTES = {
     ("c2", "ffn_stream"): 281.2e6 + 16.2e6,
     ("c3", "gemm_gateup"): 621.5e6 + 45.2e6,
-    ("attention", "attention"): 103.0e6 + 35.7e6,
+    ("attention", "attention"): 100.9e6 + 33.6e6,
 }
 
 
@@ -388,7 +388,7 @@ def main():
                           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
                           "data": "synthetic", "config": {"workload": attn["workload"]},
                           "roofline": attn["roofline"], "cpu_baseline": attn.get("cpu_baseline"),
-                          "parity": attn.get("parity")}))
+                          "parity": attn.get("parity"), "decode": attn.get("decode")}))
         return
     primary = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu, torch, bb, bb_inputs, orc, np)
     others = {}

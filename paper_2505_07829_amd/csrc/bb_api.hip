@@ -758,9 +758,8 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
             else if (tail == 2) hipLaunchKernelGGL((attention_kernel<DK, DV, 2, 4, true>), grid, block, 0, st, a);
             else if (tail == 3) hipLaunchKernelGGL((attention_kernel<DK, DV, 3, 4, true>), grid, block, 0, st, a);
             else hipLaunchKernelGGL((attention_kernel<DK, DV, 4, 4, true>), grid, block, 0, st, a);
-            const size_t threads = (size_t)B * M * (DV / 8);
-            hipLaunchKernelGGL((attention_combine_kernel<DV>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0,
-                               st, (const float*)a.part, (const float*)a.ml, a.O, (size_t)B * M, ksplit, a.c);
+            hipLaunchKernelGGL((attention_combine_kernel<DV>), dim3((unsigned)(B * M)), dim3(64), 0, st,
+                               (const float*)a.part, (const float*)a.ml, a.O, ksplit, a.c);
         } else if (nw == 8) {
             go_nw(std::integral_constant<int, 8>{});
         } else {

@@ -419,33 +419,49 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p)
     }
 }
 
-// Adds the nsplit partial results of a query row: pairs (O_s, m_s) and (l_s, m_s)
-// are brought to the largest exponent, summed, and the quotient is rounded to
-// bf16.  One thread per row and 8 consecutive output columns.
+// Adds the nsplit partial results of a query row.  Every partial result is a
+// pair (significands O_s and l_s, row exponent m_s); two pairs are added by
+// bringing both to the larger exponent (Appendix), and the quotient of the
+// totals is rounded to bf16.  One wavefront per row: lane = (group of 8 output
+// columns, phase); a phase adds every (64 / groups)-th partial result, then the
+// phases are added across lanes.
 template <int DV>
-__global__ __launch_bounds__(256) void attention_combine_kernel(const float* part, const float* ml, u16* O,
-                                                                 size_t rows, int nsplit, float c) {
-    constexpr int G = DV / 8;
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= rows * G) return;
-    const size_t row = idx / G;
-    const int c0 = 8 * (int)(idx % G);
-    float z = -INFINITY;
-    for (int sp = 0; sp < nsplit; ++sp) z = fmaxf(z, ml[2 * (row * nsplit + sp)]);
+__global__ __launch_bounds__(64) void attention_combine_kernel(const float* part, const float* ml, u16* O,
+                                                                int nsplit, float c) {
+    constexpr int G = DV / 8, NPH = 64 / G;
+    const size_t row = blockIdx.x;
+    const int lane = threadIdx.x, cg = lane % G, ph = lane / G;
+    float z = -INFINITY, l = 0.f;
     f32x4 a0 = {0, 0, 0, 0}, a1 = a0;
-    float l = 0.f;
-    for (int sp = 0; sp < nsplit; ++sp) {
+    // (z, l, a) += (z2, l2, b): both to the larger exponent; equal exponents (also -inf = -inf) need no scaling
+    auto add = [&](float z2, float l2, const f32x4& b0, const f32x4& b1) {
+        const float zn = fmaxf(z, z2);
+        const float w1 = (z == zn) ? 1.f : __builtin_amdgcn_exp2f((z - zn) * c);
+        const float w2 = (z2 == zn) ? 1.f : __builtin_amdgcn_exp2f((z2 - zn) * c);
+        l = l * w1 + l2 * w2;
+        a0 = a0 * w1 + b0 * w2;
+        a1 = a1 * w1 + b1 * w2;
+        z = zn;
+    };
+    for (int sp = ph; sp < nsplit; sp += NPH) {
         const size_t slot = row * nsplit + sp;
-        const float wgt = __builtin_amdgcn_exp2f((ml[2 * slot] - z) * c);
-        l = fmaf(ml[2 * slot + 1], wgt, l);
-        const float* src = part + slot * DV + c0;
-        a0 += *reinterpret_cast<const f32x4*>(src) * wgt;
-        a1 += *reinterpret_cast<const f32x4*>(src + 4) * wgt;
+        const f32x2 e = *reinterpret_cast<const f32x2*>(ml + 2 * slot);
+        const float* src = part + slot * DV + 8 * cg;
+        add(e[0], e[1], *reinterpret_cast<const f32x4*>(src), *reinterpret_cast<const f32x4*>(src + 4));
     }
-    const float inv = 1.0f / l;
-    const u32x4 o = {pack_bf16(a0[0] * inv, a0[1] * inv), pack_bf16(a0[2] * inv, a0[3] * inv),
-                     pack_bf16(a1[0] * inv, a1[1] * inv), pack_bf16(a1[2] * inv, a1[3] * inv)};
-    *reinterpret_cast<u32x4*>(O + row * DV + c0) = o;
+#pragma unroll
+    for (int off = G; off < 64; off <<= 1) {
+        f32x4 b0, b1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { b0[i] = __shfl_xor(a0[i], off); b1[i] = __shfl_xor(a1[i], off); }
+        add(__shfl_xor(z, off), __shfl_xor(l, off), b0, b1);
+    }
+    if (ph == 0) {
+        const float inv = 1.0f / l;
+        const u32x4 o = {pack_bf16(a0[0] * inv, a0[1] * inv), pack_bf16(a0[2] * inv, a0[3] * inv),
+                         pack_bf16(a1[0] * inv, a1[1] * inv), pack_bf16(a1[2] * inv, a1[3] * inv)};
+        *reinterpret_cast<u32x4*>(O + row * DV + 8 * cg) = o;
+    }
 }
 
 }  // namespace bb
