@@ -71,15 +71,28 @@ typedef enum bb_status {
  *                      through a cache-resident scratch between the phases.
  * BB_VARIANT_UNFUSED   the initial block program (what the *_unfused entry points
  *                       run); a candidate of the measured selection below.
+ * BB_VARIANT_PRESCALE  (FFN, M > 16) SNAPSHOT1 with the statistics loop as a
+ *                       kernel of its own, as Example 3's first snapshot has
+ *                       it (a loop over the model dimension before the K-map):
+ *                       a row kernel writes bf16(x g) and the inverse norms,
+ *                       the dual product runs the plain main loop (no vector
+ *                       work on the A operand) and applies the inverse norm,
+ *                       Swish and the Hadamard product in its epilogue.  Same
+ *                       arithmetic as SNAPSHOT1; costs one extra pass over X
+ *                       (M D bf16 written and read).  A candidate of the
+ *                       measured selection below.
  * BB_VARIANT_AUTO      the measured selection for exactly this shape if
- *                       bb_*_tune has recorded one, else STREAM for M <= 16 and
- *                       SNAPSHOT1 otherwise.
+ *                       bb_*_tune has recorded one, else STREAM for M <= 16,
+ *                       SNAPSHOT1 up to 255 rows and PRESCALE from 256 rows on
+ *                       (the table measured on an MI355X for D = 4096,
+ *                       F = 11008).
  */
 typedef enum bb_variant {
     BB_VARIANT_AUTO = 0,
     BB_VARIANT_STREAM = 1,
     BB_VARIANT_SNAPSHOT1 = 2,
-    BB_VARIANT_UNFUSED = 3
+    BB_VARIANT_UNFUSED = 3,
+    BB_VARIANT_PRESCALE = 4
 } bb_variant;
 
 typedef enum bb_op {
@@ -150,8 +163,9 @@ int bb_layernorm_matmul(const void* X, const void* gamma, const void* beta,
  * the suffix, errors) is as for bb_rmsnorm_swiglu_ffn / bb_layernorm_matmul.
  * The contraction index is contiguous in these layouts, so the weight tiles
  * need no transposition on chip.  Every M goes through the tiled kernels (for
- * few rows with the split contraction); the streaming variant takes the
- * untransposed layout only, and bb_set_variant has no effect here.
+ * few rows with the split contraction, from 256 rows on with the statistics
+ * loop as a kernel of its own, see BB_VARIANT_PRESCALE); the streaming variant
+ * takes the untransposed layout only, and bb_set_variant has no effect here.
  */
 int bb_rmsnorm_swiglu_ffn_t(const void* X, const void* g, const void* W1t,
                             const void* W3t, const void* W2t, void* Y,
@@ -255,14 +269,14 @@ size_t bb_attention_workspace_bytes(int64_t B, int64_t M, int64_t N, int64_t d,
  *
  * bb_*_tune run every candidate program of the operator on the caller's
  * operands (same arguments as the operator): STREAM (FFN, M <= 16 only),
- * SNAPSHOT1, UNFUSED; each once untimed and then `reps` (1..1000) times between
+ * SNAPSHOT1, UNFUSED, PRESCALE (FFN, M > 16 only); each once untimed and then `reps` (1..1000) times between
  * two events on `stream`, which the call waits for.  The fastest is recorded
  * for exactly this (operator, M, D, F or N) in a process-wide table that
  * BB_VARIANT_AUTO consults, so later calls of bb_rmsnorm_swiglu_ffn /
  * bb_layernorm_matmul with that shape run it.  Y holds the result of the last
  * candidate run (all candidates compute the same operator).
  *   chosen (host, may be NULL): the recorded variant.
- *   ms (host, 4 floats, may be NULL): ms[v] = mean milliseconds of variant v,
+ *   ms (host, 5 floats, may be NULL): ms[v] = mean milliseconds of variant v,
  *     -1 where v is not a candidate; ms[0] = the fastest.
  * A candidate that does not fit a caller-provided workspace is skipped.
  * bb_set_workspace and bb_tune_clear empty the table.  bb_tuned_variant returns
@@ -295,7 +309,7 @@ int bb_tune_clear(void);
  *   keeps all-zero accumulators between calls) and stays owned by the caller.
  * bb_set_variant / bb_get_variant: process-wide choice for
  *   bb_rmsnorm_swiglu_ffn (default BB_VARIANT_AUTO, or the BB_VARIANT
- *   environment variable: "auto", "stream", "snapshot1", "unfused");
+ *   environment variable: "auto", "stream", "snapshot1", "unfused", "prescale");
  *   BB_VARIANT_UNFUSED also applies to bb_layernorm_matmul.
  * bb_shutdown: frees the library's own workspace (synchronises the device).
  */

@@ -21,6 +21,7 @@ namespace {
 using namespace bb;
 
 constexpr int64_t kStreamMaxM = 16;   // rows the weight-streaming kernel handles
+constexpr int64_t kPrescaleMinM = 256; // rows from which AUTO runs the statistics loop as a kernel of its own
 constexpr size_t kAlign = 256;
 
 std::mutex g_mu;
@@ -95,6 +96,7 @@ int read_variant() {
             if (!std::strcmp(e, "stream")) g_variant = BB_VARIANT_STREAM;
             else if (!std::strcmp(e, "snapshot1")) g_variant = BB_VARIANT_SNAPSHOT1;
             else if (!std::strcmp(e, "unfused")) g_variant = BB_VARIANT_UNFUSED;
+            else if (!std::strcmp(e, "prescale")) g_variant = BB_VARIANT_PRESCALE;
         }
     }
     return g_variant;
@@ -115,7 +117,10 @@ std::map<TuneKey, int> g_tuned;
 int auto_variant(int op, int64_t M, int64_t D, int64_t FN) {
     auto it = g_tuned.find(TuneKey{op, M, D, FN});
     if (it != g_tuned.end()) return it->second;
-    if (op == BB_OP_RMSNORM_SWIGLU_FFN) return (M <= kStreamMaxM) ? BB_VARIANT_STREAM : BB_VARIANT_SNAPSHOT1;
+    // (measured on D = 4096, F = 11008: from 256 rows on the separate statistics pass beats the
+    // statistics inside the product loop by 7-9 %; below, the split contraction needs the fused form)
+    if (op == BB_OP_RMSNORM_SWIGLU_FFN)
+        return (M <= kStreamMaxM) ? BB_VARIANT_STREAM : (M >= kPrescaleMinM ? BB_VARIANT_PRESCALE : BB_VARIANT_SNAPSHOT1);
     return BB_VARIANT_SNAPSHOT1;
 }
 
@@ -250,12 +255,12 @@ constexpr int kPlanCUs = 256;   // workgroups assumed by bb_workspace_bytes (one
 // the first case or at least 512 rows: 256-row tiles, which need fewer loads
 // per flop, with the contraction split so that every compute unit gets one.
 int plan_split(int mode, int M, int N, int K, int cus, int* nk_split, int* bm = nullptr) {
-    const int ncol = (mode == MODE_GATEUP) ? 128 : 256;
+    const int ncol = (mode == MODE_GATEUP || mode == MODE_GATEUP_PRE) ? 128 : 256;
     int tiles = ((M + 127) / 128) * ((N + ncol - 1) / ncol);
     const int nk = (K + GEMM_BK - 1) / GEMM_BK;
     *nk_split = nk;
     if (bm) *bm = 128;
-    if (mode == MODE_LN) return 1;
+    if (mode == MODE_LN || mode == MODE_GATEUP_PRE) return 1;
     const int tiles256 = ((M + 255) / 256) * ((N + ncol - 1) / ncol);
     const bool can256 = mode == MODE_PLAIN && M >= 256 && tiles256 * 2 <= cus && nk >= 64;
     // (measured on D=4096, F=11008: from 512 rows on the 256-row tiles win also where 128-row tiles could split)
@@ -300,9 +305,10 @@ size_t zone_bytes(int op, int64_t M, int64_t D, int64_t F) {
 size_t scratch_bytes(int op, int64_t M, int64_t D, int64_t F) {
     switch (op) {
         // (the FFN ops end with room for the partial results of a split contraction)
-        case BB_OP_RMSNORM_SWIGLU_FFN:
+        case BB_OP_RMSNORM_SWIGLU_FFN:      // hidden | partial results of a split | gain-scaled X and inverse norms (PRESCALE)
             return align_up((size_t)M * F * 2) +
-                   std::max(split_bytes(MODE_GATEUP, M, F, D, kPlanCUs), split_bytes(MODE_PLAIN, M, D, F, kPlanCUs));
+                   std::max(split_bytes(MODE_GATEUP, M, F, D, kPlanCUs), split_bytes(MODE_PLAIN, M, D, F, kPlanCUs)) +
+                   (M > kStreamMaxM ? align_up((size_t)M * D * 2) + align_up((size_t)M * 4) : 0);
         case BB_OP_LAYERNORM_MATMUL: return (2 + 2 * COLVEC_SPLITS) * align_up((size_t)F * 4);
         case BB_OP_RMSNORM_SWIGLU_FFN_UNFUSED:
             return align_up((size_t)M * D * 2) + 3 * align_up((size_t)M * F * 2) +
@@ -360,7 +366,7 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
     a.nsplit = 1; a.nk_split = 0; a.ldp = 0; a.part = nullptr; a.ssqpart = nullptr;
     a.A = A; a.B0 = B0; a.B1 = B1; a.C = C; a.gain = gain; a.colc = colc; a.colb = colb;
     a.M = M; a.N = N; a.K = K; a.lda = lda; a.ldb = ldb; a.ldc = ldc; a.eps = eps;
-    const int ncol = (MODE == MODE_GATEUP) ? 128 : 256;
+    const int ncol = (MODE == MODE_GATEUP || MODE == MODE_GATEUP_PRE) ? 128 : 256;
     a.tiles_n = (N + ncol - 1) / ncol;
     const int tiles256 = ((M + 255) / 256) * a.tiles_n;
     int nk_split = 0, split_bm = 128;
@@ -396,7 +402,7 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
     };
     auto go2 = [&](auto BMc, auto FULLc) { if (odd) go(BMc, FULLc, T()); else go(BMc, FULLc, F_()); };
     if (do_split) {
-        constexpr int SM = (MODE == MODE_LN) ? MODE_PLAIN : MODE;     // (LN is never split)
+        constexpr int SM = (MODE == MODE_LN || MODE == MODE_GATEUP_PRE) ? MODE_PLAIN : MODE;   // (these are never split)
         if (big) {
             // (PLAIN only) 256-row tiles; complete tiles and equal shares of the contraction run without bounds checks
             constexpr int PM = MODE_PLAIN;
@@ -420,7 +426,8 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
         if (full) go2(std::integral_constant<int, 128>(), T()); else go2(std::integral_constant<int, 128>(), F_());
     }
     BB_HIP(hipGetLastError());
-    prof_mark(MODE == MODE_GATEUP ? "gemm_gateup" : MODE == MODE_LN ? "gemm_ln" : "gemm_plain", st);
+    prof_mark(MODE == MODE_GATEUP ? "gemm_gateup" : MODE == MODE_GATEUP_PRE ? "gemm_gateup_prescaled"
+              : MODE == MODE_LN ? "gemm_ln" : "gemm_plain", st);
     return BB_OK;
 }
 
@@ -490,7 +497,7 @@ const char* bb_status_string(int s) {
 }
 
 int bb_set_variant(int v) {
-    if (v < BB_VARIANT_AUTO || v > BB_VARIANT_UNFUSED) return BB_ERR_VARIANT;
+    if (v < BB_VARIANT_AUTO || v > BB_VARIANT_PRESCALE) return BB_ERR_VARIANT;
     std::lock_guard<std::mutex> lk(g_mu);
     g_variant = v;
     return BB_OK;
@@ -558,6 +565,7 @@ int ffn_locked(int variant, const void* X, const void* g, const void* W1, const 
     if (variant == BB_VARIANT_UNFUSED && R == nullptr)
         return ffn_unfused_locked(X, g, W1, W3, W2, Y, M, D, F, eps, stream);
     if (variant == BB_VARIANT_UNFUSED) variant = BB_VARIANT_SNAPSHOT1;
+    if (variant == BB_VARIANT_PRESCALE && M <= kStreamMaxM) return BB_ERR_VARIANT;   // (no room is planned for so few rows)
     const DeviceInfo* dev = nullptr;
     if (int rc = current_device_info(&dev)) return rc;
     const size_t zone = zone_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F);
@@ -573,6 +581,21 @@ int ffn_locked(int variant, const void* X, const void* g, const void* W1, const 
     const int pcus = std::min(dev->cus, kPlanCUs);          // (the workspace was sized for this many)
     mark_dirty(zone);
     prof_begin(st);
+    if (variant == BB_VARIANT_PRESCALE) {
+        // the statistics loop as a kernel of its own: bf16(x g) and the inverse norms, then the
+        // two products with the plain main loop and the SwiGLU epilogue
+        u16* Xg = (u16*)((char*)split + std::max(split_bytes(MODE_GATEUP, M, F, D, kPlanCUs),
+                                                 split_bytes(MODE_PLAIN, M, D, F, kPlanCUs)));
+        float* rstd = (float*)((char*)Xg + align_up((size_t)M * D * 2));
+        hipLaunchKernelGGL(rms_gain_rows_kernel, dim3((unsigned)M), dim3(256), 0, st, x, gg, Xg, rstd, (int)D, eps);
+        BB_HIP(hipGetLastError());
+        prof_mark("rms_gain_rows", st);
+        if (int rc = launch_gemm<MODE_GATEUP_PRE>(Xg, (int)D, w1, w3, (int)F, H, (int)F, nullptr, rstd, nullptr,
+                                                  (int)M, (int)F, (int)D, eps, pcus, st, nullptr))
+            return rc;
+        return launch_gemm<MODE_PLAIN>(H, (int)F, w2, nullptr, (int)D, (u16*)Y, (int)D, nullptr, nullptr, nullptr,
+                                       (int)M, (int)D, (int)F, 0.f, pcus, st, split, (const u16*)R, (int)D);
+    }
     if (int rc = launch_gemm<MODE_GATEUP>(x, (int)D, w1, w3, (int)F, H, (int)F, gg, nullptr, nullptr, (int)M,
                                           (int)F, (int)D, eps, pcus, st, split))
         return rc;
@@ -592,10 +615,23 @@ int ffn_t_locked(const void* X, const void* g, const void* W1t, const void* W3t,
     const int pcus = std::min(dev->cus, kPlanCUs);
     mark_dirty(zone);
     prof_begin(st);
-    if (int rc = (launch_gemm<MODE_GATEUP, true>((const u16*)X, (int)D, (const u16*)W1t, (const u16*)W3t, (int)D, H,
-                                                 (int)F, (const u16*)g, nullptr, nullptr, (int)M, (int)F, (int)D,
-                                                 eps, pcus, st, split)))
+    if (M >= kPrescaleMinM) {         // as AUTO does for the untransposed layout: statistics loop as its own kernel
+        u16* Xg = (u16*)((char*)split + std::max(split_bytes(MODE_GATEUP, M, F, D, kPlanCUs),
+                                                 split_bytes(MODE_PLAIN, M, D, F, kPlanCUs)));
+        float* rstd = (float*)((char*)Xg + align_up((size_t)M * D * 2));
+        hipLaunchKernelGGL(rms_gain_rows_kernel, dim3((unsigned)M), dim3(256), 0, st, (const u16*)X, (const u16*)g,
+                           Xg, rstd, (int)D, eps);
+        BB_HIP(hipGetLastError());
+        prof_mark("rms_gain_rows", st);
+        if (int rc = (launch_gemm<MODE_GATEUP_PRE, true>(Xg, (int)D, (const u16*)W1t, (const u16*)W3t, (int)D, H,
+                                                         (int)F, nullptr, rstd, nullptr, (int)M, (int)F, (int)D, eps,
+                                                         pcus, st, nullptr)))
+            return rc;
+    } else if (int rc = (launch_gemm<MODE_GATEUP, true>((const u16*)X, (int)D, (const u16*)W1t, (const u16*)W3t,
+                                                        (int)D, H, (int)F, (const u16*)g, nullptr, nullptr, (int)M,
+                                                        (int)F, (int)D, eps, pcus, st, split))) {
         return rc;
+    }
     return launch_gemm<MODE_PLAIN, true>(H, (int)F, (const u16*)W2t, nullptr, (int)F, (u16*)Y, (int)D, nullptr,
                                          nullptr, nullptr, (int)M, (int)D, (int)F, 0.f, pcus, st, split,
                                          (const u16*)R, (int)D);
@@ -892,10 +928,11 @@ int tune_locked(int op, int64_t M, int64_t D, int64_t FN, int reps, hipStream_t 
     int best = 0;
     float best_ms = 0.f;
     int rc = BB_OK;
-    for (int v = BB_VARIANT_STREAM; v <= BB_VARIANT_UNFUSED && rc == BB_OK; ++v) {
+    for (int v = BB_VARIANT_STREAM; v <= BB_VARIANT_PRESCALE && rc == BB_OK; ++v) {
         if (ms_out) ms_out[v] = -1.f;
-        if (op == BB_OP_LAYERNORM_MATMUL && v == BB_VARIANT_STREAM) continue;
+        if (op == BB_OP_LAYERNORM_MATMUL && (v == BB_VARIANT_STREAM || v == BB_VARIANT_PRESCALE)) continue;
         if (v == BB_VARIANT_STREAM && M > kStreamMaxM) continue;
+        if (v == BB_VARIANT_PRESCALE && M <= kStreamMaxM) continue;
         float ms = 0.f;
         rc = time_candidate([&]() { return run(v); }, reps, st, &ms);
         if (rc == BB_ERR_WORKSPACE && g_ws.user) {      // does not fit the caller's workspace: not a candidate

@@ -13,6 +13,12 @@
 //               r (P - mu c) + b with c = gamma^T W, b = beta^T W (Rule 5, 4).
 //  MODE_PLAIN   C = A B, used for the contraction with W2 and by the unfused
 //               block programs.
+//  MODE_GATEUP_PRE  the two products, Swish and Hadamard product of MODE_GATEUP
+//               on an A operand that already carries the gain (bf16(x g),
+//               written by a row kernel together with the inverse norms):
+//               the statistics loop is a loop of its own before the K-map,
+//               as in Example 3's first snapshot, and the main loop is the
+//               plain one.
 //
 // Layouts: A [M,K] row-major, B [K,N] row-major (contraction index strided),
 // C [M,N] row-major, all bf16.  fp32 accumulation in 32x32x16 matrix
@@ -61,7 +67,7 @@
 
 namespace bb {
 
-enum { MODE_PLAIN = 0, MODE_GATEUP = 1, MODE_LN = 2 };
+enum { MODE_PLAIN = 0, MODE_GATEUP = 1, MODE_LN = 2, MODE_GATEUP_PRE = 3 };
 
 struct GemmArgs {
     const u16* A;        // [M, K]
@@ -168,7 +174,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     constexpr int WN = 4 / WM;                          // and along the columns
     constexpr int WR = BM / WM, WC = 256 / WN;          // wavefront tile
     constexpr int MT = WR / 32, NT = WC / 32;           // 32x32 subtiles per wavefront
-    constexpr int NCOL = (MODE == MODE_GATEUP) ? 128 : 256;  // output columns per tile
+    constexpr bool DUAL = MODE == MODE_GATEUP || MODE == MODE_GATEUP_PRE;   // two products per tile, SwiGLU epilogue
+    constexpr bool COOK = MODE == MODE_GATEUP || MODE == MODE_LN;           // norm prologue on the A fragments
+    constexpr int NCOL = DUAL ? 128 : 256;                   // output columns per tile
     constexpr int ADMA = BM / 32;   // A load-to-LDS instructions per wavefront and step
     // (the B arrays come first: the many transposing reads of a step then reach
     // their addresses with the 16-bit displacement of the LDS instructions)
@@ -236,7 +244,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     // Instructions 0..3 of a wavefront serve W1, 4..7 W3, row groups
     // 4 (q % 4) + w.  Subtiles tt and tt + 4 of the (single-column) wavefront
     // tile are then the gate and the up product of the same hidden units.
-    constexpr bool HALF = (MODE == MODE_GATEUP);
+    constexpr bool HALF = DUAL;
     const int rowBl = HALF ? (lane >> 4) : lhi;                  // row of this lane within an instruction
     const int chunkB = HALF ? ((lane & 15) ^ ((lane >> 4) << 2)) : (l32 ^ (((2 * w + lhi) & 3) << 2));
     const int colB = n0 + 8 * chunkB;
@@ -317,7 +325,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
                                    k0 + 8 * kcA[j & 1] < p.K && m0 + rowA + 8 * j < p.M);
             load_to_lds16(g, dA + (ADMA * w + j) * 64);
         }
-        if (MODE != MODE_PLAIN && part == 3) {
+        if (COOK && part == 3) {
             const void* g = src_of(p.gain, (size_t)k0, (u32)(8 * (lane & 7)), k0 + 8 * (lane & 7) < p.K);
             load_to_lds16(g, dG);
         }
@@ -350,7 +358,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
         const int kc = 2 * ks + lhi;
 #pragma unroll
         for (int s = 0; s < MT; ++s) fa[S][s].u = bufA[lds_pos(WR * wm + 32 * s + l32, kc)];
-        if (MODE != MODE_PLAIN) fg[S].u = bufG[kc];
+        if (COOK) fg[S].u = bufG[kc];
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt) {
             if (BT) {
@@ -369,7 +377,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     // on items [lo, hi).
     auto cook = [&](auto SETC, int lo, int hi) {
         constexpr int S = decltype(SETC)::value;
-        if (MODE == MODE_PLAIN) return;
+        if (!COOK) return;
         const u32x4 gv = fg[S].u;
 #pragma unroll
         for (int s = 0; s < MT; ++s) {
@@ -403,7 +411,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
                 acc[s][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[S][s].v, fb[S][tt].v, acc[s][tt], 0, 0, 0);
             }
     };
-    constexpr int NDSR = MT + 2 * NT + (MODE != MODE_PLAIN ? 1 : 0);   // LDS reads per fragment set
+    constexpr int NDSR = MT + 2 * NT + (COOK ? 1 : 0);   // LDS reads per fragment set
     constexpr int ITEMS = 4 * MT;                                      // prologue items per fragment set
     constexpr int P1 = (ITEMS + 2) / 3, P2 = (2 * ITEMS + 2) / 3;      // item ranges of quarters 1, 2, 3
     // Placement request for one group of matrix instructions (the instructions
@@ -413,9 +421,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     // instruction is followed by its share of the B reads (so that the four
     // wavefronts do not burst into the LDS together), a slice of the vector ALU
     // work and, every second time, one load-to-LDS.
-    constexpr int NDSR_A = MT + (MODE != MODE_PLAIN ? 1 : 0);
+    constexpr int NDSR_A = MT + (COOK ? 1 : 0);
     constexpr int DSR_PER = ((BT ? 1 : 2) * NT + NMMA - 1) / NMMA;
-    constexpr int VQ = (MODE == MODE_PLAIN) ? 2 : ((MODE == MODE_LN ? 9 : 7) * ITEMS + 8) / NMMA + 3;   // vector ALU slice per matrix instruction
+    constexpr int VQ = !COOK ? 2 : ((MODE == MODE_LN ? 9 : 7) * ITEMS + 8) / NMMA + 3;   // vector ALU slice per matrix instruction
     auto pattern = [&](bool with_frags, bool with_dma) {
         if (with_frags) __builtin_amdgcn_sched_group_barrier(0x100, NDSR_A, 0);
 #pragma unroll
@@ -533,7 +541,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
 
     // ---- split contraction: store the partial results, no epilogue
     if (SPLIT) {
-        static_assert(!SPLIT || MODE != MODE_LN, "split kernels: PLAIN or GATEUP");
+        static_assert(!SPLIT || MODE == MODE_PLAIN || MODE == MODE_GATEUP, "split kernels: PLAIN or GATEUP");
         float* const part = p.part + (size_t)split * p.M * p.ldp;
         const int eqs = l32 & 3;
 #pragma unroll
@@ -567,7 +575,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     }
 
     // ---- row statistics: add the two lanes that share a row (lane, lane ^ 32)
-    if (MODE != MODE_PLAIN) {
+    if (MODE == MODE_GATEUP_PRE) {
+        // the inverse norms were computed by the row kernel that applied the gain
+        for (int i = threadIdx.x; i < BM; i += GEMM_THREADS) stat0[i] = (m0 + i < p.M) ? p.colc[m0 + i] : 0.f;
+        __syncthreads();
+    }
+    if (COOK) {
 #pragma unroll
         for (int s = 0; s < MT; ++s) {
             const float q2 = ssq[s][0] + ssq[s][1], q1 = ssum[s][0] + ssum[s][1];
@@ -598,8 +611,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     const int eq = l32 & 3;
     const u32 tsel = (eq & 1) ? 0x03020706u : 0x05040100u;
     const bool tup = (eq & 2) != 0;
-    if (MODE == MODE_GATEUP) {
-        static_assert(MODE != MODE_GATEUP || NT == 8, "gate and up subtiles must share a wavefront");
+    if (DUAL) {
+        static_assert(!DUAL || NT == 8, "gate and up subtiles must share a wavefront");
         const int fcol = n0 + 4 * (l32 >> 2);       // + 32 u
 #pragma unroll
         for (int s = 0; s < MT; ++s) {

@@ -39,6 +39,29 @@ __global__ __launch_bounds__(256) void rmsnorm_rows_kernel(const u16* X, const u
     }
 }
 
+// The statistics loop of Example 3's first snapshot as a kernel of its own, with the gain:
+// Xg[i,:] = bf16( g * x ) and rstd[i] = rsqrt(mean(x^2) + eps); one workgroup per row, X read once.
+__global__ __launch_bounds__(256) void rms_gain_rows_kernel(const u16* X, const u16* g, u16* Xg, float* rstd, int D,
+                                                            float eps) {
+    __shared__ float red[4];
+    const size_t row = blockIdx.x;
+    const u16* x = X + row * D;
+    float s = 0.f;
+    for (int c = threadIdx.x * 8; c < D; c += 256 * 8) {
+        const u32x4 v = ldg16(x + c), gv = ldg16(g + c);
+        u32x4 o;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float a = bf_lo(v[q]), b = bf_hi(v[q]);
+            s += a * a + b * b;
+            o[q] = pack_bf16(bf_lo(gv[q]) * a, bf_hi(gv[q]) * b);
+        }
+        *reinterpret_cast<u32x4*>(Xg + row * D + c) = o;
+    }
+    s = block_sum_256(s, red);
+    if (threadIdx.x == 0) rstd[row] = rsqrtf(s / (float)D + eps);
+}
+
 // Z[i,:] = bf16( gamma * (x - mean) * rsqrt(var + eps) + beta ), biased variance, two passes.
 __global__ __launch_bounds__(256) void layernorm_rows_kernel(const u16* X, const u16* gamma, const u16* beta,
                                                              u16* Z, int D, float eps) {

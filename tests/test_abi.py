@@ -153,9 +153,11 @@ def test_variant_and_workspace_queries(lib):
     assert bb.bb_get_variant() in (0, 1, 2)
     old = bb.bb_get_variant()
     with pytest.raises(bb.BBError):
-        bb.bb_set_variant(7)
+        bb.bb_set_variant(5)
     bb.bb_set_variant(bb.VARIANT_UNFUSED)
     assert bb.bb_get_variant() == bb.VARIANT_UNFUSED
+    bb.bb_set_variant(bb.VARIANT_PRESCALE)
+    assert bb.bb_get_variant() == bb.VARIANT_PRESCALE
     bb.bb_set_variant(bb.VARIANT_SNAPSHOT1)
     assert bb.bb_get_variant() == bb.VARIANT_SNAPSHOT1
     bb.bb_set_variant(old)

@@ -280,7 +280,7 @@ def test_tune_records_fastest_candidate_and_auto_follows():
     M, D, F = 96, 512, 1408
     assert bb.bb_tuned_variant(bb.OP_FFN, M, D, F) == bb.VARIANT_AUTO
     chosen, ms = bb.bb_rmsnorm_swiglu_ffn_tune(*d, 1e-6, reps=3)
-    assert set(ms) == {bb.VARIANT_SNAPSHOT1, bb.VARIANT_UNFUSED}          # STREAM is no candidate above 16 rows
+    assert set(ms) == {bb.VARIANT_SNAPSHOT1, bb.VARIANT_UNFUSED, bb.VARIANT_PRESCALE}   # STREAM is no candidate above 16 rows
     assert chosen == min(ms, key=ms.get) and all(v > 0 for v in ms.values())
     assert bb.bb_tuned_variant(bb.OP_FFN, M, D, F) == chosen
     assert bb.bb_tuned_variant(bb.OP_FFN, M + 1, D, F) == bb.VARIANT_AUTO  # exact shapes only
@@ -290,6 +290,7 @@ def test_tune_records_fastest_candidate_and_auto_follows():
     names = [k for k, _ in bb.bb_profile_last()]
     bb.bb_profile_enable(False)
     assert ("rmsnorm_rows" in names) == (chosen == bb.VARIANT_UNFUSED)
+    assert ("rms_gain_rows" in names) == (chosen == bb.VARIANT_PRESCALE)
     ref = orc.rmsnorm_swiglu_ffn(*cpu, 1e-6)
     assert row_rel_err(Y, ref) <= TOL
     bb.bb_tune_clear()
@@ -392,3 +393,32 @@ def test_split_contraction_256_row_tiles(M, D, F):
     assert row_rel_err(Yt[rows], ref) <= TOL
     Yr = bb.bb_rmsnorm_swiglu_ffn_residual(*d, d[0], 1e-6)
     assert row_rel_err(Yr[rows], ref + X[rows].double().numpy()) <= TOL
+
+
+# ---------------------------------------------------------------- statistics loop as its own kernel
+@pytest.mark.parametrize("M,D,F", [(17, 72, 136), (130, 264, 712), (300, 520, 1032), (512, 1024, 2816),
+                                   (2048, 1024, 2816)])
+def test_prescale_variant(M, D, F):
+    cpu = bb_inputs.make_ffn(M, D, F, seed=M + 1)
+    err = ffn_case(cpu, 1e-6, variant=bb.VARIANT_PRESCALE)
+    assert err <= TOL
+    # same arithmetic as the fused prologue: bf16(x g) operands, inverse norm after the dots
+    bb.bb_set_variant(bb.VARIANT_PRESCALE)
+    try:
+        Y1 = bb.bb_rmsnorm_swiglu_ffn(*dev(cpu), 1e-6)
+    finally:
+        bb.bb_set_variant(bb.VARIANT_AUTO)
+    Y2 = bb.bb_rmsnorm_swiglu_ffn(*dev(cpu), 1e-6)
+    diff = (Y1.float() - Y2.float()).abs().max().item()
+    assert diff <= 2e-2 * Y2.float().abs().max().item()
+
+
+def test_prescale_variant_refused_for_few_rows():
+    cpu = bb_inputs.make_ffn(8, 256, 704, seed=2)
+    bb.bb_set_variant(bb.VARIANT_PRESCALE)
+    try:
+        with pytest.raises(bb.BBError) as e:
+            bb.bb_rmsnorm_swiglu_ffn(*dev(cpu), 1e-6)
+        assert e.value.status == -9
+    finally:
+        bb.bb_set_variant(bb.VARIANT_AUTO)
