@@ -26,9 +26,11 @@
 //
 // Tiling: 256 threads = 4 wavefronts, workgroup tile BM x 256 columns (GATEUP:
 // 128 hidden units = 128 columns of W1 + the same 128 of W3), contraction step
-// 64, LDS double buffered with one barrier per step.  PLAIN arranges the
-// wavefronts 2x2 (least LDS read traffic); GATEUP and LN arrange them 4x1, so
-// that every wavefront owns its rows of A alone (see "A operand").
+// 64, LDS double buffered with one barrier per step.  PLAIN and GATEUP_PRE
+// arrange the wavefronts 2x2 (least LDS read traffic; in GATEUP_PRE a
+// wavefront takes 64 columns of W1 and the same 64 of W3); GATEUP and LN
+// arrange them 4x1, so that every wavefront owns its rows of A alone (see
+// "A operand").
 //
 // Both operand tiles go from global memory straight into LDS with load-to-LDS
 // instructions: no staging registers, no vector ALU work, no LDS writes.
@@ -170,7 +172,8 @@ __device__ __forceinline__ void quad_transpose_f32(float (&y)[4], bool upper, bo
 // swizzle, same load-to-LDS role) and its fragments are plain 128-bit reads.
 template <int MODE, int BM, bool FULL, bool ODD, bool SPLIT = false, bool BT = false>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
-    constexpr int WM = (MODE == MODE_PLAIN) ? 2 : 4;   // wavefronts along the rows
+    // (2 x 2 wherever the A fragments need no prologue: least LDS read traffic)
+    constexpr int WM = (MODE == MODE_PLAIN || MODE == MODE_GATEUP_PRE) ? 2 : 4;   // wavefronts along the rows
     constexpr int WN = 4 / WM;                          // and along the columns
     constexpr int WR = BM / WM, WC = 256 / WN;          // wavefront tile
     constexpr int MT = WR / 32, NT = WC / 32;           // 32x32 subtiles per wavefront
@@ -245,6 +248,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     // 4 (q % 4) + w.  Subtiles tt and tt + 4 of the (single-column) wavefront
     // tile are then the gate and the up product of the same hidden units.
     constexpr bool HALF = DUAL;
+    // HALF: a wavefront's subtiles 0 .. HT-1 are its columns of W1, HT .. NT-1 the same columns of W3
+    // (columns (128 / WN) wn + 32 (tt % HT) + ... of either half tile)
+    constexpr int HT = HALF ? NT / 2 : 4;
+    constexpr int HWC = 128 / WN;                                // a wavefront's columns within a half tile
     const int rowBl = HALF ? (lane >> 4) : lhi;                  // row of this lane within an instruction
     const int chunkB = HALF ? ((lane & 15) ^ ((lane >> 4) << 2)) : (l32 ^ (((2 * w + lhi) & 3) << 2));
     const int colB = n0 + 8 * chunkB;
@@ -280,7 +287,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
         const int piece = ip & 3;
 #pragma unroll
         for (int o = 0; o < 4; ++o) {
-            const int chunk = (HALF ? 0 : (WC / 8) * wn) + 4 * o + 2 * (b & 1) + (piece >> 1);
+            const int chunk = (HALF ? (HWC / 8) * wn : (WC / 8) * wn) + 4 * o + 2 * (b & 1) + (piece >> 1);
             offB[o] = r * BROW + ((chunk ^ ((r & 3) << 2)) << 4) + 8 * (piece & 1);
         }
     }
@@ -362,9 +369,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt) {
             if (BT) {
-                fb[S][tt].u = (PB ? sB1 : sB0)[lds_pos((HALF ? 0 : WC * wn) + 32 * tt + l32, kc)];
+                fb[S][tt].u = (PB ? sB1 : sB0)[lds_pos(
+                    (HALF ? 128 * (tt / HT) + HWC * wn + 32 * (tt % HT) : WC * wn + 32 * tt) + l32, kc)];
             } else {
-                const char* q = reinterpret_cast<const char*>(PB ? sB1 : sB0) + offB[tt & 3] + ks * (16 * BROW) + BTT4 * (tt >> 2);
+                const char* q = reinterpret_cast<const char*>(PB ? sB1 : sB0) + offB[tt % HT] + ks * (16 * BROW) + BTT4 * (tt / HT);
                 const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(q));
                 const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(q + 4 * BROW));
                 u32x2 l2 = *reinterpret_cast<const u32x2*>(&lo), h2 = *reinterpret_cast<const u32x2*>(&hi);
@@ -551,8 +559,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
                 // GATEUP: subtiles 0..3 are the W1 product of hidden units n0 + 32 tt + ..., 4..7 the W3 product.
                 // Four registers (4 rows x this lane's column) are transposed within the quad: the lane then
                 // holds 4 consecutive columns of one row, a 16-byte store.
-                const int col = ((MODE == MODE_GATEUP) ? n0 + 32 * (tt & 3) : n0 + WC * wn + 32 * tt) + 4 * (l32 >> 2);
-                const int pcol = (MODE == MODE_GATEUP && tt >= 4) ? p.N + col : col;
+                const int col = (DUAL ? n0 + HWC * wn + 32 * (tt % HT) : n0 + WC * wn + 32 * tt) + 4 * (l32 >> 2);
+                const int pcol = (DUAL && tt >= HT) ? p.N + col : col;
 #pragma unroll
                 for (int vg = 0; vg < 4; ++vg) {
                     float y[4] = {acc[s][tt][4 * vg], acc[s][tt][4 * vg + 1], acc[s][tt][4 * vg + 2], acc[s][tt][4 * vg + 3]};
@@ -612,8 +620,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     const u32 tsel = (eq & 1) ? 0x03020706u : 0x05040100u;
     const bool tup = (eq & 2) != 0;
     if (DUAL) {
-        static_assert(!DUAL || NT == 8, "gate and up subtiles must share a wavefront");
-        const int fcol = n0 + 4 * (l32 >> 2);       // + 32 u
+        static_assert(!DUAL || NT % 2 == 0, "gate and up subtiles must share a wavefront");
+        const int fcol = n0 + HWC * wn + 4 * (l32 >> 2);       // + 32 u
 #pragma unroll
         for (int s = 0; s < MT; ++s) {
 #pragma unroll
