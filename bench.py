@@ -35,7 +35,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
 MEASURED_TRAFFIC_BYTES = {
     ("c2", "ffn_stream"): 281.2e6 + 16.2e6,
     ("c3", "gemm_gateup"): 621.5e6 + 45.2e6,
-    ("c3", "gemm_gateup_prescaled"): None,
+    ("c3", "gemm_gateup_prescaled"): 624.2e6 + 45.1e6,
     ("attention", "attention"): 100.9e6 + 33.6e6,
 }
 
