@@ -114,7 +114,7 @@ def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
     ms_unfused, _ = timed(True)
     # the program with the statistics inside the product loop (nothing but the hidden materialised)
     ms_snapshot1 = None
-    if cfg.op == "ffn" and not stream_variant:
+    if not stream_variant:
         bb.bb_set_variant(bb.VARIANT_SNAPSHOT1)
         try:
             ms_snapshot1, _ = timed(False)
@@ -161,8 +161,8 @@ def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
         ms_residual = e0.elapsed_time(e1) / steps
 
     dom, work, bound = dominant_kernel(cfg, stream_variant)
-    if dom == "gemm_gateup" and "gemm_gateup_prescaled" in kernels_ms:
-        dom = "gemm_gateup_prescaled"        # AUTO ran the statistics loop as a kernel of its own
+    if dom + "_prescaled" in kernels_ms:
+        dom = dom + "_prescaled"             # AUTO ran the statistics loop as a kernel of its own
     dom_ms = kernels_ms[dom]
     if bound == "mfma":
         achieved, peak, unit = work / (dom_ms * 1e-3) / 1e12, PEAK_BF16_TFLOPS, "TFLOP/s"
@@ -171,7 +171,7 @@ def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
     res = {
         "workload": name, "op": cfg.op, "M": cfg.M, "D": cfg.D, "F_or_N": cfg.F,
         "variant": "stream" if stream_variant else (
-            ("prescale" if dom == "gemm_gateup_prescaled" else "snapshot1") if cfg.op == "ffn" else "fused_ln"),
+            "prescale" if dom.endswith("_prescaled") else "snapshot1"),
         "ms_per_step": ms_step, "ms_per_step_events": ms_step_events,
         "tflops": flops_of(cfg) / (ms_step * 1e-3) / 1e12,
         "gbs": bytes_of(cfg) / (ms_step * 1e-3) / 1e9,

@@ -71,7 +71,7 @@ typedef enum bb_status {
  *                      through a cache-resident scratch between the phases.
  * BB_VARIANT_UNFUSED   the initial block program (what the *_unfused entry points
  *                       run); a candidate of the measured selection below.
- * BB_VARIANT_PRESCALE  (FFN, M > 16) SNAPSHOT1 with the statistics loop as a
+ * BB_VARIANT_PRESCALE  (FFN with M > 16; LN -> matmul) SNAPSHOT1 with the statistics loop as a
  *                       kernel of its own, as Example 3's first snapshot has
  *                       it (a loop over the model dimension before the K-map):
  *                       a row kernel writes bf16(x g) and the inverse norms,
@@ -79,13 +79,17 @@ typedef enum bb_status {
  *                       work on the A operand) and applies the inverse norm,
  *                       Swish and the Hadamard product in its epilogue.  Same
  *                       arithmetic as SNAPSHOT1; costs one extra pass over X
- *                       (M D bf16 written and read).  A candidate of the
- *                       measured selection below.
+ *                       (M D bf16 written and read).  For LN -> matmul the row
+ *                       kernel writes bf16(x gamma), the means and the inverse
+ *                       standard deviations (two passes over the row), the
+ *                       product keeps the epilogue r (P - mu c) + b.  A
+ *                       candidate of the measured selection below.
  * BB_VARIANT_AUTO      the measured selection for exactly this shape if
  *                       bb_*_tune has recorded one, else STREAM for M <= 16,
  *                       SNAPSHOT1 up to 255 rows and PRESCALE from 256 rows on
  *                       (the table measured on an MI355X for D = 4096,
- *                       F = 11008).
+ *                       F = 11008); LN -> matmul: SNAPSHOT1 up to 255 rows,
+ *                       PRESCALE from 256 on.
  */
 typedef enum bb_variant {
     BB_VARIANT_AUTO = 0,
@@ -269,7 +273,7 @@ size_t bb_attention_workspace_bytes(int64_t B, int64_t M, int64_t N, int64_t d,
  *
  * bb_*_tune run every candidate program of the operator on the caller's
  * operands (same arguments as the operator): STREAM (FFN, M <= 16 only),
- * SNAPSHOT1, UNFUSED, PRESCALE (FFN, M > 16 only); each once untimed and then `reps` (1..1000) times between
+ * SNAPSHOT1, UNFUSED, PRESCALE (for the FFN M > 16 only); each once untimed and then `reps` (1..1000) times between
  * two events on `stream`, which the call waits for.  The fastest is recorded
  * for exactly this (operator, M, D, F or N) in a process-wide table that
  * BB_VARIANT_AUTO consults, so later calls of bb_rmsnorm_swiglu_ffn /
@@ -299,7 +303,7 @@ int bb_tune_clear(void);
  *
  * bb_workspace_bytes: bytes of device scratch `op` needs for the given sizes
  *   (third size is F for the FFN ops, N for the LN ops); the maximum over
- *   STREAM and SNAPSHOT1.  The UNFUSED candidate needs
+ *   STREAM, SNAPSHOT1 and PRESCALE.  The UNFUSED candidate needs
  *   bb_workspace_bytes(BB_OP_*_UNFUSED, ...): a caller who provides the
  *   workspace and wants it considered by bb_*_tune sizes for the larger of the
  *   two.  Returns 0 for invalid sizes.

@@ -121,7 +121,7 @@ int auto_variant(int op, int64_t M, int64_t D, int64_t FN) {
     // statistics inside the product loop by 7-9 %; below, the split contraction needs the fused form)
     if (op == BB_OP_RMSNORM_SWIGLU_FFN)
         return (M <= kStreamMaxM) ? BB_VARIANT_STREAM : (M >= kPrescaleMinM ? BB_VARIANT_PRESCALE : BB_VARIANT_SNAPSHOT1);
-    return BB_VARIANT_SNAPSHOT1;
+    return M >= kPrescaleMinM ? BB_VARIANT_PRESCALE : BB_VARIANT_SNAPSHOT1;
 }
 
 int ffn_locked(int variant, const void* X, const void* g, const void* W1, const void* W3, const void* W2,
@@ -260,7 +260,7 @@ int plan_split(int mode, int M, int N, int K, int cus, int* nk_split, int* bm = 
     const int nk = (K + GEMM_BK - 1) / GEMM_BK;
     *nk_split = nk;
     if (bm) *bm = 128;
-    if (mode == MODE_LN || mode == MODE_GATEUP_PRE) return 1;
+    if (mode == MODE_LN || mode == MODE_GATEUP_PRE || mode == MODE_LN_PRE) return 1;
     const int tiles256 = ((M + 255) / 256) * ((N + ncol - 1) / ncol);
     const bool can256 = mode == MODE_PLAIN && M >= 256 && tiles256 * 2 <= cus && nk >= 64;
     // (measured on D=4096, F=11008: from 512 rows on the 256-row tiles win also where 128-row tiles could split)
@@ -309,7 +309,9 @@ size_t scratch_bytes(int op, int64_t M, int64_t D, int64_t F) {
             return align_up((size_t)M * F * 2) +
                    std::max(split_bytes(MODE_GATEUP, M, F, D, kPlanCUs), split_bytes(MODE_PLAIN, M, D, F, kPlanCUs)) +
                    (M > kStreamMaxM ? align_up((size_t)M * D * 2) + align_up((size_t)M * 4) : 0);
-        case BB_OP_LAYERNORM_MATMUL: return (2 + 2 * COLVEC_SPLITS) * align_up((size_t)F * 4);
+        case BB_OP_LAYERNORM_MATMUL:        // column vectors and their partial sums | gamma-scaled X and row statistics (PRESCALE)
+            return (2 + 2 * COLVEC_SPLITS) * align_up((size_t)F * 4) + align_up((size_t)M * D * 2) +
+                   align_up((size_t)M * 8);
         case BB_OP_RMSNORM_SWIGLU_FFN_UNFUSED:
             return align_up((size_t)M * D * 2) + 3 * align_up((size_t)M * F * 2) +
                    std::max(split_bytes(MODE_PLAIN, M, F, D, kPlanCUs), split_bytes(MODE_PLAIN, M, D, F, kPlanCUs));
@@ -360,9 +362,10 @@ void mark_dirty(size_t off) {
 template <int MODE, bool BT = false>
 int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u16* C, int ldc,
                 const u16* gain, const float* colc, const float* colb, int M, int N, int K, float eps,
-                int cus, hipStream_t st, void* split = nullptr, const u16* res = nullptr, int ldr = 0) {
+                int cus, hipStream_t st, void* split = nullptr, const u16* res = nullptr, int ldr = 0,
+                const float* rowstat = nullptr) {
     GemmArgs a;
-    a.res = res; a.ldr = ldr;
+    a.res = res; a.ldr = ldr; a.rowstat = rowstat;
     a.nsplit = 1; a.nk_split = 0; a.ldp = 0; a.part = nullptr; a.ssqpart = nullptr;
     a.A = A; a.B0 = B0; a.B1 = B1; a.C = C; a.gain = gain; a.colc = colc; a.colb = colb;
     a.M = M; a.N = N; a.K = K; a.lda = lda; a.ldb = ldb; a.ldc = ldc; a.eps = eps;
@@ -402,7 +405,7 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
     };
     auto go2 = [&](auto BMc, auto FULLc) { if (odd) go(BMc, FULLc, T()); else go(BMc, FULLc, F_()); };
     if (do_split) {
-        constexpr int SM = (MODE == MODE_LN || MODE == MODE_GATEUP_PRE) ? MODE_PLAIN : MODE;   // (these are never split)
+        constexpr int SM = (MODE == MODE_PLAIN || MODE == MODE_GATEUP) ? MODE : MODE_PLAIN;   // (the others are never split)
         if (big) {
             // (PLAIN only) 256-row tiles; complete tiles and equal shares of the contraction run without bounds checks
             constexpr int PM = MODE_PLAIN;
@@ -427,7 +430,7 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
     }
     BB_HIP(hipGetLastError());
     prof_mark(MODE == MODE_GATEUP ? "gemm_gateup" : MODE == MODE_GATEUP_PRE ? "gemm_gateup_prescaled"
-              : MODE == MODE_LN ? "gemm_ln" : "gemm_plain", st);
+              : MODE == MODE_LN ? "gemm_ln" : MODE == MODE_LN_PRE ? "gemm_ln_prescaled" : "gemm_plain", st);
     return BB_OK;
 }
 
@@ -656,6 +659,18 @@ int ln_locked(int variant, const void* X, const void* gamma, const void* beta, c
                        (int)N);
     BB_HIP(hipGetLastError());
     prof_mark("colvec", st);
+    if (variant == BB_VARIANT_PRESCALE) {
+        // the statistics loop as a kernel of its own: bf16(x gamma), inverse standard deviations and
+        // means; the product runs the plain main loop and keeps the epilogue r (P - mu c) + b
+        u16* Xg = (u16*)((char*)g_ws.ptr + (2 + 2 * COLVEC_SPLITS) * align_up((size_t)N * 4));
+        float* stat = (float*)((char*)Xg + align_up((size_t)M * D * 2));
+        hipLaunchKernelGGL(ln_gain_rows_kernel, dim3((unsigned)M), dim3(256), 0, st, (const u16*)X,
+                           (const u16*)gamma, Xg, stat, (int)D, eps);
+        BB_HIP(hipGetLastError());
+        prof_mark("ln_gain_rows", st);
+        return launch_gemm<MODE_LN_PRE>(Xg, (int)D, (const u16*)W, nullptr, (int)N, (u16*)Y, (int)N, nullptr, colc,
+                                        colb, (int)M, (int)N, (int)D, eps, dev->cus, st, nullptr, nullptr, 0, stat);
+    }
     return launch_gemm<MODE_LN>((const u16*)X, (int)D, (const u16*)W, nullptr, (int)N, (u16*)Y, (int)N,
                                 (const u16*)gamma, colc, colb, (int)M, (int)N, (int)D, eps, dev->cus, st);
 }
@@ -670,7 +685,7 @@ int bb_layernorm_matmul(const void* X, const void* gamma, const void* beta, cons
     if (M == 0) return BB_OK;
     std::lock_guard<std::mutex> lk(g_mu);
     int variant = read_variant();
-    if (variant != BB_VARIANT_UNFUSED) variant = auto_variant(BB_OP_LAYERNORM_MATMUL, M, D, N);
+    if (variant == BB_VARIANT_AUTO || variant == BB_VARIANT_STREAM) variant = auto_variant(BB_OP_LAYERNORM_MATMUL, M, D, N);
     return ln_locked(variant, X, gamma, beta, W, Y, M, D, N, eps, stream);
 }
 
@@ -720,6 +735,17 @@ int bb_layernorm_matmul_t(const void* X, const void* gamma, const void* beta, co
                        (const u16*)gamma, (const u16*)beta, colc, colb, (int)D, (int)N);
     BB_HIP(hipGetLastError());
     prof_mark("colvec", st);
+    if (M >= kPrescaleMinM) {         // as AUTO does for the untransposed layout
+        u16* Xg = (u16*)((char*)g_ws.ptr + (2 + 2 * COLVEC_SPLITS) * align_up((size_t)N * 4));
+        float* stat = (float*)((char*)Xg + align_up((size_t)M * D * 2));
+        hipLaunchKernelGGL(ln_gain_rows_kernel, dim3((unsigned)M), dim3(256), 0, st, (const u16*)X,
+                           (const u16*)gamma, Xg, stat, (int)D, eps);
+        BB_HIP(hipGetLastError());
+        prof_mark("ln_gain_rows", st);
+        return launch_gemm<MODE_LN_PRE, true>(Xg, (int)D, (const u16*)Wt, nullptr, (int)D, (u16*)Y, (int)N, nullptr,
+                                              colc, colb, (int)M, (int)N, (int)D, eps, dev->cus, st, nullptr, nullptr,
+                                              0, stat);
+    }
     return launch_gemm<MODE_LN, true>((const u16*)X, (int)D, (const u16*)Wt, nullptr, (int)D, (u16*)Y, (int)N,
                                       (const u16*)gamma, colc, colb, (int)M, (int)N, (int)D, eps, dev->cus, st);
 }
@@ -930,9 +956,9 @@ int tune_locked(int op, int64_t M, int64_t D, int64_t FN, int reps, hipStream_t 
     int rc = BB_OK;
     for (int v = BB_VARIANT_STREAM; v <= BB_VARIANT_PRESCALE && rc == BB_OK; ++v) {
         if (ms_out) ms_out[v] = -1.f;
-        if (op == BB_OP_LAYERNORM_MATMUL && (v == BB_VARIANT_STREAM || v == BB_VARIANT_PRESCALE)) continue;
+        if (op == BB_OP_LAYERNORM_MATMUL && v == BB_VARIANT_STREAM) continue;
         if (v == BB_VARIANT_STREAM && M > kStreamMaxM) continue;
-        if (v == BB_VARIANT_PRESCALE && M <= kStreamMaxM) continue;
+        if (op == BB_OP_RMSNORM_SWIGLU_FFN && v == BB_VARIANT_PRESCALE && M <= kStreamMaxM) continue;
         float ms = 0.f;
         rc = time_candidate([&]() { return run(v); }, reps, st, &ms);
         if (rc == BB_ERR_WORKSPACE && g_ws.user) {      // does not fit the caller's workspace: not a candidate

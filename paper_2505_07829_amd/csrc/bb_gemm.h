@@ -19,6 +19,10 @@
 //               the statistics loop is a loop of its own before the K-map,
 //               as in Example 3's first snapshot, and the main loop is the
 //               plain one.
+//  MODE_LN_PRE  MODE_LN's product and epilogue on an A operand that already
+//               carries gamma (bf16(x gamma)), with means and inverse standard
+//               deviations from the row kernel that wrote it (Example 2's
+//               first snapshot: statistics loop, then the N-map).
 //
 // Layouts: A [M,K] row-major, B [K,N] row-major (contraction index strided),
 // C [M,N] row-major, all bf16.  fp32 accumulation in 32x32x16 matrix
@@ -69,7 +73,7 @@
 
 namespace bb {
 
-enum { MODE_PLAIN = 0, MODE_GATEUP = 1, MODE_LN = 2, MODE_GATEUP_PRE = 3 };
+enum { MODE_PLAIN = 0, MODE_GATEUP = 1, MODE_LN = 2, MODE_GATEUP_PRE = 3, MODE_LN_PRE = 4 };
 
 struct GemmArgs {
     const u16* A;        // [M, K]
@@ -90,6 +94,7 @@ struct GemmArgs {
     int nsplit, nk_split, ldp;
     float* part;
     float* ssqpart;
+    const float* rowstat;   // LN_PRE: [M][2] inverse standard deviation and mean per row
     const u16* res;     // PLAIN: residual added to the product before the one rounding ([M, N], row length ldr), or null
     int ldr;
 };
@@ -173,12 +178,13 @@ __device__ __forceinline__ void quad_transpose_f32(float (&y)[4], bool upper, bo
 template <int MODE, int BM, bool FULL, bool ODD, bool SPLIT = false, bool BT = false>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     // (2 x 2 wherever the A fragments need no prologue: least LDS read traffic)
-    constexpr int WM = (MODE == MODE_PLAIN || MODE == MODE_GATEUP_PRE) ? 2 : 4;   // wavefronts along the rows
+    constexpr int WM = (MODE == MODE_PLAIN || MODE == MODE_GATEUP_PRE || MODE == MODE_LN_PRE) ? 2 : 4;   // wavefronts along the rows
     constexpr int WN = 4 / WM;                          // and along the columns
     constexpr int WR = BM / WM, WC = 256 / WN;          // wavefront tile
     constexpr int MT = WR / 32, NT = WC / 32;           // 32x32 subtiles per wavefront
     constexpr bool DUAL = MODE == MODE_GATEUP || MODE == MODE_GATEUP_PRE;   // two products per tile, SwiGLU epilogue
     constexpr bool COOK = MODE == MODE_GATEUP || MODE == MODE_LN;           // norm prologue on the A fragments
+    constexpr bool LNE = MODE == MODE_LN || MODE == MODE_LN_PRE;            // epilogue r (P - mu c) + b
     constexpr int NCOL = DUAL ? 128 : 256;                   // output columns per tile
     constexpr int ADMA = BM / 32;   // A load-to-LDS instructions per wavefront and step
     // (the B arrays come first: the many transposing reads of a step then reach
@@ -588,6 +594,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
         for (int i = threadIdx.x; i < BM; i += GEMM_THREADS) stat0[i] = (m0 + i < p.M) ? p.colc[m0 + i] : 0.f;
         __syncthreads();
     }
+    if (MODE == MODE_LN_PRE) {
+        // row statistics from the row kernel: rowstat[2 m] = inverse standard deviation, [2 m + 1] = mean
+        for (int i = threadIdx.x; i < BM; i += GEMM_THREADS) {
+            const bool ok = m0 + i < p.M;
+            stat0[i] = ok ? p.rowstat[2 * (size_t)(m0 + i)] : 0.f;
+            stat1[i] = ok ? p.rowstat[2 * (size_t)(m0 + i) + 1] : 0.f;
+        }
+        __syncthreads();
+    }
     if (COOK) {
 #pragma unroll
         for (int s = 0; s < MT; ++s) {
@@ -650,7 +665,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
         const int ncol = n0 + WC * wn + l32;                 // + 32 tt: the column this lane accumulated
         const int scol = n0 + WC * wn + 4 * (l32 >> 2);      // + 32 tt: first of the 4 columns it stores
         float cc[NT], cb[NT];
-        if (MODE == MODE_LN) {
+        if (LNE) {
 #pragma unroll
             for (int tt = 0; tt < NT; ++tt) {
                 const bool ok = FULL || ncol + 32 * tt < p.N;
@@ -664,7 +679,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
             for (int vg = 0; vg < 4; ++vg) {
                 const int rl = WR * wm + 32 * s + 8 * vg + 4 * lhi;
                 float r[4], mu[4];
-                if (MODE == MODE_LN) {
+                if (LNE) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) { r[i] = stat0[rl + i]; mu[i] = stat1[rl + i]; }
                 }
@@ -674,7 +689,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         y[i] = acc[s][tt][4 * vg + i];
-                        if (MODE == MODE_LN) y[i] = fmaf(r[i], y[i] - mu[i] * cc[tt], cb[tt]);
+                        if (LNE) y[i] = fmaf(r[i], y[i] - mu[i] * cc[tt], cb[tt]);
                     }
                     const int m = m0 + rl + eq, col = scol + 32 * tt;
                     const bool inside = (FULL || m < p.M) && (FULL || col < p.N);

@@ -96,6 +96,43 @@ __global__ __launch_bounds__(256) void layernorm_rows_kernel(const u16* X, const
     }
 }
 
+// The statistics loop of Example 2's first snapshot as a kernel of its own, with gamma:
+// Xg[i,:] = bf16( gamma * x ), stat[i] = (rsqrt(var + eps), mean), biased variance, two passes;
+// one workgroup per row.
+__global__ __launch_bounds__(256) void ln_gain_rows_kernel(const u16* X, const u16* gamma, u16* Xg, float* stat,
+                                                           int D, float eps) {
+    __shared__ float red[4];
+    const size_t row = blockIdx.x;
+    const u16* x = X + row * D;
+    float s = 0.f;
+    for (int c = threadIdx.x * 8; c < D; c += 256 * 8) {
+        const u32x4 v = ldg16(x + c), gv = ldg16(gamma + c);
+        u32x4 o;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float a = bf_lo(v[q]), b = bf_hi(v[q]);
+            s += a + b;
+            o[q] = pack_bf16(bf_lo(gv[q]) * a, bf_hi(gv[q]) * b);
+        }
+        *reinterpret_cast<u32x4*>(Xg + row * D + c) = o;
+    }
+    const float mu = block_sum_256(s, red) / (float)D;
+    float s2 = 0.f;
+    for (int c = threadIdx.x * 8; c < D; c += 256 * 8) {
+        const u32x4 v = ldg16(x + c);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float a = bf_lo(v[q]) - mu, b = bf_hi(v[q]) - mu;
+            s2 += a * a + b * b;
+        }
+    }
+    s2 = block_sum_256(s2, red);
+    if (threadIdx.x == 0) {
+        stat[2 * row] = rsqrtf(s2 / (float)D + eps);
+        stat[2 * row + 1] = mu;
+    }
+}
+
 // H = bf16( SiLU(P) * Q ), elementwise over n8 groups of 8 bf16.
 __global__ __launch_bounds__(256) void silu_mul_kernel(const u16* P, const u16* Q, u16* H, size_t n8) {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {

@@ -312,7 +312,7 @@ def test_tune_layernorm_and_forced_unfused_variant():
     cpu = bb_inputs.make_ln(200, 512, 768, seed=6)
     ref = orc.layernorm_matmul(*cpu, 1e-5)
     chosen, ms = bb.bb_layernorm_matmul_tune(*dev(cpu), 1e-5, reps=3)
-    assert set(ms) == {bb.VARIANT_SNAPSHOT1, bb.VARIANT_UNFUSED} and chosen in ms
+    assert set(ms) == {bb.VARIANT_SNAPSHOT1, bb.VARIANT_UNFUSED, bb.VARIANT_PRESCALE} and chosen in ms
     assert row_rel_err(bb.bb_layernorm_matmul(*dev(cpu), 1e-5), ref) <= TOL
     bb.bb_tune_clear()
     # the unfused program through the main entry points when forced
@@ -422,3 +422,20 @@ def test_prescale_variant_refused_for_few_rows():
         assert e.value.status == -9
     finally:
         bb.bb_set_variant(bb.VARIANT_AUTO)
+
+
+@pytest.mark.parametrize("M,D,N", [(5, 72, 136), (200, 512, 768), (257, 264, 520), (1024, 1024, 2048)])
+@pytest.mark.parametrize("variant", [bb.VARIANT_PRESCALE, bb.VARIANT_SNAPSHOT1])
+def test_layernorm_variants(M, D, N, variant):
+    # statistics by a row kernel (PRESCALE, what AUTO runs from 256 rows on) and inside the product
+    # loop (SNAPSHOT1), untransposed and transposed weights
+    cpu = bb_inputs.make_ln(M, D, N, seed=M + N)
+    ref = orc.layernorm_matmul(*cpu, 1e-5)
+    bb.bb_set_variant(variant)
+    try:
+        Y = bb.bb_layernorm_matmul(*dev(cpu), 1e-5)
+    finally:
+        bb.bb_set_variant(bb.VARIANT_AUTO)
+    assert row_rel_err(Y, ref) <= TOL
+    X, ga, be, W = dev(cpu)
+    assert row_rel_err(bb.bb_layernorm_matmul_t(X, ga, be, W.t().contiguous(), 1e-5), ref) <= TOL
