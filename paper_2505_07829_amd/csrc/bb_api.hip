@@ -15,6 +15,7 @@
 #include "bb_gemm.h"
 #include "bb_misc.h"
 #include "bb_stream.h"
+#include "bb_stream_t.h"
 
 namespace {
 
@@ -216,12 +217,13 @@ int validate_ln(const void* X, const void* gamma, const void* beta, const void* 
 
 // ------------------------------------------------------------ workspace plan
 struct StreamPlan {
-    size_t bar_off, ppart_off, spart_off, h_off, ypart_off, zone_bytes, total_bytes;
+    size_t bar_off, zero_off, ppart_off, spart_off, h_off, ypart_off, zone_bytes, total_bytes;
     int Fp, nkb1, nfb, items1, per1, S1, nkb2, nnb, items2, per2, S2;
 };
 
-// Layout of the streaming kernel's scratch for G workgroups.  Only the barrier
-// word (the "zone") has to be zero between calls.
+// Layout of the streaming kernels' scratch for G workgroups.  Only the "zone"
+// (barrier words, and a block of zeros that nothing ever writes) has to be zero
+// before the first call; the barrier words only ever increase.
 StreamPlan stream_plan(int64_t D, int64_t F, int G) {
     StreamPlan s;
     s.Fp = (int)((F + 127) / 128 * 128);
@@ -236,7 +238,8 @@ StreamPlan stream_plan(int64_t D, int64_t F, int G) {
     s.per2 = (s.items2 + G - 1) / G;
     s.S2 = (s.nkb2 - 1) / s.per2 + 2;
     s.bar_off = 0;
-    s.zone_bytes = align_up((size_t)BAR_WORDS * 4);
+    s.zero_off = align_up((size_t)BAR_WORDS * 4);               // 256 bytes that stay zero
+    s.zone_bytes = s.zero_off + kAlign;
     s.ppart_off = s.zone_bytes;
     s.spart_off = s.ppart_off + align_up((size_t)s.nfb * s.S1 * 4096 * 4);
     s.h_off = s.spart_off + align_up((size_t)s.S1 * 16 * 4);
@@ -434,6 +437,16 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
     return BB_OK;
 }
 
+// the barrier words of the streaming kernels must be zero before their first use in a workspace
+int prepare_barrier_zone(const StreamPlan& sp, hipStream_t st) {
+    if (g_ws.clean < sp.zone_bytes) {
+        if (int rc = fill_zero(g_ws.ptr, sp.zone_bytes, st)) return rc;
+        g_ws.clean = sp.zone_bytes;
+        g_ws.bar_count = 0;
+    }
+    return BB_OK;
+}
+
 int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u16* W2, const u16* R, u16* Y, int M,
                int D, int F, float eps, int cus, hipStream_t st) {
     static int resident = -1;      // workgroups of the streaming kernel one compute unit can hold
@@ -446,11 +459,7 @@ int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u
     const int G = std::min(cus, kPlanCUs);
     const StreamPlan sp = stream_plan(D, F, G);
     char* base = (char*)g_ws.ptr;
-    if (g_ws.clean < sp.zone_bytes) {
-        if (int rc = fill_zero(base, sp.zone_bytes, st)) return rc;
-        g_ws.clean = sp.zone_bytes;
-        g_ws.bar_count = 0;
-    }
+    if (int rc = prepare_barrier_zone(sp, st)) return rc;
     StreamArgs a;
     a.X = X; a.g = g; a.W1 = W1; a.W3 = W3; a.W2 = W2; a.Y = Y; a.R = R;
     a.ppart = (float*)(base + sp.ppart_off);
@@ -470,6 +479,72 @@ int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u
     BB_HIP(hipGetLastError());
     prof_mark("ffn_stream", st);
     g_ws.bar_count += 3u;   // grid barriers per call
+    return BB_OK;
+}
+
+// Plan of the streaming kernel for transposed weights: rows per workgroup, the k-block of bf16(x g)
+// that fits LDS next to the partial sums.  ok = false: the shape needs more than STREAMT_MAXG groups of
+// 16 rows per workgroup (the tiled kernels take it).
+struct StreamTPlan {
+    bool ok;
+    int upw, cpw, kblk, cq2, red_off, stat_off, lds;
+};
+StreamTPlan stream_t_plan(int64_t D, int64_t F, int G) {
+    StreamTPlan s{};
+    s.upw = (int)((F + G - 1) / G);
+    s.cpw = (int)((D + G - 1) / G);
+    const int ng = (s.upw + 15) / 16, ng2 = (s.cpw + 15) / 16;
+    if (ng > STREAMT_MAXG || ng2 > STREAMT_MAXG) return s;
+    const int red = std::max(4 * ng * 2048, 4 * ng2 * 1024);
+    const int room = STREAMT_LDS - red - 320;                     // bytes left for 16 rows of kblk + 8 elements
+    int kblk = (room / 32 - 8) / 512 * 512;
+    kblk = std::min(kblk, (int)((D + 511) / 512 * 512));
+    if (kblk < 512) return s;
+    s.kblk = kblk;
+    s.cq2 = (int)(((F / 8 + 3) / 4 + 15) / 16 * 16);
+    s.red_off = 16 * (kblk + 8) * 2;
+    s.stat_off = s.red_off + red;
+    s.lds = s.stat_off + 320;                                      // 16 inverse norms, 4 x 16 partial sums
+    s.ok = true;
+    return s;
+}
+
+// BB_ERR_VARIANT: not applicable to this shape or device (the caller falls back to the tiled kernels)
+int run_stream_t(const u16* X, const u16* g, const u16* W1t, const u16* W3t, const u16* W2t, const u16* R, u16* Y,
+                 int M, int D, int F, float eps, int cus, hipStream_t st) {
+    if (M < 1 || M > kStreamMaxM) return BB_ERR_VARIANT;       // (the kernel clamps row numbers to M - 1)
+    const int G = std::min(cus, kPlanCUs);
+    const StreamTPlan tp = stream_t_plan(D, F, G);
+    if (!tp.ok) return BB_ERR_VARIANT;
+    static int resident = -1;
+    if (resident < 0) {
+        BB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_stream_t_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, STREAMT_LDS));
+        int nres = 0;
+        BB_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nres, ffn_stream_t_kernel, STREAMT_THREADS, tp.lds));
+        resident = nres;
+    }
+    if (resident < 1) return BB_ERR_VARIANT;    // the grid barrier needs every workgroup resident
+    const StreamPlan sp = stream_plan(D, F, G);        // (barrier words and hidden block: the same places)
+    char* base = (char*)g_ws.ptr;
+    if (int rc = prepare_barrier_zone(sp, st)) return rc;
+    StreamTArgs a;
+    a.X = X; a.g = g; a.W1t = W1t; a.W3t = W3t; a.W2t = W2t; a.R = R; a.Y = Y;
+    a.H = (u16*)(base + sp.h_off);
+    a.bar = (unsigned*)(base + sp.bar_off);
+    a.zeros = (const u16*)(base + sp.zero_off);
+    a.bar_base = g_ws.bar_count;
+    a.M = M; a.D = D; a.F = F; a.Fp = sp.Fp; a.eps = eps;
+    a.upw = tp.upw; a.cpw = tp.cpw; a.kblk = tp.kblk; a.cq2 = tp.cq2;
+    a.red_off = tp.red_off; a.stat_off = tp.stat_off;
+    if (log_on())
+        std::fprintf(stderr, "[bb] stream_t M %d D %d F %d units/wg %d columns/wg %d kblk %d lds %d\n", M, D, F, a.upw,
+                     a.cpw, a.kblk, tp.lds);
+    prof_begin(st);
+    hipLaunchKernelGGL(ffn_stream_t_kernel, dim3(G), dim3(STREAMT_THREADS), tp.lds, st, a);
+    BB_HIP(hipGetLastError());
+    prof_mark("ffn_stream_t", st);
+    g_ws.bar_count += 1u;   // one grid barrier per call
     return BB_OK;
 }
 
@@ -613,6 +688,13 @@ int ffn_t_locked(const void* X, const void* g, const void* W1t, const void* W3t,
     const size_t zone = zone_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F);
     if (int rc = ensure_workspace(zone + scratch_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F))) return rc;
     hipStream_t st = as_stream(stream);
+    // few rows: the weight-streaming kernel for this layout (unless a tiled variant is forced)
+    const int variant = read_variant();
+    if (M <= kStreamMaxM && (variant == BB_VARIANT_AUTO || variant == BB_VARIANT_STREAM)) {
+        const int rc = run_stream_t((const u16*)X, (const u16*)g, (const u16*)W1t, (const u16*)W3t, (const u16*)W2t,
+                                    (const u16*)R, (u16*)Y, (int)M, (int)D, (int)F, eps, dev->cus, st);
+        if (rc != BB_ERR_VARIANT) return rc;
+    }
     u16* H = (u16*)((char*)g_ws.ptr + zone);
     void* split = (char*)H + align_up((size_t)M * F * 2);
     const int pcus = std::min(dev->cus, kPlanCUs);

@@ -439,3 +439,73 @@ def test_layernorm_variants(M, D, N, variant):
     assert row_rel_err(Y, ref) <= TOL
     X, ga, be, W = dev(cpu)
     assert row_rel_err(bb.bb_layernorm_matmul_t(X, ga, be, W.t().contiguous(), 1e-5), ref) <= TOL
+
+
+# ------------------------------------------------ few rows on transposed weights: the streaming kernel of that layout
+@pytest.mark.parametrize("M,D,F", [(1, 8, 8), (2, 64, 64), (16, 256, 704), (3, 520, 1000), (16, 2048, 8192),
+                                   (5, 4104, 11016), (7, 8192, 8192), (16, 512, 32768), (9, 1024, 40000)])
+def test_transposed_stream_shapes(M, D, F):
+    # ragged unit and column ranges per workgroup, idle workgroups (fewer units than workgroups), several
+    # blocks of the model dimension in LDS (D > 4096), the widest plan (128 units per workgroup), and a
+    # hidden size past the plan (falls back to the tiled kernels)
+    X, g, W1, W3, W2 = bb_inputs.make_ffn(M, D, F, seed=M + D + F)
+    ref = orc.rmsnorm_swiglu_ffn(X, g, W1, W3, W2, 1e-6)
+    d = dev((X, g, tr(W1), tr(W3), tr(W2)))
+    Y = bb.bb_rmsnorm_swiglu_ffn_t(*d, 1e-6)
+    torch.cuda.synchronize()
+    assert row_rel_err(Y, ref) <= TOL
+    # a second call reuses the barrier words and the hidden-block scratch
+    Y2 = bb.bb_rmsnorm_swiglu_ffn_t(*d, 1e-6)
+    torch.cuda.synchronize()
+    assert torch.equal(Y.view(torch.uint16), Y2.view(torch.uint16))
+
+
+def test_transposed_stream_c2_all_rows_and_layouts_agree():
+    c = bb_inputs.CONFIGS["c2"]
+    X, g, W1, W3, W2 = bb_inputs.make_config("c2")
+    ref = orc.rmsnorm_swiglu_ffn(X, g, W1, W3, W2, c.eps)
+    d = dev((X, g, W1, W3, W2))
+    Yt = bb.bb_rmsnorm_swiglu_ffn_t(d[0], d[1], tr(d[2]), tr(d[3]), tr(d[4]), c.eps)
+    Y = bb.bb_rmsnorm_swiglu_ffn(*d, c.eps)
+    torch.cuda.synchronize()
+    err = row_rel_err(Yt, ref)
+    print("c2 transposed stream rel err", err)
+    assert err <= TOL
+    assert row_rel_err(Y, ref) <= TOL
+    # interleaving the two streaming kernels (they share the barrier words) keeps both correct
+    Yt2 = bb.bb_rmsnorm_swiglu_ffn_t(d[0], d[1], tr(d[2]), tr(d[3]), tr(d[4]), c.eps)
+    torch.cuda.synchronize()
+    assert torch.equal(Yt.view(torch.uint16), Yt2.view(torch.uint16))
+
+
+def test_transposed_stream_residual_and_forced_tiled_variant():
+    M, D, F = 11, 1024, 2816
+    X, g, W1, W3, W2 = bb_inputs.make_ffn(M, D, F, seed=77)
+    ref = orc.rmsnorm_swiglu_ffn(X, g, W1, W3, W2, 1e-6)
+    d = dev((X, g, tr(W1), tr(W3), tr(W2)))
+    Yr = bb.bb_rmsnorm_swiglu_ffn_residual(*d, d[0], 1e-6, transposed=True)
+    torch.cuda.synchronize()
+    assert row_rel_err(Yr, ref + X.double().numpy()) <= TOL
+    # in place: Y = R = X
+    Xc = d[0].clone()
+    bb.bb_rmsnorm_swiglu_ffn_residual(Xc, d[1], d[2], d[3], d[4], Xc, 1e-6, Y=Xc, transposed=True)
+    torch.cuda.synchronize()
+    assert torch.equal(Xc.view(torch.uint16), Yr.view(torch.uint16))
+    bb.bb_set_variant(bb.VARIANT_SNAPSHOT1)           # the tiled kernels on the same operands
+    try:
+        Ys = bb.bb_rmsnorm_swiglu_ffn_t(*d, 1e-6)
+        torch.cuda.synchronize()
+    finally:
+        bb.bb_set_variant(bb.VARIANT_AUTO)
+    assert row_rel_err(Ys, ref) <= TOL
+
+
+def test_transposed_stream_large_activations():
+    # |x| ~ 1e3 with heavy tails: the statistics are fp32 sums of squares, the inverse norm comes after the dots
+    M, D, F = 16, 4096, 1024
+    X, g, W1, W3, W2 = bb_inputs.make_ffn(M, D, F, seed=5)
+    X = (X.float() * 1000.0).to(torch.bfloat16)
+    ref = orc.rmsnorm_swiglu_ffn(X, g, W1, W3, W2, 1e-6)
+    Y = bb.bb_rmsnorm_swiglu_ffn_t(*dev((X, g, tr(W1), tr(W3), tr(W2))), 1e-6)
+    torch.cuda.synchronize()
+    assert row_rel_err(Y, ref) <= TOL
