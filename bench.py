@@ -143,6 +143,36 @@ def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
         ms_transposed = e0.elapsed_time(e1) / steps
         del dt
 
+    # decode: the same operator on transposed weights (W1^T, W3^T [F,D], W2^T [D,F]) runs the streaming
+    # kernel of that layout; timed like the primary, on rotating transposed weight sets
+    t_stream = None
+    if stream_variant:
+        tsets = [[d[0], d[1]] + [w.t().contiguous() for w in d[2:]] for d in dev_sets]
+        def stept(i):
+            bb.bb_rmsnorm_swiglu_ffn_t(*tsets[i % nsets], cfg.eps, Y=out)
+        for i in range(warmup):
+            stept(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(steps):
+            stept(i)
+        e1.record()
+        torch.cuda.synchronize()
+        ms_t = e0.elapsed_time(e1) / steps
+        bb.bb_profile_enable(True)
+        kt = []
+        for i in range(steps):
+            stept(i)
+            kt += [ms for kname, ms in bb.bb_profile_last() if kname == "ffn_stream_t"]
+        bb.bb_profile_enable(False)
+        stept(0)
+        torch.cuda.synchronize()
+        y_t = out.clone()
+        k_ms = float(np.mean(kt)) if kt else None
+        t_stream = {"ms_per_step": ms_t, "gbs": bytes_of(cfg) / (ms_t * 1e-3) / 1e9, "kernel_ms": k_ms, "y": y_t}
+        del tsets
+
     # the FFN with the decoder block's residual connection fused into the last kernel's epilogue
     ms_residual = None
     if cfg.op == "ffn":
@@ -206,6 +236,11 @@ def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
         y = y_fused[rows].float().cpu().numpy().astype(np.float64)
         err = float((np.linalg.norm(y - ref, axis=1) / np.linalg.norm(ref, axis=1)).max())
         res["parity"] = {"max_row_rel_err": err, "rows_checked": len(rows), "tolerance": 2e-2}
+        if t_stream is not None:
+            yt = t_stream["y"][rows].float().cpu().numpy().astype(np.float64)
+            t_stream["parity"] = {"max_row_rel_err": float((np.linalg.norm(yt - ref, axis=1) /
+                                                           np.linalg.norm(ref, axis=1)).max()),
+                                  "rows_checked": len(rows), "tolerance": 2e-2}
         cpu_tflops = row_work / sec_per_row / 1e12
         res["cpu_baseline"] = {
             "value": cpu_tflops if bound == "mfma" else bytes_of(cfg) / (sec_per_row * cfg.M) / 1e9,
@@ -215,6 +250,17 @@ def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
                       f"{t_total:.1f} s; whole-workload time extrapolated as seconds_per_row * M",
             "seconds_full_workload_extrapolated": sec_per_row * cfg.M,
         }
+    if t_stream is not None:
+        t_stream.pop("y")
+        k_ms = t_stream.pop("kernel_ms")
+        if k_ms:
+            a = bytes_of(cfg) / (k_ms * 1e-3) / 1e9
+            t_stream["kernels_ms"] = {"ffn_stream_t": k_ms}
+            t_stream["roofline"] = {"kernel": "ffn_stream_t", "bound": "hbm", "achieved": a, "peak": PEAK_HBM_GBS,
+                                    "unit": "GB/s", "frac": a / PEAK_HBM_GBS,
+                                    "traffic": MEASURED_TRAFFIC_BYTES.get((name, "ffn_stream_t")),
+                                    "algorithmic": bytes_of(cfg)}
+        res["transposed_weights"] = t_stream
     del dev_sets
     torch.cuda.empty_cache()
     return res
@@ -445,6 +491,7 @@ def main():
             "roofline": d["roofline"], "cpu_baseline": d.get("cpu_baseline"), "parity": d.get("parity"),
             "kernels_ms": d["kernels_ms"], "unfused_ms_per_step": d["unfused_ms_per_step"],
             "residual_ms_per_step": d["residual_ms_per_step"],
+            "transposed_weights": d.get("transposed_weights"),
         }
     if attn is not None:
         line["attention"] = attn

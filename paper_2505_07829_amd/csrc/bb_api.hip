@@ -467,6 +467,7 @@ int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u
     a.H = (u16*)(base + sp.h_off);
     a.ypart = (float*)(base + sp.ypart_off);
     a.bar = (unsigned*)(base + sp.bar_off);
+    a.zeros = (const u16*)(base + sp.zero_off);
     a.bar_base = g_ws.bar_count;
     a.M = M; a.D = D; a.F = F; a.Fp = sp.Fp; a.eps = eps;
     a.nkb1 = sp.nkb1; a.nfb = sp.nfb; a.items1 = sp.items1; a.per1 = sp.per1; a.S1 = sp.S1;

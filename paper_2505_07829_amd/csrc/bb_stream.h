@@ -54,6 +54,7 @@ struct StreamArgs {
     float* spart;      // [S1][16] partial row sums of squares
     u16* H;            // [16][Fp] hidden block, bf16
     float* ypart;      // [nnb][S2][16][128] partial outputs
+    const u16* zeros;  // 16 zero bytes in global memory: what a lane outside the matrices loads in phase 1
     unsigned* bar;     // BAR_WORDS barrier words (see grid_arrive), zero before the first call
     unsigned bar_base; // grid barriers completed before this call
     int M, D, F, Fp;
@@ -182,9 +183,36 @@ struct StreamItem1 {
     u32x4 r1[8], r3[8], rx, rg;
 };
 
+// Phase 1 requests its weights STREAM_NP1 items ahead with loads the compiler does not see as
+// loads (it waits for ALL outstanding loads before the first use of any loaded register inside
+// a loop, which empties the queue at every item): an asm load leaves its destination registers
+// "in flight"; stream_ready() is the one place where the wavefront waits until at most N younger
+// loads are outstanding, and it takes the registers as in-out operands, so that every use is
+// ordered after the wait.  Vector memory loads of a wavefront return in order.  Weights are
+// streamed once: non-temporal.
+__device__ __forceinline__ void stream_load16_nt(u32x4& dst, const u16* src) {
+    asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(dst) : "v"(src));
+}
+__device__ __forceinline__ void stream_load16(u32x4& dst, const u16* src) {
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(src));
+}
+template <int N>
+__device__ __forceinline__ void stream_ready(StreamItem1& r) {
+    asm volatile("s_waitcnt vmcnt(%8)"
+                 : "+v"(r.r1[0]), "+v"(r.r1[1]), "+v"(r.r1[2]), "+v"(r.r1[3]), "+v"(r.r1[4]), "+v"(r.r1[5]),
+                   "+v"(r.r1[6]), "+v"(r.r1[7])
+                 : "n"(N));
+    asm volatile(""
+                 : "+v"(r.r3[0]), "+v"(r.r3[1]), "+v"(r.r3[2]), "+v"(r.r3[3]), "+v"(r.r3[4]), "+v"(r.r3[5]),
+                   "+v"(r.r3[6]), "+v"(r.r3[7]));
+    asm volatile("" : "+v"(r.rx), "+v"(r.rg));
+}
+constexpr int STREAM_ITEM1_LOADS = 18;
+
 __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const StreamArgs p) {
     __shared__ StreamSmem sm;
-    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int t = threadIdx.x, lane = t & 63;
+    const int w = __builtin_amdgcn_readfirstlane(t >> 6);        // in a scalar register: branches on it are scalar
     const int jn = lane & 15, g4 = lane >> 4;
     const int G = gridDim.x, b = blockIdx.x;
     constexpr int RS = 2 * 16 * 128;               // floats per wavefront in sm.red
@@ -205,14 +233,21 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
             for (int c = 0; c < 8; ++c) { accP[c] = f32x4{0, 0, 0, 0}; accQ[c] = f32x4{0, 0, 0, 0}; }
             float ssq = 0.f;
             StreamItem1 it[STREAM_NP1];
-            auto issue = [&](int kb, StreamItem1& r) {          // nothing is loaded past the segment
+            // (every load is unconditional: a lane outside the matrices or past the segment reads the
+            // zero chunk instead, so no load stands inside a branch)
+            auto issue = [&](int kb, StreamItem1& r) {
                 const bool live = kb < kb1;
                 const int d0 = 32 * kb + 8 * g4;
-                load_block(p.W1, p.F, d0, p.D, col, col_ok && live, r.r1);
-                load_block(p.W3, p.F, d0, p.D, col, col_ok && live, r.r3);
+#pragma unroll
+                for (int i2 = 0; i2 < 8; ++i2) {
+                    const bool ok = col_ok && live && d0 + i2 < p.D;
+                    const size_t off = (size_t)(d0 + i2) * p.F + col;
+                    stream_load16_nt(r.r1[i2], ok ? p.W1 + off : p.zeros);
+                    stream_load16_nt(r.r3[i2], ok ? p.W3 + off : p.zeros);
+                }
                 const bool ok = live && d0 < p.D;
-                r.rx = (ok && jn < p.M) ? ldg16(p.X + (size_t)jn * p.D + d0) : zero4();
-                r.rg = ok ? ldg16(p.g + d0) : zero4();
+                stream_load16(r.rx, (ok && jn < p.M) ? p.X + (size_t)jn * p.D + d0 : p.zeros);
+                stream_load16(r.rg, ok ? p.g + d0 : p.zeros);
             };
             // the wavefronts take the items round robin: kb0 + w, kb0 + w + 4, ...
 #pragma unroll
@@ -220,32 +255,36 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
             for (int kbb = kb0 + w; kbb < kb1; kbb += 4 * STREAM_NP1) {
 #pragma unroll
                 for (int u = 0; u < STREAM_NP1; ++u) {
+                    // (past the segment the item is all zeros and adds nothing)
                     const int kb = kbb + 4 * u;
-                    if (kb < kb1) {
-                        // consume the registers of item kb, then refill them
-                        Chunk xa;
+                    stream_ready<STREAM_ITEM1_LOADS * (STREAM_NP1 - 1)>(it[u]);
+                    // consume the registers of item kb, then refill them
+                    Chunk xa;
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const float x0 = bf_lo(it[u].rx[q]), x1 = bf_hi(it[u].rx[q]);
-                            ssq = fmaf(x0, x0, ssq);
-                            ssq = fmaf(x1, x1, ssq);
-                            xa.u[q] = pack_bf16(x0 * bf_lo(it[u].rg[q]), x1 * bf_hi(it[u].rg[q]));
-                        }
-                        u32x4 t1[8], t3[8];
-                        transpose8x8(it[u].r1, t1);
-                        transpose8x8(it[u].r3, t3);
-                        issue(kb + 4 * STREAM_NP1, it[u]);
+                    for (int q = 0; q < 4; ++q) {
+                        const float x0 = bf_lo(it[u].rx[q]), x1 = bf_hi(it[u].rx[q]);
+                        ssq = fmaf(x0, x0, ssq);
+                        ssq = fmaf(x1, x1, ssq);
+                        xa.u[q] = pack_bf16(x0 * bf_lo(it[u].rg[q]), x1 * bf_hi(it[u].rg[q]));
+                    }
+                    u32x4 t1[8], t3[8];
+                    transpose8x8(it[u].r1, t1);
+                    transpose8x8(it[u].r3, t3);
+                    issue(kb + 4 * STREAM_NP1, it[u]);
 #pragma unroll
-                        for (int c = 0; c < 8; ++c) {
-                            Chunk b1, b3;
-                            b1.u = t1[c];
-                            b3.u = t3[c];
-                            accP[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa.v, b1.v, accP[c], 0, 0, 0);
-                            accQ[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa.v, b3.v, accQ[c], 0, 0, 0);
-                        }
+                    for (int c = 0; c < 8; ++c) {
+                        Chunk b1, b3;
+                        b1.u = t1[c];
+                        b3.u = t3[c];
+                        accP[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa.v, b1.v, accP[c], 0, 0, 0);
+                        accQ[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa.v, b3.v, accQ[c], 0, 0, 0);
                     }
                 }
             }
+            // the requests past the segment are still in flight: their registers stay reserved until they
+            // have landed (a register reused earlier would be overwritten when its load returns)
+#pragma unroll
+            for (int u = 0; u < STREAM_NP1; ++u) stream_ready<0>(it[u]);
             BB_STREAM_TRACE(1);
             // ---- add the 4 wavefronts in LDS and store the workgroup's partial tile in its slot
             stash_tile(sm.red[w][0], accP, lane);

@@ -131,6 +131,14 @@ __device__ __forceinline__ f32x4 fold16(const f32x4 (&acc)[2][2], int upper) {
 }
 
 template <int N>
+__device__ __forceinline__ void async_wait() {
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+__device__ __forceinline__ void async_tie(u32x4 (&a)[4], u32x4 (&b)[4]) {
+    asm volatile(""
+                 : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]));
+}
+template <int N>
 __device__ __forceinline__ void async_ready(u32x4 (&a)[4], u32x4 (&b)[4]) {
     asm volatile("s_waitcnt vmcnt(%8)"
                  : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3])
@@ -387,8 +395,11 @@ __global__ __launch_bounds__(STREAMT_THREADS) void ffn_stream_t_kernel(const Str
                 // Younger loads: in the first pass through the ring the hidden values of all items were
                 // requested together, after all their weights: at least the 4 (NPF2 - 1) hidden loads of
                 // the items behind this one; later, weights and hidden values of an item go out together.
-                if (idx0 == 0) async_ready<4 * (STREAMT_NPF2 - 1)>(it[u].r2, it[u].h);
-                else async_ready<8 * (STREAMT_NPF2 - 1)>(it[u].r2, it[u].h);
+                // (the wait alone in the branch, ONE tie after it: two ties in two branches would be joined
+                // by register copies - of registers whose loads are still in flight)
+                if (idx0 == 0) async_wait<4 * (STREAMT_NPF2 - 1)>();
+                else async_wait<8 * (STREAMT_NPF2 - 1)>();
+                async_tie(it[u].r2, it[u].h);
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     Chunk alo, ahi;

@@ -1,0 +1,47 @@
+"""The streaming kernels load with inline asm and wait explicitly; the compiler must not have put a
+spill or a register copy between such a load and its wait.  This compiles the library's device code
+to assembly (no GPU needed) and runs the static check that ships next to the kernels."""
+import os
+import shutil
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2505_07829_amd", "csrc")
+KERNELS = ["_ZN2bb17ffn_stream_kernelENS_10StreamArgsE", "_ZN2bb19ffn_stream_t_kernelENS_11StreamTArgsE"]
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None, reason="hipcc not on PATH")
+def test_no_instruction_touches_a_register_whose_load_is_in_flight(tmp_path):
+    asm = tmp_path / "bb_api.s"
+    cmd = ["hipcc", "-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-S", "--cuda-device-only", "-o", str(asm), os.path.join(CSRC, "bb_api.hip")]
+    subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL, timeout=900)
+    r = subprocess.run([sys.executable, os.path.join(CSRC, "check_inflight.py"), str(asm)] + KERNELS,
+                       capture_output=True, text=True, timeout=300)
+    print(r.stdout)
+    assert r.returncode == 0, r.stdout + r.stderr
+    for k in KERNELS:
+        assert f"{k}: 0 suspicious" in r.stdout
+
+
+def test_checker_flags_a_planted_copy(tmp_path):
+    # a copy of a register between its asm load and the wait must be reported; after the wait it must not
+    text = """k:
+\t;;#ASMSTART
+\tglobal_load_dwordx4 v[4:7], v[0:1], off nt
+\t;;#ASMEND
+\tv_mov_b32_e32 v9, v5
+\t;;#ASMSTART
+\ts_waitcnt vmcnt(0)
+\t;;#ASMEND
+\tv_mov_b32_e32 v10, v5
+\ts_endpgm
+"""
+    f = tmp_path / "k.s"
+    f.write_text(text)
+    r = subprocess.run([sys.executable, os.path.join(CSRC, "check_inflight.py"), str(f), "k"], capture_output=True,
+                       text=True)
+    assert r.returncode == 1 and "k: 1 suspicious" in r.stdout
