@@ -1,62 +1,135 @@
 #!/usr/bin/env python3
 """Hazard check for the streaming kernels, which request their weights with inline-asm loads and
 wait with explicit s_waitcnt (the compiler does not know that those destination registers are in
-flight, so a spill or a copy it inserts between a load and its wait would read garbage).
+flight, so a spill or a copy it inserts between a load and its wait would read garbage, and a
+register it reuses too early is overwritten when the load returns).
 
     check_inflight.py <device assembly (.s)> <kernel symbol> [...]
 
-Linear simulation of the wavefront's vector-memory queue over the kernel's text (loads return in
-order; "s_waitcnt vmcnt(N)" retires all but the N youngest): flags any instruction outside the
-asm blocks that mentions a register whose asm load may still be outstanding.  Not aware of the
-control flow: a block placed before its loop header in the text can give a false alarm, which
-has to be read; a clean run means no spill or copy stands between a load and its wait in text
-order.  Exit status 1 if anything was flagged."""
-import re, sys
-def regs(l):
-    out=set()
-    for m in re.finditer(r'\bv\[(\d+):(\d+)\]',l): out.update(range(int(m.group(1)),int(m.group(2))+1))
-    for m in re.finditer(r'\bv(\d+)\b',l): out.add(int(m.group(1)))
+Forward data-flow analysis over the kernel's control-flow graph.  State: for every vector
+register that an asm load has been issued to, the least number of vector-memory instructions
+issued after that load on any path ("younger").  Loads of a wavefront return in order, so
+"s_waitcnt vmcnt(N)" completes every load with at least N younger ones; states of joining paths
+are merged register by register with the minimum.  Any instruction outside the asm blocks that
+mentions a register whose load may be outstanding is reported.  Exit status 1 if anything was
+reported."""
+import re
+import sys
+
+BIG = 1 << 20
+
+
+def regs(text):
+    out = set()
+    for m in re.finditer(r'\bv\[(\d+):(\d+)\]', text):
+        out.update(range(int(m.group(1)), int(m.group(2)) + 1))
+    for m in re.finditer(r'\bv(\d+)\b', text):
+        out.add(int(m.group(1)))
     return out
-def check(path, kernel):
-    txt=open(path).read().split('\n')
-    L=[i for i,l in enumerate(txt) if l.startswith(kernel+':')][0]
-    E=next(i for i in range(L,len(txt)) if 's_endpgm' in txt[i])
-    lines=txt[L:E]
-    queue=[]      # (is_asm, regs) in issue order
-    inflight={}   # reg -> issue line
-    inapp=False; bad=0
-    def wait(n):
-        nonlocal queue
-        done=queue[:max(0,len(queue)-n)]; queue=queue[max(0,len(queue)-n):]
-        for isasm,rs,_ in done:
-            for r in rs:
-                # only clear if no younger load to the same register remains
-                if not any(r in q[1] for q in queue): inflight.pop(r,None)
-    for i,l in enumerate(lines):
-        s=l.strip()
-        if 'ASMSTART' in s: inapp=True; continue
-        if 'ASMEND' in s: inapp=False; continue
-        if not s or s.startswith(';') or s.startswith('.'): continue
-        m=re.match(r's_waitcnt\b(.*)',s)
+
+
+def parse(lines):
+    """-> blocks: list of dicts {label, ins: [(lineno, text, in_asm)], succ: [labels or indices]}"""
+    blocks, cur, in_asm = [], {"label": None, "ins": [], "succ": [], "fall": True}, False
+    for i, raw in enumerate(lines):
+        s = raw.strip()
+        if 'ASMSTART' in s:
+            in_asm = True
+            continue
+        if 'ASMEND' in s:
+            in_asm = False
+            continue
+        m = re.match(r'^(\.LBB\d+_\d+):', raw)
         if m:
-            mm=re.search(r'vmcnt\((\d+)\)',s)
-            if mm: wait(int(mm.group(1)))
-            elif re.match(r's_waitcnt\s+(0x0+|0)\s*$',s): wait(0)
+            blocks.append(cur)
+            cur = {"label": m.group(1), "ins": [], "succ": [], "fall": True}
             continue
-        if inapp:
-            m=re.match(r'global_load_dwordx4 v\[(\d+):(\d+)\]',s)
+        if not s or s.startswith(';') or s.startswith('.'):
+            continue
+        cur["ins"].append((i, s, in_asm))
+        m = re.match(r'(s_branch|s_cbranch_\w+)\s+(\.LBB\d+_\d+)', s)
+        if m:
+            cur["succ"].append(m.group(2))
+            if m.group(1) == 's_branch':
+                cur["fall"] = False
+            blocks.append(cur)
+            cur = {"label": None, "ins": [], "succ": [], "fall": True}
+        elif s.startswith('s_endpgm'):
+            cur["fall"] = False
+            blocks.append(cur)
+            cur = {"label": None, "ins": [], "succ": [], "fall": True}
+    blocks.append(cur)
+    index = {b["label"]: k for k, b in enumerate(blocks) if b["label"]}
+    for k, b in enumerate(blocks):
+        succ = [index[l] for l in b["succ"] if l in index]
+        if b["fall"] and k + 1 < len(blocks):
+            succ.append(k + 1)
+        b["succ"] = succ
+    return blocks
+
+
+def transfer(state, block, report=None):
+    st = dict(state)
+    for lineno, s, in_asm in block["ins"]:
+        m = re.match(r's_waitcnt\b(.*)', s)
+        if m:
+            mm = re.search(r'vmcnt\((\d+)\)', s)
+            n = int(mm.group(1)) if mm else (0 if re.match(r's_waitcnt\s+(0x0+|0)\s*$', s) else None)
+            if n is not None:
+                st = {r: y for r, y in st.items() if y < n}
+            continue
+        is_vmem = re.match(r'(global_load|global_store|global_atomic|buffer_|flat_|scratch_)', s) is not None
+        if in_asm:
+            m = re.match(r'global_load_dwordx4 v\[(\d+):(\d+)\]', s)
             if m:
-                rs=set(range(int(m.group(1)),int(m.group(2))+1))
-                queue.append((True,rs,i))
-                for r in rs: inflight[r]=i
+                st = {r: y + 1 for r, y in st.items()}
+                for r in range(int(m.group(1)), int(m.group(2)) + 1):
+                    st[r] = 0
             continue
-        if re.match(r'(global_load|global_store|global_atomic|buffer_|flat_)',s):
-            queue.append((False,set(),i))          # compiler's own vector memory op: only counts
-        hit=regs(s)&set(inflight)
-        if hit:
-            bad+=1
-            if bad<=12: print("  line %d: %s   <- registers %s in flight since line %s"%(i,s[:70],sorted(hit)[:4],sorted(set(inflight[r] for r in hit))[:2]))
-    print("%s: %d suspicious instruction(s)"%(kernel,bad))
-    return bad
-if __name__=='__main__':
-    sys.exit(1 if sum(check(sys.argv[1],k) for k in sys.argv[2:]) else 0)
+        hit = regs(s) & set(st)
+        if hit and report is not None:
+            report.append((lineno, s, sorted(hit)))
+        if is_vmem:
+            st = {r: y + 1 for r, y in st.items()}
+    return st
+
+
+def check(path, kernel):
+    txt = open(path).read().split('\n')
+    start = [i for i, l in enumerate(txt) if l.startswith(kernel + ':')][0]
+    end = next(i for i in range(start, len(txt)) if 's_endpgm' in txt[i])
+    blocks = parse(txt[start:end + 1])
+    n = len(blocks)
+    inst = [None] * n
+    inst[0] = {}
+    work = [0]
+    while work:
+        k = work.pop()
+        out = transfer(inst[k], blocks[k])
+        for j in blocks[k]["succ"]:
+            if inst[j] is None:
+                new = dict(out)
+            else:
+                new = dict(inst[j])
+                for r, y in out.items():
+                    new[r] = min(new.get(r, BIG), y)
+            if new != inst[j]:
+                inst[j] = new
+                work.append(j)
+    report = []
+    for k in range(n):
+        if inst[k] is not None:
+            transfer(inst[k], blocks[k], report)
+    seen = set()
+    for lineno, s, hit in report:
+        if lineno in seen:
+            continue
+        seen.add(lineno)
+        if len(seen) <= 12:
+            print("  line %d: %s   <- registers %s may be in flight" % (lineno, s[:72], hit[:4]))
+    print("%s: %d suspicious instruction(s)" % (kernel, len(seen)))
+    return len(seen)
+
+
+if __name__ == '__main__':
+    sys.exit(1 if sum(check(sys.argv[1], k) for k in sys.argv[2:]) else 0)
