@@ -33,7 +33,8 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
 # calibrated against bb_calib_copy).  Counters cannot be read from inside a timed run, so the
 # figures are carried here; workloads without a counter run report null.
 MEASURED_TRAFFIC_BYTES = {
-    ("c2", "ffn_stream"): 281.2e6 + 16.2e6,
+    ("c2", "ffn_stream"): 280.4e6 + 16.2e6,
+    ("c2", "ffn_stream_t"): 275.0e6 + 0.7e6,
     ("c3", "gemm_gateup"): 621.5e6 + 45.2e6,
     ("c3", "gemm_gateup_prescaled"): 624.2e6 + 45.1e6,
     ("attention", "attention"): 100.9e6 + 33.6e6,

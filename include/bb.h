@@ -166,10 +166,15 @@ int bb_layernorm_matmul(const void* X, const void* gamma, const void* beta,
  * Everything else (arguments, arithmetic, results, workspace of the op without
  * the suffix, errors) is as for bb_rmsnorm_swiglu_ffn / bb_layernorm_matmul.
  * The contraction index is contiguous in these layouts, so the weight tiles
- * need no transposition on chip.  Every M goes through the tiled kernels (for
- * few rows with the split contraction, from 256 rows on with the statistics
- * loop as a kernel of its own, see BB_VARIANT_PRESCALE); the streaming variant
- * takes the untransposed layout only, and bb_set_variant has no effect here.
+ * need no transposition on chip.  The FFN with at most 16 rows runs a
+ * weight-streaming kernel of its own for this layout (every workgroup owns a
+ * contiguous range of rows of W1t, W3t and then of W2t: no partial sums between
+ * workgroups, one grid barrier), unless bb_set_variant selected a tiled variant
+ * or the shape gives a workgroup more than 128 hidden units or output columns
+ * (F or D above 128 times the number of compute units); more rows, and
+ * bb_layernorm_matmul_t at any size, go through the tiled kernels (for few rows
+ * with the split contraction, from 256 rows on with the statistics loop as a
+ * kernel of its own, see BB_VARIANT_PRESCALE).
  */
 int bb_rmsnorm_swiglu_ffn_t(const void* X, const void* g, const void* W1t,
                             const void* W3t, const void* W2t, void* Y,
