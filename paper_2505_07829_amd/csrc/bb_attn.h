@@ -150,7 +150,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p)
 #pragma unroll
         for (int j = 0; j < NIK; ++j) {
             const u32 off = W == 2 ? offKd[j] - (u32)(max(rowKd[j] - rmax, 0) * DK) : offKd[j];
-            load_to_lds16(reinterpret_cast<const char*>(Kb) + (u32)(2 * (off + (u32)(key0 * DK))), dK + (NIK * w + j) * 64);
+            (KSPLIT ? load_to_lds16_nt : load_to_lds16)(reinterpret_cast<const char*>(Kb) + (u32)(2 * (off + (u32)(key0 * DK))), dK + (NIK * w + j) * 64);
         }
     };
     auto dma_v = [&](int kt, u32x4* dV, auto WHICH) {
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p)
 #pragma unroll
         for (int j = 0; j < NIV; ++j) {
             const u32 off = W == 2 ? offVd[j] - (u32)(max(rowVd[j] - rmax, 0) * DV) : offVd[j];
-            load_to_lds16(reinterpret_cast<const char*>(Vb) + (u32)(2 * (off + (u32)(key0 * DV))), dV + (NIV * w + j) * 64);
+            (KSPLIT ? load_to_lds16_nt : load_to_lds16)(reinterpret_cast<const char*>(Vb) + (u32)(2 * (off + (u32)(key0 * DV))), dV + (NIV * w + j) * 64);
         }
     };
 

@@ -120,6 +120,10 @@ constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 __device__ __forceinline__ void load_to_lds16(const void* src, void* dst) {
     __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 16, 0, 0);
 }
+// the same with the non-temporal cache policy (data that is read once)
+__device__ __forceinline__ void load_to_lds16_nt(const void* src, void* dst) {
+    __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 16, 0, 2);
+}
 
 // LDS byte address of a pointer into a __shared__ array
 __device__ __forceinline__ u32 lds_addr(const void* q) {
