@@ -69,6 +69,11 @@ typedef enum bb_status {
  *                      K-map) through per-workgroup partial-sum slots that a
  *                      short phase adds up.  The hidden block (16 x F) passes
  *                      through a cache-resident scratch between the phases.
+ *                      The kernel synchronises its workgroups through counters
+ *                      in the workspace that only the kernels touch: a launch
+ *                      carries no host-side state and, once a first call has
+ *                      set up the workspace, may be captured into a HIP graph
+ *                      and replayed.
  * BB_VARIANT_UNFUSED   the initial block program (what the *_unfused entry points
  *                       run); a candidate of the measured selection below.
  * BB_VARIANT_PRESCALE  (FFN with M > 16; LN -> matmul) SNAPSHOT1 with the statistics loop as a

@@ -35,7 +35,6 @@ struct Workspace {
     size_t bytes = 0;
     bool user = false;
     size_t clean = 0;                  // leading bytes known to be zero
-    unsigned bar_count = 0;            // grid barriers completed so far (the barrier words only increase)
     int device = -1;
 } g_ws;
 
@@ -217,13 +216,14 @@ int validate_ln(const void* X, const void* gamma, const void* beta, const void* 
 
 // ------------------------------------------------------------ workspace plan
 struct StreamPlan {
-    size_t bar_off, zero_off, ppart_off, spart_off, h_off, ypart_off, zone_bytes, total_bytes;
+    size_t bar_off, zero_off, epoch_off, ppart_off, spart_off, h_off, ypart_off, zone_bytes, total_bytes;
     int Fp, nkb1, nfb, items1, per1, S1, nkb2, nnb, items2, per2, S2;
 };
 
 // Layout of the streaming kernels' scratch for G workgroups.  Only the "zone"
-// (barrier words, and a block of zeros that nothing ever writes) has to be zero
-// before the first call; the barrier words only ever increase.
+// (barrier words, a block of zeros that nothing ever writes, and the kernels' count
+// of completed grid barriers) has to be zero before the first call; the barrier
+// words and the count only ever increase, and only the kernels touch them.
 StreamPlan stream_plan(int64_t D, int64_t F, int G) {
     StreamPlan s;
     s.Fp = (int)((F + 127) / 128 * 128);
@@ -239,7 +239,8 @@ StreamPlan stream_plan(int64_t D, int64_t F, int G) {
     s.S2 = (s.nkb2 - 1) / s.per2 + 2;
     s.bar_off = 0;
     s.zero_off = align_up((size_t)BAR_WORDS * 4);               // 256 bytes that stay zero
-    s.zone_bytes = s.zero_off + kAlign;
+    s.epoch_off = s.zero_off + kAlign;                          // the kernels' count of completed grid barriers
+    s.zone_bytes = s.epoch_off + kAlign;
     s.ppart_off = s.zone_bytes;
     s.spart_off = s.ppart_off + align_up((size_t)s.nfb * s.S1 * 4096 * 4);
     s.h_off = s.spart_off + align_up((size_t)s.S1 * 16 * 4);
@@ -442,7 +443,6 @@ int prepare_barrier_zone(const StreamPlan& sp, hipStream_t st) {
     if (g_ws.clean < sp.zone_bytes) {
         if (int rc = fill_zero(g_ws.ptr, sp.zone_bytes, st)) return rc;
         g_ws.clean = sp.zone_bytes;
-        g_ws.bar_count = 0;
     }
     return BB_OK;
 }
@@ -468,7 +468,7 @@ int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u
     a.ypart = (float*)(base + sp.ypart_off);
     a.bar = (unsigned*)(base + sp.bar_off);
     a.zeros = (const u16*)(base + sp.zero_off);
-    a.bar_base = g_ws.bar_count;
+    a.epoch = (unsigned*)(base + sp.epoch_off);
     a.M = M; a.D = D; a.F = F; a.Fp = sp.Fp; a.eps = eps;
     a.nkb1 = sp.nkb1; a.nfb = sp.nfb; a.items1 = sp.items1; a.per1 = sp.per1; a.S1 = sp.S1;
     a.nkb2 = sp.nkb2; a.nnb = sp.nnb; a.items2 = sp.items2; a.per2 = sp.per2; a.S2 = sp.S2;
@@ -479,7 +479,6 @@ int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u
     hipLaunchKernelGGL(ffn_stream_kernel, dim3(G), dim3(STREAM_THREADS), 0, st, a);
     BB_HIP(hipGetLastError());
     prof_mark("ffn_stream", st);
-    g_ws.bar_count += 3u;   // grid barriers per call
     return BB_OK;
 }
 
@@ -534,7 +533,7 @@ int run_stream_t(const u16* X, const u16* g, const u16* W1t, const u16* W3t, con
     a.H = (u16*)(base + sp.h_off);
     a.bar = (unsigned*)(base + sp.bar_off);
     a.zeros = (const u16*)(base + sp.zero_off);
-    a.bar_base = g_ws.bar_count;
+    a.epoch = (unsigned*)(base + sp.epoch_off);
     a.M = M; a.D = D; a.F = F; a.Fp = sp.Fp; a.eps = eps;
     a.upw = tp.upw; a.cpw = tp.cpw; a.kblk = tp.kblk; a.cq2 = tp.cq2;
     a.red_off = tp.red_off; a.stat_off = tp.stat_off;
@@ -545,7 +544,6 @@ int run_stream_t(const u16* X, const u16* g, const u16* W1t, const u16* W3t, con
     hipLaunchKernelGGL(ffn_stream_t_kernel, dim3(G), dim3(STREAMT_THREADS), tp.lds, st, a);
     BB_HIP(hipGetLastError());
     prof_mark("ffn_stream_t", st);
-    g_ws.bar_count += 1u;   // one grid barrier per call
     return BB_OK;
 }
 

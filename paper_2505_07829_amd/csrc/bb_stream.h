@@ -56,7 +56,7 @@ struct StreamArgs {
     float* ypart;      // [nnb][S2][16][128] partial outputs
     const u16* zeros;  // 16 zero bytes in global memory: what a lane outside the matrices loads in phase 1
     unsigned* bar;     // BAR_WORDS barrier words (see grid_arrive), zero before the first call
-    unsigned bar_base; // grid barriers completed before this call
+    unsigned* epoch;   // one word next to them: grid barriers completed by earlier launches (kept by the kernels)
     int M, D, F, Fp;
     int nkb1, nfb, items1, per1, S1;   // phase 1: D/32 blocks, F/128 blocks, items, items per workgroup, slots
     int nkb2, nnb, items2, per2, S2;   // phase 2: F/32 blocks, D/128 blocks, ...
@@ -217,6 +217,13 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
     const int G = gridDim.x, b = blockIdx.x;
     constexpr int RS = 2 * 16 * 128;               // floats per wavefront in sm.red
 
+    // Grid barriers completed before this launch: the barrier words only ever increase, and the count
+    // lives in device memory (workgroup 0 advances it at the end), so the host keeps no state per
+    // launch and a launch may be replayed from a captured graph.  Every workgroup reads it before its
+    // first arrival; workgroup 0 writes it after the last barrier, i.e. after every arrival.
+    const unsigned bar_base =
+        __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+
     BB_STREAM_TRACE(0);
     // =====================  phase 1: partial pre-activations  =====================
     {
@@ -313,7 +320,7 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
     }
 
     BB_STREAM_TRACE(2);
-    grid_arrive(p.bar, p.bar_base + 1u);
+    grid_arrive(p.bar, bar_base + 1u);
 
     // ---- phase 2 work of this workgroup.  Wavefronts 1..3 request their first
     // weight blocks now, so HBM stays busy while wavefront 0 runs the short
@@ -338,7 +345,7 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
         prefetch2();
     } else {
         BB_STREAM_TRACE(3);
-        if (lane == 0) bar_poll(p.bar, p.bar_base + 1u);
+        if (lane == 0) bar_poll(p.bar, bar_base + 1u);
         BB_STREAM_TRACE(4);
         // =====================  phase 1b: hidden block  =====================
         const int groups_per_row = p.Fp / 8;                   // tasks: (row, 8 consecutive hidden units)
@@ -408,8 +415,8 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
         __builtin_amdgcn_s_waitcnt(0);                    // this wavefront's hidden stores are complete
         BB_STREAM_TRACE(8);
         if (lane == 0) {
-            bar_signal(p.bar, p.bar_base + 2u);
-            bar_poll(p.bar, p.bar_base + 2u);
+            bar_signal(p.bar, bar_base + 2u);
+            bar_poll(p.bar, bar_base + 2u);
         }
     }
     __syncthreads();
@@ -477,8 +484,11 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
     }
 
     BB_STREAM_TRACE(6);
-    grid_arrive(p.bar, p.bar_base + 3u);
-    if (t == 0) bar_poll(p.bar, p.bar_base + 3u);
+    grid_arrive(p.bar, bar_base + 3u);
+    if (t == 0) {
+        bar_poll(p.bar, bar_base + 3u);
+        if (b == 0) __hip_atomic_store(p.epoch, bar_base + 3u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     __syncthreads();
     BB_STREAM_TRACE(9);
 

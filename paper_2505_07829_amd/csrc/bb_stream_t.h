@@ -90,7 +90,7 @@ struct StreamTArgs {
                        // of a global variable the compiler would know that it can be read ahead of time, and turn
                        // the loads back into branches around the real ones.)
     unsigned* bar;     // barrier words (see grid_arrive), shared with the row-major streaming kernel
-    unsigned bar_base; // grid barriers completed before this call
+    unsigned* epoch;   // grid barriers completed by earlier launches (see ffn_stream_kernel)
     int M, D, F, Fp;
     int upw, cpw;      // hidden units / output columns per workgroup
     int kblk;          // model channels whose bf16(x g) LDS holds at a time: a multiple of 512
@@ -164,6 +164,9 @@ __global__ __launch_bounds__(STREAMT_THREADS) void ffn_stream_t_kernel(const Str
     u16* const xg = reinterpret_cast<u16*>(smem);                          // [16][xstride] bf16(x g)
     float* const red = reinterpret_cast<float*>(smem + p.red_off);         // [4][groups][2][64][4] / [4][groups][64][4]
     float* const stat = reinterpret_cast<float*>(smem + p.stat_off);       // [16] inverse norms, [4][16] partial sums of squares
+
+    const unsigned bar_base =
+        __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
 
     BB_STREAM_TRACE(0);
     // =====================  phase 1: hidden units [u0, u1)  =====================
@@ -332,7 +335,7 @@ __global__ __launch_bounds__(STREAMT_THREADS) void ffn_stream_t_kernel(const Str
         }
     }
     BB_STREAM_TRACE(2);
-    grid_arrive(p.bar, p.bar_base + 1u);
+    grid_arrive(p.bar, bar_base + 1u);
 
     // =====================  phase 2: output columns [c0, c1)  =====================
     const int c0 = min(p.D, b * p.cpw), c1 = min(p.D, c0 + p.cpw);
@@ -376,7 +379,10 @@ __global__ __launch_bounds__(STREAMT_THREADS) void ffn_stream_t_kernel(const Str
 #pragma unroll
         for (int u = 0; u < STREAMT_NPF2; ++u) issue_w(it[u]);
         BB_STREAM_TRACE(3);
-        if (t == 0) bar_poll(p.bar, p.bar_base + 1u);
+        if (t == 0) {
+            bar_poll(p.bar, bar_base + 1u);
+            if (b == 0) __hip_atomic_store(p.epoch, bar_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         __syncthreads();
         if (BB_ST_FENCE) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         BB_STREAM_TRACE(4);

@@ -509,3 +509,40 @@ def test_transposed_stream_large_activations():
     Y = bb.bb_rmsnorm_swiglu_ffn_t(*dev((X, g, tr(W1), tr(W3), tr(W2))), 1e-6)
     torch.cuda.synchronize()
     assert row_rel_err(Y, ref) <= TOL
+
+
+# ------------------------------------------------ the streaming kernels keep no host-side state per launch
+@pytest.mark.parametrize("transposed", [False, True])
+def test_stream_kernels_replay_from_a_captured_graph(transposed):
+    # the grid barriers' epoch lives in device memory, so a captured launch can be replayed: several
+    # replays, with eager calls of both streaming kernels and new inputs in between, each compared with
+    # the eager result on the same inputs
+    M, D, F = 16, 1024, 2816
+    X, g, W1, W3, W2 = bb_inputs.make_ffn(M, D, F, seed=31)
+    d = dev((X, g, W1, W3, W2))
+    dt = [d[0], d[1], tr(d[2]), tr(d[3]), tr(d[4])]
+    call = (lambda Y: bb.bb_rmsnorm_swiglu_ffn_t(*dt, 1e-6, Y=Y)) if transposed else \
+           (lambda Y: bb.bb_rmsnorm_swiglu_ffn(*d, 1e-6, Y=Y))
+    out_g = torch.empty((M, D), dtype=torch.bfloat16, device="cuda")
+    out_e = torch.empty_like(out_g)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call(out_g)                                    # warm-up: workspace, kernel attributes
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call(out_g)
+    for rep in range(4):
+        newX = bb_inputs.make_ffn(M, D, F, seed=40 + rep)[0].cuda()
+        d[0].copy_(newX)
+        graph.replay()
+        torch.cuda.synchronize()
+        call(out_e)                                    # eager, same inputs
+        bb.bb_rmsnorm_swiglu_ffn(*d, 1e-6)             # and the other layout's kernel shares the barrier words
+        bb.bb_rmsnorm_swiglu_ffn_t(*dt, 1e-6)
+        torch.cuda.synchronize()
+        assert torch.equal(out_g.view(torch.uint16), out_e.view(torch.uint16)), rep
+    ref = orc.rmsnorm_swiglu_ffn(d[0].cpu(), g, W1, W3, W2, 1e-6)
+    assert row_rel_err(out_g, ref) <= TOL
