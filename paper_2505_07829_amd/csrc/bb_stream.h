@@ -227,23 +227,28 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
     BB_STREAM_TRACE(0);
     // =====================  phase 1: partial pre-activations  =====================
     {
-        int i = b * p.per1;
-        const int iend = min(i + p.per1, p.items1);
-        while (i < iend) {                         // one segment = one block of 128 hidden units
-            const int fb = i / p.nkb1, kb0 = i % p.nkb1;
-            const int kb1 = min(p.nkb1, kb0 + (iend - i));
-            const int slot = b - (fb * p.nkb1) / p.per1;
-            const int col = 128 * fb + 8 * jn;
-            const bool col_ok = col < p.F;
+        // The workgroup's items [i0, iend) lie in one or more blocks of 128 hidden units ("segments", each
+        // with its own partial tile and slot).  Wavefront w takes items i0 + w, i0 + w + 4, ... as ONE stream:
+        // the request queue runs on across a segment boundary (draining and refilling it there cost the
+        // workgroups with a boundary 3-6 us; they were the last to reach the barrier).  Every wavefront takes
+        // part in the flush of every segment, with zeros if it had no item there.
+        const int i0 = b * p.per1;
+        const int iend = min(i0 + p.per1, p.items1);
+        if (i0 < iend) {
+            const int fb_last = (iend - 1) / p.nkb1;
+            int cur_fb = i0 / p.nkb1;
             f32x4 accP[8], accQ[8];
 #pragma unroll
             for (int c = 0; c < 8; ++c) { accP[c] = f32x4{0, 0, 0, 0}; accQ[c] = f32x4{0, 0, 0, 0}; }
             float ssq = 0.f;
             StreamItem1 it[STREAM_NP1];
-            // (every load is unconditional: a lane outside the matrices or past the segment reads the
+            // (every load is unconditional: a lane outside the matrices or past the last item reads the
             // zero chunk instead, so no load stands inside a branch)
-            auto issue = [&](int kb, StreamItem1& r) {
-                const bool live = kb < kb1;
+            auto issue = [&](int id, StreamItem1& r) {
+                const bool live = id < iend;
+                const int fb = id / p.nkb1, kb = id - fb * p.nkb1;
+                const int col = 128 * fb + 8 * jn;
+                const bool col_ok = col < p.F;
                 const int d0 = 32 * kb + 8 * g4;
 #pragma unroll
                 for (int i2 = 0; i2 < 8; ++i2) {
@@ -256,16 +261,48 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
                 stream_load16(r.rx, (ok && jn < p.M) ? p.X + (size_t)jn * p.D + d0 : p.zeros);
                 stream_load16(r.rg, ok ? p.g + d0 : p.zeros);
             };
-            // the wavefronts take the items round robin: kb0 + w, kb0 + w + 4, ...
+            // adds the 4 wavefronts' tiles of segment fb in LDS, stores the workgroup's partial tile in its
+            // slot, and clears the accumulators
+            auto flush = [&](int fb) {
+                const int slot = b - (fb * p.nkb1) / p.per1;
+                stash_tile(sm.red[w][0], accP, lane);
+                stash_tile(sm.red[w][1], accQ, lane);
+                __syncthreads();
+                float* dst = p.ppart + (size_t)(fb * p.S1 + slot) * RS;
 #pragma unroll
-            for (int u = 0; u < STREAM_NP1; ++u) issue(kb0 + w + 4 * u, it[u]);
-            for (int kbb = kb0 + w; kbb < kb1; kbb += 4 * STREAM_NP1) {
+                for (int j = 0; j < 4; ++j) {
+                    const int i4 = t + STREAM_THREADS * j;        // float4 index in [2][16][128]
+                    cstore16f(dst + 4 * i4, sum4(&sm.red[0][0][0][0], RS, i4));
+                }
+                if (fb == 0) {   // sum x^2 is counted once per model channel: by the items of hidden block 0
+                    ssq += __shfl_xor(ssq, 16);
+                    ssq += __shfl_xor(ssq, 32);
+                    __syncthreads();
+                    if (lane < 16) sm.red[w][0][0][lane] = ssq;
+                    __syncthreads();
+                    if (t < 16)
+                        __hip_atomic_store(p.spart + slot * 16 + t,
+                                           sm.red[0][0][0][t] + sm.red[1][0][0][t] + sm.red[2][0][0][t] + sm.red[3][0][0][t],
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                __syncthreads();
+#pragma unroll
+                for (int c = 0; c < 8; ++c) { accP[c] = f32x4{0, 0, 0, 0}; accQ[c] = f32x4{0, 0, 0, 0}; }
+                ssq = 0.f;
+            };
+#pragma unroll
+            for (int u = 0; u < STREAM_NP1; ++u) issue(i0 + w + 4 * u, it[u]);
+            for (int id0 = i0 + w; id0 < iend; id0 += 4 * STREAM_NP1) {
 #pragma unroll
                 for (int u = 0; u < STREAM_NP1; ++u) {
-                    // (past the segment the item is all zeros and adds nothing)
-                    const int kb = kbb + 4 * u;
+                    // (past the last item the item is all zeros and adds nothing)
+                    const int id = id0 + 4 * u;
+                    if (id < iend) {
+                        const int fbi = id / p.nkb1;
+                        while (cur_fb < fbi) flush(cur_fb++);     // (the stores of a flush only add to the count
+                    }                                             //  the wait below looks at: it waits longer)
                     stream_ready<STREAM_ITEM1_LOADS * (STREAM_NP1 - 1)>(it[u]);
-                    // consume the registers of item kb, then refill them
+                    // consume the registers of the item, then refill them
                     Chunk xa;
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
@@ -277,7 +314,7 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
                     u32x4 t1[8], t3[8];
                     transpose8x8(it[u].r1, t1);
                     transpose8x8(it[u].r3, t3);
-                    issue(kb + 4 * STREAM_NP1, it[u]);
+                    issue(id + 4 * STREAM_NP1, it[u]);
 #pragma unroll
                     for (int c = 0; c < 8; ++c) {
                         Chunk b1, b3;
@@ -288,34 +325,12 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
                     }
                 }
             }
-            // the requests past the segment are still in flight: their registers stay reserved until they
+            // the requests past the last item are still in flight: their registers stay reserved until they
             // have landed (a register reused earlier would be overwritten when its load returns)
 #pragma unroll
             for (int u = 0; u < STREAM_NP1; ++u) stream_ready<0>(it[u]);
             BB_STREAM_TRACE(1);
-            // ---- add the 4 wavefronts in LDS and store the workgroup's partial tile in its slot
-            stash_tile(sm.red[w][0], accP, lane);
-            stash_tile(sm.red[w][1], accQ, lane);
-            __syncthreads();
-            float* dst = p.ppart + (size_t)(fb * p.S1 + slot) * RS;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int i4 = t + STREAM_THREADS * j;        // float4 index in [2][16][128]
-                cstore16f(dst + 4 * i4, sum4(&sm.red[0][0][0][0], RS, i4));
-            }
-            if (fb == 0) {   // sum x^2 is counted once per model channel: by the items of hidden block 0
-                ssq += __shfl_xor(ssq, 16);
-                ssq += __shfl_xor(ssq, 32);
-                __syncthreads();
-                if (lane < 16) sm.red[w][0][0][lane] = ssq;
-                __syncthreads();
-                if (t < 16)
-                    __hip_atomic_store(p.spart + slot * 16 + t,
-                                       sm.red[0][0][0][t] + sm.red[1][0][0][t] + sm.red[2][0][0][t] + sm.red[3][0][0][t],
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-            __syncthreads();
-            i += kb1 - kb0;
+            while (cur_fb <= fb_last) flush(cur_fb++);
         }
     }
 
