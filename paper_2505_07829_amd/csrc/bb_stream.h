@@ -99,42 +99,43 @@ __device__ __forceinline__ f32x4 sum4(const float* red0, int stride, int i4) {
 
 // Grid barrier in two halves.  All workgroups of the grid must be resident.
 // 256 simultaneous atomics and polls on ONE word serialise at its memory
-// channel (measured: > 10 us), so arrivals are counted in two levels: 16 groups
-// of workgroups (id mod 16) each own an arrival word, the last arriver of a
-// group bumps the top word, the last group's arriver publishes the barrier
-// number in 16 flag words, and a workgroup polls only its group's flag.  Every
-// word sits in its own 256-byte block.  All words only ever increase (the host
-// passes the number of barriers completed before the call), so nothing needs
-// resetting; the wait gives up after about two seconds.
-// Only thread 0 talks to the other workgroups, after the whole workgroup's
-// stores have been acknowledged.
+// channel (measured: > 10 us), so arrivals are counted in 16 groups of
+// workgroups (id mod 16), each with an arrival word; the last arriver of a
+// group publishes the barrier number in the group's flag word, and a waiting
+// wavefront reads all 16 flags with one load (lane j reads flag j).  The
+// critical path is one returning atomic, one store and one load (a second
+// counting level on top of the groups cost another atomic round trip, about
+// 1 us per barrier).  Every word sits in its own 256-byte block.  All words only
+// ever increase (the kernels keep the number of completed barriers next to
+// them), so nothing needs resetting; the wait gives up after about two seconds.
+// Only thread 0 signals, after the whole workgroup's stores have been
+// acknowledged.
 constexpr int BAR_GROUPS = 16;
 constexpr int BAR_STRIDE = 64;                 // words between barrier words (256 bytes)
 constexpr int BAR_WORDS = (2 * BAR_GROUPS + 2) * BAR_STRIDE;
-// word layout: group arrival g -> g, top -> 16, flag g -> 17 + g, timeout marker -> 33 (times BAR_STRIDE)
+// word layout: group arrival g -> g, (16 unused), flag g -> 17 + g, timeout marker -> 33 (times BAR_STRIDE)
 
 // thread-level half: count this workgroup's arrival at barrier number k (>= 1)
 __device__ __forceinline__ void bar_signal(unsigned* bar, unsigned k) {
     const unsigned G = gridDim.x, g = blockIdx.x % BAR_GROUPS;
-    const unsigned ngroups = G < BAR_GROUPS ? G : BAR_GROUPS;
     const unsigned gsize = (G - g + BAR_GROUPS - 1) / BAR_GROUPS;
     const unsigned old = __hip_atomic_fetch_add(bar + g * BAR_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (old + 1u == gsize * k) {
-        const unsigned oldt = __hip_atomic_fetch_add(bar + BAR_GROUPS * BAR_STRIDE, 1u, __ATOMIC_RELAXED,
-                                                     __HIP_MEMORY_SCOPE_AGENT);
-        if (oldt + 1u == ngroups * k)
-            for (unsigned j = 0; j < ngroups; ++j)
-                __hip_atomic_store(bar + (BAR_GROUPS + 1 + j) * BAR_STRIDE, k, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-    }
+    if (old + 1u == gsize * k)
+        __hip_atomic_store(bar + (BAR_GROUPS + 1 + g) * BAR_STRIDE, k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// thread-level half: wait until barrier number k has been published (bounded)
-__device__ __forceinline__ void bar_poll(unsigned* bar, unsigned k) {
-    const unsigned* flag = bar + (BAR_GROUPS + 1 + blockIdx.x % BAR_GROUPS) * BAR_STRIDE;
+// wavefront-level half (all 64 lanes call it): wait until every group has published barrier number k (bounded)
+__device__ __forceinline__ void bar_poll_wave(unsigned* bar, unsigned k) {
+    const unsigned G = gridDim.x, ngroups = G < BAR_GROUPS ? G : BAR_GROUPS;
+    const unsigned l = threadIdx.x & 63;
     unsigned spins = 0;
-    while ((int)(__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - k) < 0) {
+    while (true) {
+        unsigned v = k;                        // lanes without a group count as done
+        if (l < ngroups)
+            v = __hip_atomic_load(bar + (BAR_GROUPS + 1 + l) * BAR_STRIDE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (__all((int)(v - k) >= 0)) break;
         if (++spins > 8000000u) {
-            __hip_atomic_store(bar + (2 * BAR_GROUPS + 1) * BAR_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (l == 0)
+                __hip_atomic_store(bar + (2 * BAR_GROUPS + 1) * BAR_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             break;
         }
         __builtin_amdgcn_s_sleep(2);
@@ -360,7 +361,7 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
         prefetch2();
     } else {
         BB_STREAM_TRACE(3);
-        if (lane == 0) bar_poll(p.bar, bar_base + 1u);
+        bar_poll_wave(p.bar, bar_base + 1u);
         BB_STREAM_TRACE(4);
         // =====================  phase 1b: hidden block  =====================
         const int groups_per_row = p.Fp / 8;                   // tasks: (row, 8 consecutive hidden units)
@@ -429,10 +430,8 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __builtin_amdgcn_s_waitcnt(0);                    // this wavefront's hidden stores are complete
         BB_STREAM_TRACE(8);
-        if (lane == 0) {
-            bar_signal(p.bar, bar_base + 2u);
-            bar_poll(p.bar, bar_base + 2u);
-        }
+        if (lane == 0) bar_signal(p.bar, bar_base + 2u);
+        bar_poll_wave(p.bar, bar_base + 2u);
     }
     __syncthreads();
     if (w == 0) prefetch2();
@@ -500,9 +499,10 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
 
     BB_STREAM_TRACE(6);
     grid_arrive(p.bar, bar_base + 3u);
-    if (t == 0) {
-        bar_poll(p.bar, bar_base + 3u);
-        if (b == 0) __hip_atomic_store(p.epoch, bar_base + 3u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (w == 0) {
+        bar_poll_wave(p.bar, bar_base + 3u);
+        if (lane == 0 && b == 0)
+            __hip_atomic_store(p.epoch, bar_base + 3u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     BB_STREAM_TRACE(9);

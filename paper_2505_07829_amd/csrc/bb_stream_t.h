@@ -379,9 +379,10 @@ __global__ __launch_bounds__(STREAMT_THREADS) void ffn_stream_t_kernel(const Str
 #pragma unroll
         for (int u = 0; u < STREAMT_NPF2; ++u) issue_w(it[u]);
         BB_STREAM_TRACE(3);
-        if (t == 0) {
-            bar_poll(p.bar, bar_base + 1u);
-            if (b == 0) __hip_atomic_store(p.epoch, bar_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (w == 0) {
+            bar_poll_wave(p.bar, bar_base + 1u);
+            if (lane == 0 && b == 0)
+                __hip_atomic_store(p.epoch, bar_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         __syncthreads();
         if (BB_ST_FENCE) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
