@@ -112,6 +112,11 @@ struct TuneKey {
 };
 std::map<TuneKey, int> g_tuned;
 
+// The streaming kernel keeps per-workgroup state for at most 64 blocks of 128 output columns
+// (a workgroup's share of the second phase spans at most D / 128 / workgroups + 2 of them; the rule of
+// thumb assumes no fewer than 64 workgroups, run_stream checks the real number).
+bool stream_fits(int64_t D) { return (D + 127) / 128 / 64 + 2 <= 64; }
+
 // AUTO: a measured selection for exactly this shape if there is one, else the rule of thumb
 // (weight-streaming kernel up to kStreamMaxM rows, tiled kernels beyond; LN always fused)
 int auto_variant(int op, int64_t M, int64_t D, int64_t FN) {
@@ -120,7 +125,8 @@ int auto_variant(int op, int64_t M, int64_t D, int64_t FN) {
     // (measured on D = 4096, F = 11008: from 256 rows on the separate statistics pass beats the
     // statistics inside the product loop by 7-9 %; below, the split contraction needs the fused form)
     if (op == BB_OP_RMSNORM_SWIGLU_FFN)
-        return (M <= kStreamMaxM) ? BB_VARIANT_STREAM : (M >= kPrescaleMinM ? BB_VARIANT_PRESCALE : BB_VARIANT_SNAPSHOT1);
+        return (M <= kStreamMaxM && stream_fits(D)) ? BB_VARIANT_STREAM
+                                                    : (M >= kPrescaleMinM ? BB_VARIANT_PRESCALE : BB_VARIANT_SNAPSHOT1);
     return M >= kPrescaleMinM ? BB_VARIANT_PRESCALE : BB_VARIANT_SNAPSHOT1;
 }
 
@@ -216,7 +222,7 @@ int validate_ln(const void* X, const void* gamma, const void* beta, const void* 
 
 // ------------------------------------------------------------ workspace plan
 struct StreamPlan {
-    size_t bar_off, zero_off, epoch_off, ppart_off, spart_off, h_off, ypart_off, zone_bytes, total_bytes;
+    size_t bar_off, zero_off, epoch_off, ppart_off, spart_off, h_off, ypart_off, cnt_off, zone_bytes, total_bytes;
     int Fp, nkb1, nfb, items1, per1, S1, nkb2, nnb, items2, per2, S2;
 };
 
@@ -245,7 +251,8 @@ StreamPlan stream_plan(int64_t D, int64_t F, int G) {
     s.spart_off = s.ppart_off + align_up((size_t)s.nfb * s.S1 * 4096 * 4);
     s.h_off = s.spart_off + align_up((size_t)s.S1 * 16 * 4);
     s.ypart_off = s.h_off + align_up((size_t)16 * s.Fp * 2);
-    s.total_bytes = s.ypart_off + align_up((size_t)s.nnb * s.S2 * 2048 * 4);
+    s.cnt_off = s.ypart_off + align_up((size_t)s.nnb * s.S2 * 2048 * 4);
+    s.total_bytes = s.cnt_off + align_up((size_t)s.nnb * 4);
     return s;
 }
 
@@ -458,6 +465,7 @@ int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u
     if (resident < 1) return BB_ERR_VARIANT;   // the grid barrier needs every workgroup resident
     const int G = std::min(cus, kPlanCUs);
     const StreamPlan sp = stream_plan(D, F, G);
+    if ((sp.per2 - 1) / sp.nkb2 + 2 > 64) return BB_ERR_VARIANT;   // (see stream_fits)
     char* base = (char*)g_ws.ptr;
     if (int rc = prepare_barrier_zone(sp, st)) return rc;
     StreamArgs a;
@@ -466,6 +474,7 @@ int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u
     a.spart = (float*)(base + sp.spart_off);
     a.H = (u16*)(base + sp.h_off);
     a.ypart = (float*)(base + sp.ypart_off);
+    a.cnt = (unsigned*)(base + sp.cnt_off);
     a.bar = (unsigned*)(base + sp.bar_off);
     a.zeros = (const u16*)(base + sp.zero_off);
     a.epoch = (unsigned*)(base + sp.epoch_off);

@@ -17,7 +17,8 @@
 //     resident scratch.
 //   phase 2 (N-map): work item = (block of 32 hidden units, block of 128
 //     output columns), again dealt out evenly; partial outputs go to slots.
-//   phase 2b: partial outputs are added and stored as bf16.
+//   phase 2b: the workgroup that is the last to deliver its partial tile of a
+//     block of output columns adds the tiles (in slot order) and stores bf16.
 //
 // The parallel reductions use per-workgroup slots instead of atomics: fp32
 // atomics run at about one per L2 channel per clock on this part and stall the
@@ -54,6 +55,8 @@ struct StreamArgs {
     float* spart;      // [S1][16] partial row sums of squares
     u16* H;            // [16][Fp] hidden block, bf16
     float* ypart;      // [nnb][S2][16][128] partial outputs
+    unsigned* cnt;     // [nnb] arrival counters of the output blocks (any initial values: used relative to their
+                       // value at the start of the launch)
     const u16* zeros;  // 16 zero bytes in global memory: what a lane outside the matrices loads in phase 1
     unsigned* bar;     // BAR_WORDS barrier words (see grid_arrive), zero before the first call
     unsigned* epoch;   // one word next to them: grid barriers completed by earlier launches (kept by the kernels)
@@ -65,6 +68,8 @@ struct StreamArgs {
 
 struct StreamSmem {
     float red[4][2][16][128];   // per-wavefront partial tiles
+    unsigned segbase[64];       // arrival counters of this workgroup's output blocks at the start of the launch
+    unsigned last;              // this workgroup delivered the last partial tile of the block at hand
 };
 
 // loads the 8 rows x 8 columns block of a row-major matrix this lane owns
@@ -430,8 +435,18 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __builtin_amdgcn_s_waitcnt(0);                    // this wavefront's hidden stores are complete
         BB_STREAM_TRACE(8);
+        // Where the output blocks' arrival counters stand before any workgroup can arrive in this launch
+        // (arrivals come after barrier 2, which this workgroup has not signalled yet): lane j reads the
+        // counter of this workgroup's j-th block of output columns.
+        if (i2 < iend2) {
+            const int nb_first = i2 / p.nkb2, nseg = (iend2 - 1) / p.nkb2 - nb_first + 1;     // (the host made sure nseg <= 64)
+            if (lane < nseg)
+                sm.segbase[lane] = __hip_atomic_load(p.cnt + nb_first + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         if (lane == 0) bar_signal(p.bar, bar_base + 2u);
         bar_poll_wave(p.bar, bar_base + 2u);
+        if (lane == 0 && b == 0)       // (every workgroup read the count before its first arrival)
+            __hip_atomic_store(p.epoch, bar_base + 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     if (w == 0) prefetch2();
@@ -492,53 +507,51 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
                 const int i4 = t + STREAM_THREADS * j;        // float4 index in [16][128]
                 cstore16f(dst + 4 * i4, sum4(&sm.red[0][0][0][0], RS, i4));
             }
+            // ---- phase 2b.  The partial tile is complete in memory (stores acknowledged), then thread 0
+            // counts the delivery; the workgroup whose delivery is the last one of the block adds the
+            // tiles of all slots in slot order (so the result does not depend on who is last), adds
+            // the residual and stores the block's output.  No grid barrier.
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            const int first = (nb * p.nkb2) / p.per2;
+            const int ns = min(G - 1, ((nb + 1) * p.nkb2 - 1) / p.per2) - first + 1;      // slots of this block
+            if (t == 0) {
+                const unsigned old = __hip_atomic_fetch_add(p.cnt + nb, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                sm.last = (old + 1u - sm.segbase[nb - i2 / p.nkb2] == (unsigned)ns) ? 1u : 0u;
+            }
+            __syncthreads();
+            if (sm.last) {
+                const int row = t >> 4, cc = 8 * (t & 15);            // task: (row, 8 consecutive columns of the block)
+                const int c0 = 128 * nb + cc;
+                if (row < p.M && c0 < p.D) {
+                    const float* src0 = p.ypart + (size_t)nb * p.S2 * 2048 + row * 128 + cc;
+                    f32x4 y0 = {0, 0, 0, 0}, y1 = y0;
+                    for (int s0 = 0; s0 < ns; s0 += 8) {              // eight slots' loads in flight together
+                        f32x4 v[8][2];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const float* src = src0 + (size_t)(s0 + u) * 2048;
+                            const bool ok = s0 + u < ns;
+                            const f32x4 z = {0, 0, 0, 0};
+                            v[u][0] = ok ? cload16f(src) : z;
+                            v[u][1] = ok ? cload16f(src + 4) : z;
+                        }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) { y0 += v[u][0]; y1 += v[u][1]; }
+                    }
+                    if (p.R != nullptr) {
+                        const u32x4 rr = ldg16(p.R + (size_t)row * p.D + c0);
+                        y0 += f32x4{bf_lo(rr[0]), bf_hi(rr[0]), bf_lo(rr[1]), bf_hi(rr[1])};
+                        y1 += f32x4{bf_lo(rr[2]), bf_hi(rr[2]), bf_lo(rr[3]), bf_hi(rr[3])};
+                    }
+                    const u32x4 o = {pack_bf16(y0[0], y0[1]), pack_bf16(y0[2], y0[3]), pack_bf16(y1[0], y1[1]),
+                                     pack_bf16(y1[2], y1[3])};
+                    *reinterpret_cast<u32x4*>(p.Y + (size_t)row * p.D + c0) = o;
+                }
+            }
             __syncthreads();
             i += kb1 - kb0;
-        }
-    }
-
-    BB_STREAM_TRACE(6);
-    grid_arrive(p.bar, bar_base + 3u);
-    if (w == 0) {
-        bar_poll_wave(p.bar, bar_base + 3u);
-        if (lane == 0 && b == 0)
-            __hip_atomic_store(p.epoch, bar_base + 3u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __syncthreads();
-    BB_STREAM_TRACE(9);
-
-    // =====================  phase 2b: output  =====================
-    {
-        const int groups_per_row = p.D / 8;                    // tasks: (row, 8 consecutive columns)
-        const int total = p.M * groups_per_row;
-        for (int idx = b * STREAM_THREADS + t; idx < total; idx += G * STREAM_THREADS) {
-            const int row = idx / groups_per_row, c0 = 8 * (idx % groups_per_row);
-            const int nb = c0 >> 7, cc = c0 & 127;
-            const int first = (nb * p.nkb2) / p.per2;
-            const int ns = min(G - 1, ((nb + 1) * p.nkb2 - 1) / p.per2) - first + 1;
-            const float* src0 = p.ypart + (size_t)nb * p.S2 * 2048 + row * 128 + cc;
-            f32x4 y0 = {0, 0, 0, 0}, y1 = y0;
-            for (int s0 = 0; s0 < ns; s0 += 8) {                 // eight slots' loads in flight together
-                f32x4 v[8][2];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const float* src = src0 + (size_t)(s0 + u) * 2048;
-                    const bool ok = s0 + u < ns;
-                    const f32x4 z = {0, 0, 0, 0};
-                    v[u][0] = ok ? cload16f(src) : z;
-                    v[u][1] = ok ? cload16f(src + 4) : z;
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u) { y0 += v[u][0]; y1 += v[u][1]; }
-            }
-            if (p.R != nullptr) {
-                const u32x4 rr = ldg16(p.R + (size_t)row * p.D + c0);
-                y0 += f32x4{bf_lo(rr[0]), bf_hi(rr[0]), bf_lo(rr[1]), bf_hi(rr[1])};
-                y1 += f32x4{bf_lo(rr[2]), bf_hi(rr[2]), bf_lo(rr[3]), bf_hi(rr[3])};
-            }
-            const u32x4 o = {pack_bf16(y0[0], y0[1]), pack_bf16(y0[2], y0[3]), pack_bf16(y1[0], y1[1]),
-                             pack_bf16(y1[2], y1[3])};
-            *reinterpret_cast<u32x4*>(p.Y + (size_t)row * p.D + c0) = o;
         }
     }
     BB_STREAM_TRACE(7);
