@@ -35,6 +35,7 @@ struct Workspace {
     size_t bytes = 0;
     bool user = false;
     size_t clean = 0;                  // leading bytes known to be zero
+    size_t attn_zone = 0;              // leading bytes that hold arrival counters of bb_attention, all zero
     int device = -1;
 } g_ws;
 
@@ -300,6 +301,13 @@ size_t split_bytes(int mode, int64_t M, int64_t N, int64_t K, int cus) {
 // Key splits of the attention kernel for `wgs` (problem, query block) pairs and nt key blocks:
 // the largest divisor of nt that keeps about two workgroups per compute unit and at least two
 // key blocks per workgroup; 1 = no split (enough workgroups already, or a short sequence).
+// split keys: with at most this many query rows per problem, the last workgroup to arrive adds the partial
+// results.  (Measured, 4096 keys, back-to-back calls: one row 11.9 -> 9.2 us for 1 or 2 problems, 11.9 -> 11.4 for
+// 8, no difference for 32; 4 rows and more are slower than the second launch, which has a workgroup per row.)
+constexpr int64_t kAttnFusedCombineRows = 1;
+// arrival counters of the split-key kernel, one per (problem, block of 128 queries), at the workspace's start
+size_t attn_zone_bytes(int64_t B, int64_t M) { return align_up((size_t)B * ((M + 127) / 128) * 4); }
+
 int attn_key_splits(int64_t wgs, int64_t nt, int cus) {
     if (wgs * 2 > cus || nt < 8) return 1;
     const int64_t target = std::min<int64_t>((2 * (int64_t)cus) / wgs, nt / 2);
@@ -365,6 +373,7 @@ int fill_zero(void* p, size_t bytes, hipStream_t st) {
 // scratch region [off, off+len) is about to be written: it is no longer zero
 void mark_dirty(size_t off) {
     if (off < g_ws.clean) g_ws.clean = off;
+    if (off < g_ws.attn_zone) g_ws.attn_zone = 0;
 }
 
 // ------------------------------------------------------------------- launches
@@ -447,6 +456,7 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
 
 // the barrier words of the streaming kernels must be zero before their first use in a workspace
 int prepare_barrier_zone(const StreamPlan& sp, hipStream_t st) {
+    g_ws.attn_zone = 0;                // (the streaming kernels leave their own words there)
     if (g_ws.clean < sp.zone_bytes) {
         if (int rc = fill_zero(g_ws.ptr, sp.zone_bytes, st)) return rc;
         g_ws.clean = sp.zone_bytes;
@@ -884,13 +894,31 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
     a.nt_split = (int)(nt_all / ksplit);
     a.part = nullptr;
     a.ml = nullptr;
+    a.cnt = nullptr;
+    // one query per problem (decoding): the last workgroup of a problem to finish adds the partial
+    // results itself; else a second launch does, with a workgroup per row
+    const bool fused_combine = ksplit > 1 && M <= kAttnFusedCombineRows;
     if (ksplit > 1) {
         const size_t rows = (size_t)B * M;
+        const size_t zone = attn_zone_bytes(B, M);
         const size_t pbytes = align_up(rows * ksplit * dv * 4);
-        if (int rc = ensure_workspace(pbytes + align_up(rows * ksplit * 8))) return rc;
-        mark_dirty(0);
-        a.part = (float*)g_ws.ptr;
-        a.ml = (float*)((char*)g_ws.ptr + pbytes);
+        if (int rc = ensure_workspace(zone + pbytes + align_up(rows * ksplit * 8))) return rc;
+        if (fused_combine) {
+            // counters: zero before their first use; every launch leaves them zero again
+            const size_t had = g_ws.attn_zone;
+            mark_dirty(0);
+            if (had < zone) {
+                if (int rc = fill_zero(g_ws.ptr, zone, st)) return rc;
+                g_ws.attn_zone = zone;
+            } else {
+                g_ws.attn_zone = had;
+            }
+            a.cnt = (unsigned*)g_ws.ptr;
+        } else {
+            mark_dirty(0);
+        }
+        a.part = (float*)((char*)g_ws.ptr + zone);
+        a.ml = (float*)((char*)g_ws.ptr + zone + pbytes);
     }
     const dim3 grid((unsigned)(8 * a.wgs_per_xcd)), block((unsigned)(64 * nw));
     prof_begin(st);
@@ -910,8 +938,9 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
             else if (tail == 2) hipLaunchKernelGGL((attention_kernel<DK, DV, 2, 4, true>), grid, block, 0, st, a);
             else if (tail == 3) hipLaunchKernelGGL((attention_kernel<DK, DV, 3, 4, true>), grid, block, 0, st, a);
             else hipLaunchKernelGGL((attention_kernel<DK, DV, 4, 4, true>), grid, block, 0, st, a);
-            hipLaunchKernelGGL((attention_combine_kernel<DV>), dim3((unsigned)(B * M)), dim3(64), 0, st,
-                               (const float*)a.part, (const float*)a.ml, a.O, ksplit, a.c);
+            if (!fused_combine)
+                hipLaunchKernelGGL((attention_combine_kernel<DV>), dim3((unsigned)(B * M)), dim3(64), 0, st,
+                                   (const float*)a.part, (const float*)a.ml, a.O, ksplit, a.c);
         } else if (nw == 8) {
             go_nw(std::integral_constant<int, 8>{});
         } else {
@@ -934,7 +963,7 @@ size_t bb_attention_workspace_bytes(int64_t B, int64_t M, int64_t N, int64_t d, 
     const int s = attn_key_splits(B * ((M + 127) / 128), (N + ATTN_BK - 1) / ATTN_BK, kPlanCUs);
     if (s < 2) return 0;
     const size_t rows = (size_t)B * M;
-    return align_up(rows * s * dv * 4) + align_up(rows * s * 8);
+    return attn_zone_bytes(B, M) + align_up(rows * s * dv * 4) + align_up(rows * s * 8);
 }
 
 int bb_rmsnorm_swiglu_ffn_unfused(const void* X, const void* g, const void* W1, const void* W3,

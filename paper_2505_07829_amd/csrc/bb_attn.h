@@ -51,6 +51,9 @@ struct AttnArgs {
     int nsplit, nt_split;
     float* part;        // [B M][nsplit][DV]
     float* ml;          // [B M][nsplit][2]
+    // arrival counters, one per (problem, query block), zero between launches; nullptr: the partial
+    // results are added by attention_combine_kernel instead of by the last workgroup to arrive
+    unsigned* cnt;
 };
 
 // a workgroup has NW = 4 or 8 wavefronts of 32 queries each
@@ -71,6 +74,62 @@ __device__ __forceinline__ int attn_swz_tr(int row) {
     return CPR == 16 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
 }
 
+// Adds the nsplit partial results of a query row.  Every partial result is a
+// pair (significands O_s and l_s, row exponent m_s); two pairs are added by
+// bringing both to the larger exponent (Appendix), and the quotient of the
+// totals is rounded to bf16.  One wavefront per row: lane = (group of 8 output
+// columns, phase); a phase adds every (64 / groups)-th partial result, then the
+// phases are added across lanes.  The partial results are read with agent-scope
+// loads: they may have been written by other workgroups of the same launch.
+template <int DV>
+__device__ __forceinline__ void attention_combine_row(const float* part, const float* ml, u16* O, size_t row,
+                                                      int nsplit, float c, int lane) {
+    constexpr int G = DV / 8, NPH = 64 / G;
+    const int cg = lane % G, ph = lane / G;
+    float z = -INFINITY, l = 0.f;
+    f32x4 a0 = {0, 0, 0, 0}, a1 = a0;
+    // (z, l, a) += (z2, l2, b): both to the larger exponent; equal exponents (also -inf = -inf) need no scaling
+    auto add = [&](float z2, float l2, const f32x4& b0, const f32x4& b1) {
+        const float zn = fmaxf(z, z2);
+        const float w1 = (z == zn) ? 1.f : __builtin_amdgcn_exp2f((z - zn) * c);
+        const float w2 = (z2 == zn) ? 1.f : __builtin_amdgcn_exp2f((z2 - zn) * c);
+        l = l * w1 + l2 * w2;
+        a0 = a0 * w1 + b0 * w2;
+        a1 = a1 * w1 + b1 * w2;
+        z = zn;
+    };
+    constexpr int NB = 4;                                  // partial results whose loads are in flight together
+    for (int sp0 = ph; sp0 < nsplit; sp0 += NB * NPH) {
+        u32x2 e[NB];
+        f32x4 b0[NB], b1[NB];
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const int sp = min(sp0 + u * NPH, nsplit - 1);     // (past the end: loaded again, not added)
+            const size_t slot = row * nsplit + sp;
+            const float* src = part + slot * DV + 8 * cg;
+            e[u] = cload8(ml + 2 * slot);
+            b0[u] = cload16f(src);
+            b1[u] = cload16f(src + 4);
+        }
+#pragma unroll
+        for (int u = 0; u < NB; ++u)
+            if (sp0 + u * NPH < nsplit) add(__uint_as_float(e[u][0]), __uint_as_float(e[u][1]), b0[u], b1[u]);
+    }
+#pragma unroll
+    for (int off = G; off < 64; off <<= 1) {
+        f32x4 b0, b1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { b0[i] = __shfl_xor(a0[i], off); b1[i] = __shfl_xor(a1[i], off); }
+        add(__shfl_xor(z, off), __shfl_xor(l, off), b0, b1);
+    }
+    if (ph == 0) {
+        const float inv = 1.0f / l;
+        const u32x4 o = {pack_bf16(a0[0] * inv, a0[1] * inv), pack_bf16(a0[2] * inv, a0[3] * inv),
+                         pack_bf16(a1[0] * inv, a1[1] * inv), pack_bf16(a1[2] * inv, a1[3] * inv)};
+        *reinterpret_cast<u32x4*>(O + row * DV + 8 * cg) = o;
+    }
+}
+
 // TAIL: iterations left after the main loop (1 .. 4; the loop takes two
 // complete iterations per trip while at least five key blocks remain).  A
 // template parameter, so that no branch merges the accumulators and only the
@@ -81,8 +140,9 @@ __device__ __forceinline__ int attn_swz_tr(int row) {
 // KSPLIT (few queries, e.g. decoding): the serial loop over the key blocks is
 // cut into nsplit equal ranges that run in parallel workgroups (Rule 3's
 // parallel form); each stores its accumulators as significand-exponent pairs
-// (output sums and row sum at its own row exponents) and
-// attention_combine_kernel adds them the Appendix's way.
+// (output sums and row sum at its own row exponents), which are added the
+// Appendix's way: by the workgroup of a (problem, query block) that finishes
+// last when arrival counters are given (p.cnt), else by attention_combine_kernel.
 template <int DK, int DV, int TAIL, int NW, bool KSPLIT = false>
 __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p) {
     constexpr int ATTN_BQ = 32 * NW;
@@ -92,6 +152,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p)
     static_assert((DK == 64 || DK == 128) && (DV == 64 || DV == 128), "head dimensions 64 or 128");
     __shared__ u32x4 sK0[ATTN_BK * CK], sK1[ATTN_BK * CK];
     __shared__ u32x4 sV0[ATTN_BK * CV], sV1[ATTN_BK * CV];
+    __shared__ unsigned last_arrival;                // (KSPLIT) this workgroup adds the partial results
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -399,10 +460,28 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p)
             for (int ds = 0; ds < NDS; ++ds)
 #pragma unroll
                 for (int vg = 0; vg < 4; ++vg)
-                    *reinterpret_cast<f32x4*>(orow + 32 * ds + 8 * vg + 4 * g) =
-                        f32x4{oacc[ds][4 * vg], oacc[ds][4 * vg + 1], oacc[ds][4 * vg + 2], oacc[ds][4 * vg + 3]};
-            if (g == 0) *reinterpret_cast<f32x2*>(p.ml + 2 * slot) = f32x2{m_run, l};
+                    cstore16f(orow + 32 * ds + 8 * vg + 4 * g,
+                              f32x4{oacc[ds][4 * vg], oacc[ds][4 * vg + 1], oacc[ds][4 * vg + 2], oacc[ds][4 * vg + 3]});
+            if (g == 0) cstore8(p.ml + 2 * slot, __float_as_uint(m_run), __float_as_uint(l));
         }
+        if (p.cnt == nullptr) return;
+        // The partial results are complete in memory (stores acknowledged), then thread 0 counts the
+        // delivery.  The workgroup whose delivery is the last of the nsplit of this (problem, query
+        // block) adds the partial results of the block's rows, a wavefront per row and in slot order
+        // (so the result does not depend on who is last), and puts the counter back to zero.
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const unsigned old = __hip_atomic_fetch_add(p.cnt + lin, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            last_arrival = (old + 1u == (unsigned)p.nsplit) ? 1u : 0u;
+        }
+        __syncthreads();
+        if (last_arrival == 0u) return;
+        const int q_end = min(p.M, (qt + 1) * ATTN_BQ);
+        for (int qq = qt * ATTN_BQ + w; qq < q_end; qq += NW)
+            attention_combine_row<DV>(p.part, p.ml, p.O, (size_t)b * p.M + qq, p.nsplit, p.c, lane);
+        if (threadIdx.x == 0) __hip_atomic_store(p.cnt + lin, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
     const float inv = 1.0f / l;
@@ -419,49 +498,11 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p)
     }
 }
 
-// Adds the nsplit partial results of a query row.  Every partial result is a
-// pair (significands O_s and l_s, row exponent m_s); two pairs are added by
-// bringing both to the larger exponent (Appendix), and the quotient of the
-// totals is rounded to bf16.  One wavefront per row: lane = (group of 8 output
-// columns, phase); a phase adds every (64 / groups)-th partial result, then the
-// phases are added across lanes.
+// One wavefront per query row (the launch that follows a split-key kernel run without arrival counters).
 template <int DV>
 __global__ __launch_bounds__(64) void attention_combine_kernel(const float* part, const float* ml, u16* O,
                                                                 int nsplit, float c) {
-    constexpr int G = DV / 8, NPH = 64 / G;
-    const size_t row = blockIdx.x;
-    const int lane = threadIdx.x, cg = lane % G, ph = lane / G;
-    float z = -INFINITY, l = 0.f;
-    f32x4 a0 = {0, 0, 0, 0}, a1 = a0;
-    // (z, l, a) += (z2, l2, b): both to the larger exponent; equal exponents (also -inf = -inf) need no scaling
-    auto add = [&](float z2, float l2, const f32x4& b0, const f32x4& b1) {
-        const float zn = fmaxf(z, z2);
-        const float w1 = (z == zn) ? 1.f : __builtin_amdgcn_exp2f((z - zn) * c);
-        const float w2 = (z2 == zn) ? 1.f : __builtin_amdgcn_exp2f((z2 - zn) * c);
-        l = l * w1 + l2 * w2;
-        a0 = a0 * w1 + b0 * w2;
-        a1 = a1 * w1 + b1 * w2;
-        z = zn;
-    };
-    for (int sp = ph; sp < nsplit; sp += NPH) {
-        const size_t slot = row * nsplit + sp;
-        const f32x2 e = *reinterpret_cast<const f32x2*>(ml + 2 * slot);
-        const float* src = part + slot * DV + 8 * cg;
-        add(e[0], e[1], *reinterpret_cast<const f32x4*>(src), *reinterpret_cast<const f32x4*>(src + 4));
-    }
-#pragma unroll
-    for (int off = G; off < 64; off <<= 1) {
-        f32x4 b0, b1;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { b0[i] = __shfl_xor(a0[i], off); b1[i] = __shfl_xor(a1[i], off); }
-        add(__shfl_xor(z, off), __shfl_xor(l, off), b0, b1);
-    }
-    if (ph == 0) {
-        const float inv = 1.0f / l;
-        const u32x4 o = {pack_bf16(a0[0] * inv, a0[1] * inv), pack_bf16(a0[2] * inv, a0[3] * inv),
-                         pack_bf16(a1[0] * inv, a1[1] * inv), pack_bf16(a1[2] * inv, a1[3] * inv)};
-        *reinterpret_cast<u32x4*>(O + row * DV + 8 * cg) = o;
-    }
+    attention_combine_row<DV>(part, ml, O, blockIdx.x, nsplit, c, threadIdx.x);
 }
 
 }  // namespace bb

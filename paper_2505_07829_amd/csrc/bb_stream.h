@@ -154,34 +154,6 @@ __device__ __forceinline__ void grid_arrive(unsigned* bar, unsigned k) {
     if (threadIdx.x == 0) bar_signal(bar, k);
 }
 
-// Data exchanged between workgroups inside the kernel is written with
-// agent-scope stores (written through, complete when acknowledged) and read
-// with agent-scope loads (never a stale cached copy).  So neither side needs a
-// cache write-back or invalidation around the barrier, and nothing waits on
-// the weight loads that are in flight.
-__device__ __forceinline__ void cstore8(void* p, u32 lo, u32 hi) {
-    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), ((unsigned long long)hi << 32) | lo,
-                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void cstore16f(float* p, const f32x4 v) {
-    cstore8(p, __float_as_uint(v[0]), __float_as_uint(v[1]));
-    cstore8(p + 2, __float_as_uint(v[2]), __float_as_uint(v[3]));
-}
-__device__ __forceinline__ u32x2 cload8(const void* p) {
-    const unsigned long long v =
-        __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    u32x2 r = {(u32)v, (u32)(v >> 32)};
-    return r;
-}
-__device__ __forceinline__ f32x4 cload16f(const float* p) {
-    const u32x2 a = cload8(p), b = cload8(p + 2);
-    f32x4 r = {__uint_as_float(a[0]), __uint_as_float(a[1]), __uint_as_float(b[0]), __uint_as_float(b[1])};
-    return r;
-}
-__device__ __forceinline__ float cload4f(const float* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 constexpr int STREAM_NP1 = 2;   // phase 1 items (16 KiB each) a wavefront keeps in flight
 constexpr int STREAM_NP2 = 6;   // phase 2 items (8 KiB each) a wavefront keeps in flight
 

@@ -196,3 +196,22 @@ def test_split_keys_with_caller_workspace_too_small_is_an_error():
         assert torch.isfinite(O.float()).all()
     finally:
         bb.bb_set_workspace(None)
+
+
+def test_split_keys_arrival_counters_survive_other_calls():
+    # few query rows: the last workgroup of a (problem, query block) to finish adds the partial
+    # results; its counters sit at the start of the workspace that the other entry points also use.
+    # Calls in a row, with other batch sizes and with a streaming FFN call between them, must each
+    # give the oracle's result (a counter left non-zero would leave rows of O unwritten).
+    cases = [bb_inputs.make_attn(B, M, 4096, 128, 128, seed=40 + B) for B, M in [(32, 1), (4, 3), (32, 1), (9, 16)]]
+    refs = [orc.attention(*c) for c in cases]
+    X, g, W1, W3, W2 = [t.cuda() for t in bb_inputs.make_ffn(8, 512, 1024, seed=3)]
+    for rep in range(3):
+        for (Q, K, V), ref in zip(cases, refs):
+            O = bb.bb_attention(Q.cuda(), K.cuda(), V.cuda())
+            O2 = bb.bb_attention(Q.cuda(), K.cuda(), V.cuda())
+            torch.cuda.synchronize()
+            assert rel_err(O.reshape(-1, 128), ref) <= TOL
+            assert torch.equal(O, O2)                          # fixed order of addition: the same bits
+            if rep == 1:
+                bb.bb_rmsnorm_swiglu_ffn(X, g, W1, W3, W2, 1e-6)
