@@ -338,9 +338,9 @@ def run_attention(steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
     refd = orc.attention(*cpu_d)
     od = Od.reshape(-1, wd["dv"]).float().cpu().numpy().astype(np.float64)
     res["decode"] = {
-        "workload": "attention B=%(B)d M=1 N=%(N)d d=%(d)d dv=%(dv)d (keys split over workgroups, added by the last to finish)" % wd,
+        "workload": "attention B=%(B)d M=1 N=%(N)d d=%(d)d dv=%(dv)d (one-query streaming kernel: keys split over workgroups, added by the last to finish)" % wd,
         "kernels_ms": {"attention": d_ms},
-        "roofline": {"kernel": "attention (split keys, last arriver adds)", "bound": "hbm",
+        "roofline": {"kernel": "attention_decode_kernel", "bound": "hbm",
                      "achieved": d_bytes / (d_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": d_bytes / (d_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None, "algorithmic": d_bytes},
         "parity": {"max_row_rel_err": float((np.linalg.norm(od - refd, axis=1) / np.linalg.norm(refd, axis=1)).max()),

@@ -262,13 +262,19 @@ int bb_layernorm_matmul_unfused(const void* X, const void* gamma,
  * compute units, and at least 8 blocks of 64 keys): the loop over the key
  * blocks is cut into equal ranges that run in parallel workgroups (Rule 3's
  * parallel form); each stores its unnormalised output and row sum with their
- * row exponents, fp32, and these significand-exponent pairs are added
- * (Appendix: both terms brought to the larger exponent) and divided, in a
- * fixed order: by a second kernel, or, with one query per problem (M = 1), by
- * the workgroup of a problem that finishes last (arrival counters at the start
- * of the workspace, which every launch leaves at zero).
+ * row exponents, fp32, and a second kernel adds these significand-exponent
+ * pairs (Appendix: both terms brought to the larger exponent) in a fixed
+ * order and divides.
+ * One query per problem (M = 1, any N): no matrix product is left; a
+ * streaming kernel reads K and V once with every lane loading (fp32 dot
+ * products and probabilities, Example 1's online softmax per wavefront over
+ * blocks of 64 keys), workgroups share a problem's keys as above, and the
+ * workgroup of a problem that finishes last adds the pairs (arrival counters
+ * at the start of the workspace, which every launch leaves at zero): one
+ * launch.
  * This path uses bb_attention_workspace_bytes(B, M, N, d, dv) bytes of the
- * library workspace (0 when the keys are not split; see bb_set_workspace).
+ * library workspace (0 when M > 1 and the keys are not split; see
+ * bb_set_workspace).
  * The entry points share the workspace: a launch captured into a HIP graph
  * (this one, or a BB_VARIANT_STREAM one) is replayed only while no other
  * entry point of the library has run since its capture.  The environment variable BB_ATTN_WAVES=4|8 (read once) forces

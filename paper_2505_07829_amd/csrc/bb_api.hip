@@ -301,12 +301,17 @@ size_t split_bytes(int mode, int64_t M, int64_t N, int64_t K, int cus) {
 // Key splits of the attention kernel for `wgs` (problem, query block) pairs and nt key blocks:
 // the largest divisor of nt that keeps about two workgroups per compute unit and at least two
 // key blocks per workgroup; 1 = no split (enough workgroups already, or a short sequence).
-// split keys: with at most this many query rows per problem, the last workgroup to arrive adds the partial
-// results.  (Measured, 4096 keys, back-to-back calls: one row 11.9 -> 9.2 us for 1 or 2 problems, 11.9 -> 11.4 for
-// 8, no difference for 32; 4 rows and more are slower than the second launch, which has a workgroup per row.)
-constexpr int64_t kAttnFusedCombineRows = 1;
-// arrival counters of the split-key kernel, one per (problem, block of 128 queries), at the workspace's start
-size_t attn_zone_bytes(int64_t B, int64_t M) { return align_up((size_t)B * ((M + 127) / 128) * 4); }
+// arrival counters of attention_decode_kernel, one per problem, at the workspace's start
+size_t attn_zone_bytes(int64_t B) { return align_up((size_t)B * 4); }
+
+// One query per problem: blocks of 64 keys per wavefront of attention_decode_kernel (a workgroup has four), so
+// that the launch has about three workgroups per compute unit; *nsplit = workgroups per problem.
+int attn_decode_plan(int64_t B, int64_t N, int cus, int64_t* nsplit) {
+    const int64_t nblocks = (N + ATTN_BK - 1) / ATTN_BK, units = B * ((nblocks + 3) / 4);
+    const int64_t per = std::min<int64_t>(std::max<int64_t>((units + 3 * cus - 1) / (3 * (int64_t)cus), 1), 64);
+    *nsplit = (nblocks + 4 * per - 1) / (4 * per);
+    return (int)per;
+}
 
 int attn_key_splits(int64_t wgs, int64_t nt, int cus) {
     if (wgs * 2 > cus || nt < 8) return 1;
@@ -875,6 +880,38 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
     a.B = (int)B;
     a.M = (int)M;
     a.N = (int)N;
+    if (M == 1) {
+        // one query per problem: the streaming kernel (no matrix product), any N
+        int64_t nsplit = 1;
+        a.nt_split = attn_decode_plan(B, N, std::min(dev->cus, kPlanCUs), &nsplit);
+        if (B * nsplit > 0x7fffffffLL) return BB_ERR_SHAPE;
+        a.nsplit = (int)nsplit;
+        a.tiles_q = 1;
+        a.wgs_per_xcd = 0;
+        a.c = (float)(1.4426950408889634 / std::sqrt((double)d));
+        const size_t zone = attn_zone_bytes(B), pbytes = align_up((size_t)B * nsplit * dv * 4);
+        if (int rc = ensure_workspace(zone + pbytes + align_up((size_t)B * nsplit * 8))) return rc;
+        const size_t had = g_ws.attn_zone;
+        mark_dirty(0);
+        if (had < zone) {                  // counters: zero before their first use; every launch leaves them zero
+            if (int rc = fill_zero(g_ws.ptr, zone, st)) return rc;
+            g_ws.attn_zone = zone;
+        } else {
+            g_ws.attn_zone = had;
+        }
+        a.cnt = (unsigned*)g_ws.ptr;
+        a.part = (float*)((char*)g_ws.ptr + zone);
+        a.ml = (float*)((char*)g_ws.ptr + zone + pbytes);
+        const dim3 grid((unsigned)(B * nsplit)), block(256);
+        prof_begin(st);
+        if (d == 64 && dv == 64) hipLaunchKernelGGL((attention_decode_kernel<64, 64>), grid, block, 0, st, a);
+        else if (d == 64) hipLaunchKernelGGL((attention_decode_kernel<64, 128>), grid, block, 0, st, a);
+        else if (dv == 64) hipLaunchKernelGGL((attention_decode_kernel<128, 64>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((attention_decode_kernel<128, 128>), grid, block, 0, st, a);
+        BB_HIP(hipGetLastError());
+        prof_mark("attention", st);
+        return BB_OK;
+    }
     // few queries (decoding): split the keys over workgroups so that the chip has about two per
     // compute unit; equal numbers of key blocks per workgroup, at least two each
     const int64_t nt_all = (N + ATTN_BK - 1) / ATTN_BK;
@@ -895,30 +932,13 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
     a.part = nullptr;
     a.ml = nullptr;
     a.cnt = nullptr;
-    // one query per problem (decoding): the last workgroup of a problem to finish adds the partial
-    // results itself; else a second launch does, with a workgroup per row
-    const bool fused_combine = ksplit > 1 && M <= kAttnFusedCombineRows;
     if (ksplit > 1) {
         const size_t rows = (size_t)B * M;
-        const size_t zone = attn_zone_bytes(B, M);
         const size_t pbytes = align_up(rows * ksplit * dv * 4);
-        if (int rc = ensure_workspace(zone + pbytes + align_up(rows * ksplit * 8))) return rc;
-        if (fused_combine) {
-            // counters: zero before their first use; every launch leaves them zero again
-            const size_t had = g_ws.attn_zone;
-            mark_dirty(0);
-            if (had < zone) {
-                if (int rc = fill_zero(g_ws.ptr, zone, st)) return rc;
-                g_ws.attn_zone = zone;
-            } else {
-                g_ws.attn_zone = had;
-            }
-            a.cnt = (unsigned*)g_ws.ptr;
-        } else {
-            mark_dirty(0);
-        }
-        a.part = (float*)((char*)g_ws.ptr + zone);
-        a.ml = (float*)((char*)g_ws.ptr + zone + pbytes);
+        if (int rc = ensure_workspace(pbytes + align_up(rows * ksplit * 8))) return rc;
+        mark_dirty(0);
+        a.part = (float*)g_ws.ptr;
+        a.ml = (float*)((char*)g_ws.ptr + pbytes);
     }
     const dim3 grid((unsigned)(8 * a.wgs_per_xcd)), block((unsigned)(64 * nw));
     prof_begin(st);
@@ -938,9 +958,8 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
             else if (tail == 2) hipLaunchKernelGGL((attention_kernel<DK, DV, 2, 4, true>), grid, block, 0, st, a);
             else if (tail == 3) hipLaunchKernelGGL((attention_kernel<DK, DV, 3, 4, true>), grid, block, 0, st, a);
             else hipLaunchKernelGGL((attention_kernel<DK, DV, 4, 4, true>), grid, block, 0, st, a);
-            if (!fused_combine)
-                hipLaunchKernelGGL((attention_combine_kernel<DV>), dim3((unsigned)(B * M)), dim3(64), 0, st,
-                                   (const float*)a.part, (const float*)a.ml, a.O, ksplit, a.c);
+            hipLaunchKernelGGL((attention_combine_kernel<DV>), dim3((unsigned)(B * M)), dim3(64), 0, st,
+                               (const float*)a.part, (const float*)a.ml, a.O, ksplit, a.c);
         } else if (nw == 8) {
             go_nw(std::integral_constant<int, 8>{});
         } else {
@@ -960,10 +979,16 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
 
 size_t bb_attention_workspace_bytes(int64_t B, int64_t M, int64_t N, int64_t d, int64_t dv) {
     if (B < 0 || M < 0 || N < 1 || (d != 64 && d != 128) || (dv != 64 && dv != 128)) return 0;
+    if (B == 0 || M == 0) return 0;
+    if (M == 1) {
+        int64_t nsplit = 1;
+        attn_decode_plan(B, N, kPlanCUs, &nsplit);
+        return attn_zone_bytes(B) + align_up((size_t)B * nsplit * dv * 4) + align_up((size_t)B * nsplit * 8);
+    }
     const int s = attn_key_splits(B * ((M + 127) / 128), (N + ATTN_BK - 1) / ATTN_BK, kPlanCUs);
     if (s < 2) return 0;
     const size_t rows = (size_t)B * M;
-    return attn_zone_bytes(B, M) + align_up(rows * s * dv * 4) + align_up(rows * s * 8);
+    return align_up(rows * s * dv * 4) + align_up(rows * s * 8);
 }
 
 int bb_rmsnorm_swiglu_ffn_unfused(const void* X, const void* g, const void* W1, const void* W3,

@@ -51,8 +51,8 @@ struct AttnArgs {
     int nsplit, nt_split;
     float* part;        // [B M][nsplit][DV]
     float* ml;          // [B M][nsplit][2]
-    // arrival counters, one per (problem, query block), zero between launches; nullptr: the partial
-    // results are added by attention_combine_kernel instead of by the last workgroup to arrive
+    // attention_decode_kernel: arrival counters, one per problem, zero between launches (the last
+    // workgroup of a problem to arrive adds the problem's partial results)
     unsigned* cnt;
 };
 
@@ -140,9 +140,8 @@ __device__ __forceinline__ void attention_combine_row(const float* part, const f
 // KSPLIT (few queries, e.g. decoding): the serial loop over the key blocks is
 // cut into nsplit equal ranges that run in parallel workgroups (Rule 3's
 // parallel form); each stores its accumulators as significand-exponent pairs
-// (output sums and row sum at its own row exponents), which are added the
-// Appendix's way: by the workgroup of a (problem, query block) that finishes
-// last when arrival counters are given (p.cnt), else by attention_combine_kernel.
+// (output sums and row sum at its own row exponents) and
+// attention_combine_kernel adds them the Appendix's way.
 template <int DK, int DV, int TAIL, int NW, bool KSPLIT = false>
 __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p) {
     constexpr int ATTN_BQ = 32 * NW;
@@ -152,7 +151,6 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p)
     static_assert((DK == 64 || DK == 128) && (DV == 64 || DV == 128), "head dimensions 64 or 128");
     __shared__ u32x4 sK0[ATTN_BK * CK], sK1[ATTN_BK * CK];
     __shared__ u32x4 sV0[ATTN_BK * CV], sV1[ATTN_BK * CV];
-    __shared__ unsigned last_arrival;                // (KSPLIT) this workgroup adds the partial results
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -464,24 +462,6 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p)
                               f32x4{oacc[ds][4 * vg], oacc[ds][4 * vg + 1], oacc[ds][4 * vg + 2], oacc[ds][4 * vg + 3]});
             if (g == 0) cstore8(p.ml + 2 * slot, __float_as_uint(m_run), __float_as_uint(l));
         }
-        if (p.cnt == nullptr) return;
-        // The partial results are complete in memory (stores acknowledged), then thread 0 counts the
-        // delivery.  The workgroup whose delivery is the last of the nsplit of this (problem, query
-        // block) adds the partial results of the block's rows, a wavefront per row and in slot order
-        // (so the result does not depend on who is last), and puts the counter back to zero.
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            const unsigned old = __hip_atomic_fetch_add(p.cnt + lin, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            last_arrival = (old + 1u == (unsigned)p.nsplit) ? 1u : 0u;
-        }
-        __syncthreads();
-        if (last_arrival == 0u) return;
-        const int q_end = min(p.M, (qt + 1) * ATTN_BQ);
-        for (int qq = qt * ATTN_BQ + w; qq < q_end; qq += NW)
-            attention_combine_row<DV>(p.part, p.ml, p.O, (size_t)b * p.M + qq, p.nsplit, p.c, lane);
-        if (threadIdx.x == 0) __hip_atomic_store(p.cnt + lin, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
     const float inv = 1.0f / l;
@@ -498,7 +478,153 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_kernel(const AttnArgs p)
     }
 }
 
-// One wavefront per query row (the launch that follows a split-key kernel run without arrival counters).
+// One query per problem (decoding): no matrix product is left, the work is reading K and V once.
+// A workgroup of four wavefronts takes 4 nt_split blocks of 64 keys of one problem, wavefront w the
+// blocks 4 j + w.  A block's K and V rows are requested together (a lane holds 8 features of a
+// row, DK / 8 lanes a row), the scores are fp32 dot products reduced over the lanes of a row, the
+// softmax runs online per wavefront with the row exponent in score units (Example 1's running
+// maximum and sum; the probabilities stay fp32 here), and the value sums of the lanes' keys are
+// added over the lane groups at the end.  The four wavefronts' significand-exponent pairs are
+// added in LDS (Appendix), the workgroup's pair goes to slot `split` of part / ml, and the last
+// workgroup of the problem to arrive adds the slots (attention_combine_row).  nsplit may be 1.
+template <int DK, int DV>
+__global__ __launch_bounds__(256) void attention_decode_kernel(const AttnArgs p) {
+    constexpr int LK = DK / 8, RK = 64 / LK, NLK = 64 / RK;   // lanes per K row, rows per load instruction, instructions per block
+    constexpr int LV = DV / 8, RV = 64 / LV, NLV = 64 / RV;
+    __shared__ float s_p[4][64];
+    __shared__ float s_o[4][DV];
+    __shared__ float s_ml[4][2];
+    __shared__ unsigned last_arrival;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int b = blockIdx.x / p.nsplit, split = blockIdx.x % p.nsplit;
+    const u16* const Kb = p.K + (size_t)b * p.N * DK;
+    const u16* const Vb = p.V + (size_t)b * p.N * DV;
+    const int kl = lane % LK, kr0 = lane / LK;      // this lane's features 8 kl .. 8 kl + 7 of key row kr0 (+ RK i)
+    const int vl = lane % LV, vr0 = lane / LV;
+
+    float qf[8];
+    {
+        const u32x4 qc = ldg16(p.Q + (size_t)b * DK + 8 * kl);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { qf[2 * e] = bf_lo(qc[e]); qf[2 * e + 1] = bf_hi(qc[e]); }
+    }
+    float m_run = -INFINITY, l_run = 0.f;           // l_run: this lane's keys only
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+
+    for (int j = 0; j < p.nt_split; ++j) {
+        const int key0 = ((split * p.nt_split + j) * 4 + w) * ATTN_BK;
+        if (key0 >= p.N) break;                      // (the same for the whole wavefront)
+        u32x4 kreg[NLK], vreg[NLV];
+#pragma unroll
+        for (int i = 0; i < NLK; ++i) {
+            const int row = min(key0 + RK * i + kr0, p.N - 1);
+            kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Kb + (size_t)row * DK + 8 * kl));
+        }
+#pragma unroll
+        for (int i = 0; i < NLV; ++i) {
+            const int row = min(key0 + RV * i + vr0, p.N - 1);
+            vreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Vb + (size_t)row * DV + 8 * vl));
+        }
+        // scores of keys key0 + RK i + kr0 (all lanes of a row hold the row's score); past the end: -inf
+        float sc[NLK];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < NLK; ++i) {
+            float d = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                d = fmaf(qf[2 * e], bf_lo(kreg[i][e]), d);
+                d = fmaf(qf[2 * e + 1], bf_hi(kreg[i][e]), d);
+            }
+#pragma unroll
+            for (int off = 1; off < LK; off <<= 1) d += __shfl_xor(d, off);
+            sc[i] = (key0 + RK * i + kr0 < p.N) ? d : -INFINITY;
+            mx = fmaxf(mx, sc[i]);
+        }
+#pragma unroll
+        for (int off = LK; off < 64; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+        const float m_new = fmaxf(m_run, mx);        // finite: key0 < N
+        const float scale = __builtin_amdgcn_exp2f((m_run - m_new) * p.c);     // 0 at the first block
+        m_run = m_new;
+        l_run *= scale;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] *= scale;
+        // probabilities through LDS from the K layout (key RK i + kr0) to the V layout (key RV i + vr0)
+#pragma unroll
+        for (int i = 0; i < NLK; ++i)
+            if (kl == 0) s_p[w][RK * i + kr0] = __builtin_amdgcn_exp2f((sc[i] - m_new) * p.c);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int i = 0; i < NLV; ++i) {
+            const float pr = s_p[w][RV * i + vr0];
+            l_run += pr;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[2 * e] = fmaf(pr, bf_lo(vreg[i][e]), acc[2 * e]);
+                acc[2 * e + 1] = fmaf(pr, bf_hi(vreg[i][e]), acc[2 * e + 1]);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();             // s_p[w] is rewritten by the next block
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    // add over the lane groups (keys); group 0 then holds the wavefront's sums for value columns 8 vl .. 8 vl + 7
+#pragma unroll
+    for (int off = LV; off < 64; off <<= 1) {
+        l_run += __shfl_xor(l_run, off);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += __shfl_xor(acc[e], off);
+    }
+    if (vr0 == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s_o[w][8 * vl + e] = acc[e];
+    }
+    if (lane == 0) { s_ml[w][0] = m_run; s_ml[w][1] = l_run; }
+    __syncthreads();
+    // the four wavefronts' pairs -> the workgroup's pair (wavefront 0 always has a key: its exponent is finite)
+    const size_t slot = (size_t)b * p.nsplit + split;
+    {
+        float mw[4], ww[4];
+        float mm = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { mw[u] = s_ml[u][0]; mm = fmaxf(mm, mw[u]); }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) ww[u] = (mw[u] == mm) ? 1.f : __builtin_amdgcn_exp2f((mw[u] - mm) * p.c);
+        const int t = threadIdx.x;
+        if (t < DV) {
+            float o = 0.f;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) o = fmaf(s_o[u][t], ww[u], o);
+            __hip_atomic_store(p.part + slot * DV + t, o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (t == 0) {
+            float l = 0.f;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) l = fmaf(s_ml[u][1], ww[u], l);
+            cstore8(p.ml + 2 * slot, __float_as_uint(mm), __float_as_uint(l));
+        }
+    }
+    // count the delivery; the last workgroup of the problem adds the slots (in slot order) and
+    // puts the counter back to zero
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned old = __hip_atomic_fetch_add(p.cnt + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        last_arrival = (old + 1u == (unsigned)p.nsplit) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (last_arrival == 0u || w != 0) return;
+    attention_combine_row<DV>(p.part, p.ml, p.O, (size_t)b, p.nsplit, p.c, lane);
+    if (lane == 0) __hip_atomic_store(p.cnt + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// One wavefront per query row (the launch that follows attention_kernel<..., KSPLIT>).
 template <int DV>
 __global__ __launch_bounds__(64) void attention_combine_kernel(const float* part, const float* ml, u16* O,
                                                                 int nsplit, float c) {

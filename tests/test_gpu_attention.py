@@ -153,8 +153,9 @@ def test_eight_wavefront_workgroups_on_the_shape_that_selects_them():
 
 # ---------------------------------------------------------------- few queries: keys split over workgroups
 @pytest.mark.parametrize("B,M,N", [(32, 1, 4096), (8, 1, 8192), (4, 16, 2048), (2, 130, 4096), (1, 1, 777),
-                                   (3, 5, 64 * 13), (16, 1, 4096 + 17)])
-@pytest.mark.parametrize("d,dv", [(128, 128), (64, 128)])
+                                   (3, 5, 64 * 13), (16, 1, 4096 + 17), (3, 1, 1), (2, 1, 63), (5, 1, 257),
+                                   (1, 1, 70000), (600, 1, 1100), (2, 2, 8192)])
+@pytest.mark.parametrize("d,dv", [(128, 128), (64, 128), (128, 64), (64, 64)])
 def test_split_keys_decode_shapes(B, M, N, d, dv):
     # (several of these split the keys, the ones whose block count has no suitable divisor or that
     # are short do not; bb_attention_workspace_bytes says which)
@@ -164,9 +165,11 @@ def test_split_keys_decode_shapes(B, M, N, d, dv):
 
 def test_split_keys_is_taken_and_needs_workspace():
     assert bb.bb_attention_workspace_bytes(32, 1, 4096, 128, 128) > 0
+    assert bb.bb_attention_workspace_bytes(32, 2, 4096, 128, 128) > 0
+    assert bb.bb_attention_workspace_bytes(1, 1, 1, 128, 128) > 0              # one query: always (slots + counters)
     assert bb.bb_attention_workspace_bytes(32, 4096, 4096, 128, 128) == 0      # enough query blocks
-    assert bb.bb_attention_workspace_bytes(32, 1, 256, 128, 128) == 0          # short sequence
-    assert bb.bb_attention_workspace_bytes(1, 1, 64 * 13, 128, 128) == 0       # 13 blocks: no divisor
+    assert bb.bb_attention_workspace_bytes(32, 2, 256, 128, 128) == 0          # short sequence
+    assert bb.bb_attention_workspace_bytes(1, 2, 64 * 13, 128, 128) == 0       # 13 blocks: no divisor
     assert bb.bb_attention_workspace_bytes(2, 2, 4096, 96, 128) == 0           # invalid head dimension
 
 
@@ -215,3 +218,25 @@ def test_split_keys_arrival_counters_survive_other_calls():
             assert torch.equal(O, O2)                          # fixed order of addition: the same bits
             if rep == 1:
                 bb.bb_rmsnorm_swiglu_ffn(X, g, W1, W3, W2, 1e-6)
+
+
+@pytest.mark.parametrize("pos", [5, 2000, 4090])
+def test_one_query_large_scores_maximum_early_middle_late(pos):
+    # one query per problem (the streaming kernel): a dominant key in the first, a middle or the last
+    # workgroup's range; the other slots' exponents are far below it
+    Q, K, V = bb_inputs.make_attn(3, 1, 4096, 128, 128, seed=6, q_scale=30.0)
+    K = K.float()
+    K[1, pos] = 4.0 * Q[1, 0].float()
+    assert run(Q, K.to(torch.bfloat16), V) <= TOL
+
+
+def test_one_query_constant_keys_give_the_mean_of_the_values():
+    # closed form: equal scores -> uniform weights -> O = mean of V's rows (ragged N: masked keys weigh 0)
+    B, N = 2, 1000
+    Q = torch.ones(B, 1, 128, dtype=torch.bfloat16)
+    K = torch.full((B, N, 128), 0.5, dtype=torch.bfloat16)
+    V = bb_inputs.make_attn(B, 1, N, 128, 128, seed=2)[2]
+    O = bb.bb_attention(Q.cuda(), K.cuda(), V.cuda())
+    torch.cuda.synchronize()
+    mean = V.double().mean(dim=1).numpy()
+    assert rel_err(O.reshape(B, 128), mean) <= TOL
