@@ -38,6 +38,7 @@ MEASURED_TRAFFIC_BYTES = {
     ("c3", "gemm_gateup"): 621.5e6 + 45.2e6,
     ("c3", "gemm_gateup_prescaled"): 624.2e6 + 45.1e6,
     ("attention", "attention"): 100.9e6 + 33.6e6,
+    ("attention", "attention_decode"): 67.6e6 + 0.3e6,
 }
 
 
@@ -342,7 +343,8 @@ def run_attention(steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
         "kernels_ms": {"attention": d_ms},
         "roofline": {"kernel": "attention_decode_kernel", "bound": "hbm",
                      "achieved": d_bytes / (d_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": d_bytes / (d_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None, "algorithmic": d_bytes},
+                     "frac": d_bytes / (d_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(("attention", "attention_decode")), "algorithmic": d_bytes},
         "parity": {"max_row_rel_err": float((np.linalg.norm(od - refd, axis=1) / np.linalg.norm(refd, axis=1)).max()),
                    "rows_checked": wd["B"], "tolerance": 2e-2},
     }
