@@ -240,3 +240,9 @@ def test_one_query_constant_keys_give_the_mean_of_the_values():
     torch.cuda.synchronize()
     mean = V.double().mean(dim=1).numpy()
     assert rel_err(O.reshape(B, 128), mean) <= TOL
+
+
+def test_one_query_a_million_keys():
+    # hundreds of workgroups share the one problem, several key blocks per wavefront, ragged end
+    Q, K, V = bb_inputs.make_attn(1, 1, 1_000_003, 128, 128, seed=12)
+    assert run(Q, K, V) <= TOL
