@@ -276,8 +276,9 @@ int bb_layernorm_matmul_unfused(const void* X, const void* gamma,
  * library workspace (0 when M > 1 and the keys are not split; see
  * bb_set_workspace).
  * The entry points share the workspace: a launch captured into a HIP graph
- * (this one, or a BB_VARIANT_STREAM one) is replayed only while no other
- * entry point of the library has run since its capture.  The environment variable BB_ATTN_WAVES=4|8 (read once) forces
+ * (this one with M = 1, or a BB_VARIANT_STREAM one) is replayed only while
+ * no other entry point of the library, and no call that needs a larger
+ * workspace, has run since its capture.  The environment variable BB_ATTN_WAVES=4|8 (read once) forces
  * the number of wavefronts per workgroup (32 queries each) instead of the
  * shape-driven choice; a query row is computed by one wavefront in the same
  * order either way, so the results are bit-identical.

@@ -246,3 +246,34 @@ def test_one_query_a_million_keys():
     # hundreds of workgroups share the one problem, several key blocks per wavefront, ragged end
     Q, K, V = bb_inputs.make_attn(1, 1, 1_000_003, 128, 128, seed=12)
     assert run(Q, K, V) <= TOL
+
+
+def test_one_query_replays_from_a_captured_graph():
+    # the arrival counters are device memory that every launch leaves at zero, so a captured launch can be
+    # replayed: several replays, with eager one-query calls (other batch sizes too) and new inputs in
+    # between, each compared with the eager result on the same inputs
+    B, N = 8, 3000
+    Q, K, V = [t.cuda() for t in bb_inputs.make_attn(B, 1, N, 128, 128, seed=21)]
+    other = [t.cuda() for t in bb_inputs.make_attn(20, 1, 777, 128, 128, seed=22)]
+    out_g = torch.empty((B, 1, 128), dtype=torch.bfloat16, device="cuda")
+    out_e = torch.empty_like(out_g)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        bb.bb_attention(*other)                        # warm-up: workspace and counters for the larger batch
+        bb.bb_attention(Q, K, V, O=out_g)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        bb.bb_attention(Q, K, V, O=out_g)
+    for rep in range(4):
+        Q.copy_(bb_inputs.make_attn(B, 1, N, 128, 128, seed=50 + rep)[0].cuda())
+        graph.replay()
+        torch.cuda.synchronize()
+        bb.bb_attention(Q, K, V, O=out_e)              # eager, same inputs
+        bb.bb_attention(*other)
+        torch.cuda.synchronize()
+        assert torch.equal(out_g.view(torch.uint16), out_e.view(torch.uint16)), rep
+    ref = orc.attention(Q.cpu(), K.cpu(), V.cpu())
+    assert rel_err(out_g.reshape(-1, 128), ref) <= TOL
