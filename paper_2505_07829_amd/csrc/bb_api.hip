@@ -11,8 +11,10 @@
 #include <tuple>
 
 #include "../../include/bb.h"
+#define BB_HOST_ONLY        // the streaming kernels themselves are compiled in bb_stream_inst.hip
 #include "bb_attn.h"
 #include "bb_gemm.h"
+#include "bb_launch.h"
 #include "bb_misc.h"
 #include "bb_stream.h"
 #include "bb_stream_t.h"
@@ -398,7 +400,9 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
     a.tiles_n = (N + ncol - 1) / ncol;
     const int tiles256 = ((M + 255) / 256) * a.tiles_n;
     int nk_split = 0, split_bm = 128;
-    const int nsplit = split ? plan_split(MODE, M, N, K, cus, &nk_split, &split_bm) : 1;
+    // (planned for kPlanCUs compute units whatever the device has: the scratch for the partial results was sized with
+    // that plan, and a plan for fewer units can ask for more splits than it has room for)
+    const int nsplit = split ? plan_split(MODE, M, N, K, kPlanCUs, &nk_split, &split_bm) : 1;
     const bool do_split = nsplit >= 2;
     const bool big = do_split ? split_bm == 256 : tiles256 >= cus;
     const int BM = big ? 256 : 128;
@@ -422,36 +426,16 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
     const bool small = (size_t)M * lda * 2 < (1ull << 32) && bbytes < (1ull << 32);
     const bool full = (M % BM == 0) && (N % ncol == 0) && (K % GEMM_BK == 0) && small;
     const bool odd = ((do_split ? nk_split : (K + GEMM_BK - 1) / GEMM_BK) & 1) != 0;
-    using T = std::true_type;
-    using F_ = std::false_type;
-    auto go = [&](auto BMc, auto FULLc, auto ODDc) {
-        hipLaunchKernelGGL((gemm_kernel<MODE, decltype(BMc)::value, decltype(FULLc)::value, decltype(ODDc)::value, false, BT>),
-                           grid, block, 0, st, a);
-    };
-    auto go2 = [&](auto BMc, auto FULLc) { if (odd) go(BMc, FULLc, T()); else go(BMc, FULLc, F_()); };
     if (do_split) {
         constexpr int SM = (MODE == MODE_PLAIN || MODE == MODE_GATEUP) ? MODE : MODE_PLAIN;   // (the others are never split)
-        if (big) {
-            // (PLAIN only) 256-row tiles; complete tiles and equal shares of the contraction run without bounds checks
-            constexpr int PM = MODE_PLAIN;
-            const bool sfull = full && ((K + GEMM_BK - 1) / GEMM_BK) % nsplit == 0;
-            if (sfull && odd) hipLaunchKernelGGL((gemm_kernel<PM, 256, true, true, true, BT>), grid, block, 0, st, a);
-            else if (sfull) hipLaunchKernelGGL((gemm_kernel<PM, 256, true, false, true, BT>), grid, block, 0, st, a);
-            else if (odd) hipLaunchKernelGGL((gemm_kernel<PM, 256, false, true, true, BT>), grid, block, 0, st, a);
-            else hipLaunchKernelGGL((gemm_kernel<PM, 256, false, false, true, BT>), grid, block, 0, st, a);
-        } else if (odd) {
-            hipLaunchKernelGGL((gemm_kernel<SM, 128, false, true, true, BT>), grid, block, 0, st, a);
-        } else {
-            hipLaunchKernelGGL((gemm_kernel<SM, 128, false, false, true, BT>), grid, block, 0, st, a);
-        }
+        // 256-row tiles (PLAIN only): complete tiles and equal shares of the contraction run without bounds checks
+        const bool sfull = big && full && ((K + GEMM_BK - 1) / GEMM_BK) % nsplit == 0;
+        gemm_dispatch<SM, BT>(BM, sfull, odd, true, grid, st, a);
         BB_HIP(hipGetLastError());
-        const size_t threads = (size_t)M * (N / 8);
-        hipLaunchKernelGGL((splitk_reduce_kernel<SM>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
-                           (const float*)a.part, (const float*)a.ssqpart, C, M, N, K, a.ldp, ldc, nsplit, eps, res, ldr);
-    } else if (big) {
-        if (full) go2(std::integral_constant<int, 256>(), T()); else go2(std::integral_constant<int, 256>(), F_());
+        splitk_reduce_dispatch(SM, (const float*)a.part, (const float*)a.ssqpart, C, M, N, K, a.ldp, ldc, nsplit, eps,
+                               res, ldr, st);
     } else {
-        if (full) go2(std::integral_constant<int, 128>(), T()); else go2(std::integral_constant<int, 128>(), F_());
+        gemm_dispatch<MODE, BT>(BM, full, odd, false, grid, st, a);
     }
     BB_HIP(hipGetLastError());
     prof_mark(MODE == MODE_GATEUP ? "gemm_gateup" : MODE == MODE_GATEUP_PRE ? "gemm_gateup_prescaled"
@@ -473,8 +457,9 @@ int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u
                int D, int F, float eps, int cus, hipStream_t st) {
     static int resident = -1;      // workgroups of the streaming kernel one compute unit can hold
     if (resident < 0) {
-        int n = 0;
-        BB_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, ffn_stream_kernel, STREAM_THREADS, 0));
+        hipError_t e = hipSuccess;
+        const int n = stream_resident(&e);
+        BB_HIP(e);
         resident = n;
     }
     if (resident < 1) return BB_ERR_VARIANT;   // the grid barrier needs every workgroup resident
@@ -500,7 +485,7 @@ int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u
         std::fprintf(stderr, "[bb] stream M %d D %d F %d items %d/%d per wg %d/%d slots %d/%d\n", M, D, F,
                      a.items1, a.items2, a.per1, a.per2, a.S1, a.S2);
     prof_begin(st);   // (a refill of the barrier word above, if any, is not part of the kernel's time)
-    hipLaunchKernelGGL(ffn_stream_kernel, dim3(G), dim3(STREAM_THREADS), 0, st, a);
+    stream_launch(G, st, a);
     BB_HIP(hipGetLastError());
     prof_mark("ffn_stream", st);
     return BB_OK;
@@ -542,10 +527,9 @@ int run_stream_t(const u16* X, const u16* g, const u16* W1t, const u16* W3t, con
     if (!tp.ok) return BB_ERR_VARIANT;
     static int resident = -1;
     if (resident < 0) {
-        BB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_stream_t_kernel),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, STREAMT_LDS));
-        int nres = 0;
-        BB_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nres, ffn_stream_t_kernel, STREAMT_THREADS, tp.lds));
+        hipError_t e = hipSuccess;
+        const int nres = stream_t_resident(tp.lds, &e);
+        BB_HIP(e);
         resident = nres;
     }
     if (resident < 1) return BB_ERR_VARIANT;    // the grid barrier needs every workgroup resident
@@ -565,7 +549,7 @@ int run_stream_t(const u16* X, const u16* g, const u16* W1t, const u16* W3t, con
         std::fprintf(stderr, "[bb] stream_t M %d D %d F %d units/wg %d columns/wg %d kblk %d lds %d\n", M, D, F, a.upw,
                      a.cpw, a.kblk, tp.lds);
     prof_begin(st);
-    hipLaunchKernelGGL(ffn_stream_t_kernel, dim3(G), dim3(STREAMT_THREADS), tp.lds, st, a);
+    stream_t_launch(G, tp.lds, st, a);
     BB_HIP(hipGetLastError());
     prof_mark("ffn_stream_t", st);
     return BB_OK;
@@ -904,10 +888,10 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
         a.ml = (float*)((char*)g_ws.ptr + zone + pbytes);
         const dim3 grid((unsigned)(B * nsplit)), block(256);
         prof_begin(st);
-        if (d == 64 && dv == 64) hipLaunchKernelGGL((attention_decode_kernel<64, 64>), grid, block, 0, st, a);
-        else if (d == 64) hipLaunchKernelGGL((attention_decode_kernel<64, 128>), grid, block, 0, st, a);
-        else if (dv == 64) hipLaunchKernelGGL((attention_decode_kernel<128, 64>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((attention_decode_kernel<128, 128>), grid, block, 0, st, a);
+        if (d == 64 && dv == 64) attn_decode_launch<64, 64>(grid, st, a);
+        else if (d == 64) attn_decode_launch<64, 128>(grid, st, a);
+        else if (dv == 64) attn_decode_launch<128, 64>(grid, st, a);
+        else attn_decode_launch<128, 128>(grid, st, a);
         BB_HIP(hipGetLastError());
         prof_mark("attention", st);
         return BB_OK;
@@ -944,34 +928,10 @@ int bb_attention(const void* Q, const void* K, const void* V, void* O, int64_t B
     prof_begin(st);
     const int64_t nt = nt_all / ksplit;                            // key blocks per workgroup
     const int tail = nt <= 4 ? (int)nt : ((nt & 1) ? 3 : 4);     // iterations left after the main loop
-    auto go = [&](auto DKC, auto DVC) {
-        constexpr int DK = decltype(DKC)::value, DV = decltype(DVC)::value;
-        auto go_nw = [&](auto NWC) {
-            constexpr int NW = decltype(NWC)::value;
-            if (tail == 1) hipLaunchKernelGGL((attention_kernel<DK, DV, 1, NW>), grid, block, 0, st, a);
-            else if (tail == 2) hipLaunchKernelGGL((attention_kernel<DK, DV, 2, NW>), grid, block, 0, st, a);
-            else if (tail == 3) hipLaunchKernelGGL((attention_kernel<DK, DV, 3, NW>), grid, block, 0, st, a);
-            else hipLaunchKernelGGL((attention_kernel<DK, DV, 4, NW>), grid, block, 0, st, a);
-        };
-        if (ksplit > 1) {
-            if (tail == 1) hipLaunchKernelGGL((attention_kernel<DK, DV, 1, 4, true>), grid, block, 0, st, a);
-            else if (tail == 2) hipLaunchKernelGGL((attention_kernel<DK, DV, 2, 4, true>), grid, block, 0, st, a);
-            else if (tail == 3) hipLaunchKernelGGL((attention_kernel<DK, DV, 3, 4, true>), grid, block, 0, st, a);
-            else hipLaunchKernelGGL((attention_kernel<DK, DV, 4, 4, true>), grid, block, 0, st, a);
-            hipLaunchKernelGGL((attention_combine_kernel<DV>), dim3((unsigned)(B * M)), dim3(64), 0, st,
-                               (const float*)a.part, (const float*)a.ml, a.O, ksplit, a.c);
-        } else if (nw == 8) {
-            go_nw(std::integral_constant<int, 8>{});
-        } else {
-            go_nw(std::integral_constant<int, 4>{});
-        }
-    };
-    using I64 = std::integral_constant<int, 64>;
-    using I128 = std::integral_constant<int, 128>;
-    if (d == 64 && dv == 64) go(I64{}, I64{});
-    else if (d == 64) go(I64{}, I128{});
-    else if (dv == 64) go(I128{}, I64{});
-    else go(I128{}, I128{});
+    if (d == 64 && dv == 64) attn_tiled_launch<64, 64>(tail, nw, ksplit, grid, block, st, a);
+    else if (d == 64) attn_tiled_launch<64, 128>(tail, nw, ksplit, grid, block, st, a);
+    else if (dv == 64) attn_tiled_launch<128, 64>(tail, nw, ksplit, grid, block, st, a);
+    else attn_tiled_launch<128, 128>(tail, nw, ksplit, grid, block, st, a);
     BB_HIP(hipGetLastError());
     prof_mark("attention", st);
     return BB_OK;

@@ -1,0 +1,6 @@
+// attention kernel instantiations: head dimensions d = 64, dv = 128
+#include "bb_attn_inst.h"
+namespace bb {
+template void attn_tiled_launch<64, 128>(int, int, int, dim3, dim3, hipStream_t, const AttnArgs&);
+template void attn_decode_launch<64, 128>(dim3, hipStream_t, const AttnArgs&);
+}

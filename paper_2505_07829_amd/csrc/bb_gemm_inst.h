@@ -1,0 +1,48 @@
+// Body of gemm_dispatch<MODE, BT>: maps the run-time launch shape onto the
+// instantiations of gemm_kernel.  Included by the bb_gemm_inst_*.hip sources,
+// each of which instantiates it for one MODE and one weight layout, so that
+// the instantiations compile side by side.
+#pragma once
+#include <type_traits>
+
+#include "bb_gemm.h"
+#include "bb_launch.h"
+
+namespace bb {
+
+template <int MODE, bool BT>
+void gemm_dispatch(int bm, bool full, bool odd, bool split, dim3 grid, hipStream_t st, const GemmArgs& a) {
+    const dim3 block(GEMM_THREADS);
+    using T = std::true_type;
+    using F_ = std::false_type;
+    auto go = [&](auto BMc, auto FULLc, auto ODDc, auto SPLITc) {
+        hipLaunchKernelGGL((gemm_kernel<MODE, decltype(BMc)::value, decltype(FULLc)::value, decltype(ODDc)::value,
+                                        decltype(SPLITc)::value, BT>),
+                           grid, block, 0, st, a);
+    };
+    auto by_odd = [&](auto BMc, auto FULLc, auto SPLITc) {
+        if (odd) go(BMc, FULLc, T(), SPLITc); else go(BMc, FULLc, F_(), SPLITc);
+    };
+    using B128 = std::integral_constant<int, 128>;
+    using B256 = std::integral_constant<int, 256>;
+    if (split) {
+        if constexpr (MODE == MODE_PLAIN || MODE == MODE_GATEUP) {
+            if (bm == 256) {
+                // (PLAIN only) 256-row tiles; complete tiles and equal shares of the contraction run without bounds checks
+                if constexpr (MODE == MODE_PLAIN) {
+                    if (full) by_odd(B256(), T(), T()); else by_odd(B256(), F_(), T());
+                }
+            } else {
+                by_odd(B128(), F_(), T());
+            }
+        }
+        return;
+    }
+    if (bm == 256) {
+        if (full) by_odd(B256(), T(), F_()); else by_odd(B256(), F_(), F_());
+    } else {
+        if (full) by_odd(B128(), T(), F_()); else by_odd(B128(), F_(), F_());
+    }
+}
+
+}  // namespace bb

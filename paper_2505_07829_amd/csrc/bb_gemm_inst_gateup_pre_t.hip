@@ -1,0 +1,5 @@
+// gemm_kernel instantiations: MODE_GATEUP_PRE, weights transposed ([N, K])
+#include "bb_gemm_inst.h"
+namespace bb {
+template void gemm_dispatch<MODE_GATEUP_PRE, true>(int, bool, bool, bool, dim3, hipStream_t, const GemmArgs&);
+}

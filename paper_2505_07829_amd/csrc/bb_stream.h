@@ -187,6 +187,7 @@ __device__ __forceinline__ void stream_ready(StreamItem1& r) {
 }
 constexpr int STREAM_ITEM1_LOADS = 18;
 
+#ifndef BB_HOST_ONLY   // (bb_api.hip includes this file for the argument structures only)
 __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const StreamArgs p) {
     __shared__ StreamSmem sm;
     const int t = threadIdx.x, lane = t & 63;
@@ -528,5 +529,6 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
     }
     BB_STREAM_TRACE(7);
 }
+#endif  // BB_HOST_ONLY
 
 }  // namespace bb

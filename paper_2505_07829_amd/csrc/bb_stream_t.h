@@ -150,6 +150,7 @@ __device__ __forceinline__ void async_ready(u32x4 (&a)[4], u32x4 (&b)[4]) {
 // cached copy.  Measured alternatives for the reads, phase 2 alone with the weight loads off:
 // agent-scope loads 10.7 us, ordinary loads behind an agent-scope acquire fence 16 us (the fence
 // invalidates the whole L2), ordinary loads without the fence (not coherent) 9.4 us.
+#ifndef BB_HOST_ONLY   // (bb_api.hip includes this file for the argument structures only)
 __global__ __launch_bounds__(STREAMT_THREADS) void ffn_stream_t_kernel(const StreamTArgs p) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int t = threadIdx.x, lane = t & 63;
@@ -449,5 +450,6 @@ __global__ __launch_bounds__(STREAMT_THREADS) void ffn_stream_t_kernel(const Str
     }
     BB_STREAM_TRACE(7);
 }
+#endif  // BB_HOST_ONLY
 
 }  // namespace bb

@@ -2,22 +2,24 @@
 spill or a register copy between such a load and its wait.  This compiles the library's device code
 to assembly (no GPU needed) and runs the static check that ships next to the kernels."""
 import os
-import shutil
 import subprocess
 import sys
 
 import pytest
+
+from paper_2505_07829_amd import build as bb_build
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 CSRC = os.path.join(ROOT, "paper_2505_07829_amd", "csrc")
 KERNELS = ["_ZN2bb17ffn_stream_kernelENS_10StreamArgsE", "_ZN2bb19ffn_stream_t_kernelENS_11StreamTArgsE"]
 
 
-@pytest.mark.skipif(shutil.which("hipcc") is None, reason="hipcc not on PATH")
 def test_no_instruction_touches_a_register_whose_load_is_in_flight(tmp_path):
-    asm = tmp_path / "bb_api.s"
-    cmd = ["hipcc", "-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-S", "--cuda-device-only", "-o", str(asm), os.path.join(CSRC, "bb_api.hip")]
+    # the compiler and the flags of the shipped build (paper_2505_07829_amd/build.py), device code to assembly
+    assert os.path.exists(bb_build.HIPCC), f"{bb_build.HIPCC} not found: the check cannot run"
+    asm = tmp_path / "bb_stream_inst.s"
+    cmd = [bb_build.HIPCC, *bb_build.HIPCC_FLAGS, "-S", "--cuda-device-only", "-o", str(asm),
+           os.path.join(CSRC, "bb_stream_inst.hip")]
     subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL, timeout=900)
     r = subprocess.run([sys.executable, os.path.join(CSRC, "check_inflight.py"), str(asm)] + KERNELS,
                        capture_output=True, text=True, timeout=300)
