@@ -354,15 +354,25 @@ int bb_version(void);
 int bb_last_hip_error(void); /* raw hipError_t of the last BB_ERR_HIP, else 0 */
 
 /* ------------------------------------------------------------------------
- * Per-kernel timing of the most recent operator call, for roofline reports.
+ * Per-kernel timing of the most recent operator calls, for roofline reports.
  * While enabled, every operator call records a HIP event on its stream before
  * its first kernel and after each kernel (this serialises nothing but adds a
- * few event packets, so time whole calls with profiling off).
- * bb_profile_count: kernels recorded by the last call.
- * bb_profile_get:   waits for kernel i of the last call and returns its
- *                   duration in ms and a static name (host pointers).
+ * few event packets, so time whole calls with profiling off).  The last 64
+ * calls are kept, so kernels can be timed inside a run of back-to-back calls
+ * (a call timed alone starts on an idle chip and reads longer).
+ * bb_profile_enable: switches recording on or off and forgets what was kept.
+ * bb_profile_calls:  calls kept (at most 64).
+ * bb_profile_count_of / bb_profile_get_of: kernels recorded by the call `back`
+ *                   calls before the most recent one (0 = the most recent);
+ *                   waits for kernel i of that call and returns its duration
+ *                   in ms and a static name (host pointers).  BB_ERR_SHAPE for
+ *                   an index out of range.
+ * bb_profile_count / bb_profile_get: the same for the most recent call.
  */
 int bb_profile_enable(int on);
+int bb_profile_calls(void);
+int bb_profile_count_of(int back);
+int bb_profile_get_of(int back, int i, float* ms, const char** name);
 int bb_profile_count(void);
 int bb_profile_get(int i, float* ms, const char** name);
 

@@ -27,7 +27,8 @@ EXPORTS = [
     "bb_workspace_bytes", "bb_set_workspace", "bb_set_variant", "bb_get_variant",
     "bb_shutdown", "bb_status_string", "bb_version", "bb_last_hip_error",
     "bb_calib_copy", "bb_calib_read", "bb_calib_mfma", "bb_calib_mfma_data",
-    "bb_profile_enable", "bb_profile_count", "bb_profile_get",
+    "bb_profile_enable", "bb_profile_count", "bb_profile_get", "bb_profile_calls", "bb_profile_count_of",
+    "bb_profile_get_of",
 ]
 
 _lib = None
@@ -80,6 +81,8 @@ def load() -> ctypes.CDLL:
     lib.bb_calib_mfma_data.argtypes = [vp, ci, ci, vp, vp]
     lib.bb_profile_enable.argtypes = [ci]
     lib.bb_profile_get.argtypes = [ci, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_char_p)]
+    lib.bb_profile_count_of.argtypes = [ci]
+    lib.bb_profile_get_of.argtypes = [ci, ci, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_char_p)]
     for name in EXPORTS:
         fn = getattr(lib, name)
         if name not in ("bb_workspace_bytes", "bb_status_string", "bb_attention_workspace_bytes"):
@@ -316,12 +319,18 @@ def bb_profile_enable(on: bool) -> None:
     _check(load().bb_profile_enable(1 if on else 0), "bb_profile_enable")
 
 
-def bb_profile_last():
-    """[(kernel name, milliseconds)] of the most recent operator call (waits for it)."""
+def bb_profile_last(back: int = 0):
+    """[(kernel name, milliseconds)] of the operator call `back` calls before the most recent one (waits for it)."""
     lib = load()
     out = []
-    for i in range(int(lib.bb_profile_count())):
+    for i in range(int(lib.bb_profile_count_of(int(back)))):
         ms, name = ctypes.c_float(), ctypes.c_char_p()
-        _check(lib.bb_profile_get(i, ctypes.byref(ms), ctypes.byref(name)), "bb_profile_get")
+        _check(lib.bb_profile_get_of(int(back), i, ctypes.byref(ms), ctypes.byref(name)), "bb_profile_get_of")
         out.append((name.value.decode(), float(ms.value)))
     return out
+
+
+def bb_profile_history():
+    """[[(kernel name, milliseconds)]] of the calls kept since profiling was switched on, oldest first."""
+    n = int(load().bb_profile_calls())
+    return [bb_profile_last(back) for back in range(n - 1, -1, -1)]

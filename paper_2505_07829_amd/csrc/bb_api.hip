@@ -41,14 +41,21 @@ struct Workspace {
     int device = -1;
 } g_ws;
 
-// optional per-kernel timing of the most recent call (bb_profile_*)
+// optional per-kernel timing of the most recent calls (bb_profile_*): a ring of the last kProfRing
+// operator calls, so that a caller can time kernels inside a run of back-to-back calls
 constexpr int kMaxProf = 8;
-struct Profile {
-    bool on = false;
-    int n = 0;                         // kernels recorded by the last call
+constexpr int kProfRing = 64;
+struct ProfCall {
+    int n = 0;                         // kernels recorded by this call
     hipEvent_t ev[kMaxProf + 1] = {};
     const char* name[kMaxProf] = {};
+};
+struct Profile {
+    bool on = false;
     bool created = false;
+    long calls = 0;                    // operator calls recorded since profiling was switched on
+    ProfCall ring[kProfRing];
+    ProfCall& cur() { return ring[(calls + kProfRing - 1) % kProfRing]; }   // the most recent call (calls >= 1)
 } g_prof;
 
 struct DeviceInfo {
@@ -146,14 +153,18 @@ int ln_unfused_locked(const void* X, const void* gamma, const void* beta, const 
 
 void prof_begin(hipStream_t st) {
     if (!g_prof.on) return;
-    g_prof.n = 0;
-    (void)hipEventRecord(g_prof.ev[0], st);
+    ++g_prof.calls;
+    ProfCall& c = g_prof.cur();
+    c.n = 0;
+    (void)hipEventRecord(c.ev[0], st);
 }
 void prof_mark(const char* name, hipStream_t st) {
-    if (!g_prof.on || g_prof.n >= kMaxProf) return;
-    g_prof.name[g_prof.n] = name;
-    ++g_prof.n;
-    (void)hipEventRecord(g_prof.ev[g_prof.n], st);
+    if (!g_prof.on || g_prof.calls == 0) return;
+    ProfCall& c = g_prof.cur();
+    if (c.n >= kMaxProf) return;
+    c.name[c.n] = name;
+    ++c.n;
+    (void)hipEventRecord(c.ev[c.n], st);
 }
 
 // ---------------------------------------------------------------- validation
@@ -1123,28 +1134,42 @@ int bb_tune_clear(void) {
 int bb_profile_enable(int on) {
     std::lock_guard<std::mutex> lk(g_mu);
     if (on && !g_prof.created) {
-        for (int i = 0; i <= kMaxProf; ++i) BB_HIP(hipEventCreate(&g_prof.ev[i]));
+        for (auto& c : g_prof.ring)
+            for (int i = 0; i <= kMaxProf; ++i) BB_HIP(hipEventCreate(&c.ev[i]));
         g_prof.created = true;
     }
     g_prof.on = on != 0;
-    g_prof.n = 0;
+    g_prof.calls = 0;
+    for (auto& c : g_prof.ring) c.n = 0;
     return BB_OK;
 }
 
-int bb_profile_count(void) {
+int bb_profile_calls(void) {
     std::lock_guard<std::mutex> lk(g_mu);
-    return g_prof.n;
+    return (int)std::min<long>(g_prof.calls, kProfRing);
 }
 
-int bb_profile_get(int i, float* ms, const char** name) {
+int bb_profile_count_of(int back) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (back < 0 || back >= std::min<long>(g_prof.calls, kProfRing)) return 0;
+    return g_prof.ring[(g_prof.calls - 1 - back) % kProfRing].n;
+}
+
+int bb_profile_get_of(int back, int i, float* ms, const char** name) {
     std::lock_guard<std::mutex> lk(g_mu);
     if (!ms) return BB_ERR_NULL;
-    if (!g_prof.created || i < 0 || i >= g_prof.n) return BB_ERR_SHAPE;
-    BB_HIP(hipEventSynchronize(g_prof.ev[i + 1]));
-    BB_HIP(hipEventElapsedTime(ms, g_prof.ev[i], g_prof.ev[i + 1]));
-    if (name) *name = g_prof.name[i];
+    if (!g_prof.created || back < 0 || back >= std::min<long>(g_prof.calls, kProfRing)) return BB_ERR_SHAPE;
+    ProfCall& c = g_prof.ring[(g_prof.calls - 1 - back) % kProfRing];
+    if (i < 0 || i >= c.n) return BB_ERR_SHAPE;
+    BB_HIP(hipEventSynchronize(c.ev[i + 1]));
+    BB_HIP(hipEventElapsedTime(ms, c.ev[i], c.ev[i + 1]));
+    if (name) *name = c.name[i];
     return BB_OK;
 }
+
+int bb_profile_count(void) { return bb_profile_count_of(0); }
+
+int bb_profile_get(int i, float* ms, const char** name) { return bb_profile_get_of(0, i, ms, name); }
 
 // ------------------------------------------------------------- calibration
 int bb_calib_copy(const void* src, void* dst, size_t bytes, void* stream) {

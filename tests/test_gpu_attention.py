@@ -12,6 +12,7 @@ import pytest
 import torch
 
 import bb_inputs
+import bb_parity
 import paper_2505_07829_amd as bb
 from oracle import oracle as orc
 
@@ -20,12 +21,10 @@ TOL = 2e-2
 
 
 def rel_err(O_gpu, O_ref):
-    o = O_gpu.float().cpu().numpy().astype(np.float64)
-    assert np.all(np.isfinite(o))
-    num = np.linalg.norm(o - O_ref, axis=1)
-    den = np.linalg.norm(O_ref, axis=1)
-    assert np.all(den > 0)
-    return float((num / den).max())
+    """the row figure; the element-wise gate (bb_parity.py) is asserted on the way"""
+    row, elem = bb_parity.errors(O_gpu, O_ref)
+    assert elem <= bb_parity.TOL_ELEM, f"element error {elem:.3e} > {bb_parity.TOL_ELEM} (row error {row:.3e})"
+    return row
 
 
 def run(Q, K, V, rows=None):

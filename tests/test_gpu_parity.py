@@ -1,7 +1,8 @@
 """GPU parity: the HIP library (through its C ABI) against the fp64 oracle on
-the same seeded inputs.  Gate (both operators):
+the same seeded inputs.  Gates (both operators; bb_parity.py derives the second):
 
-    max_i || Ygpu[i,:] - Yref[i,:] ||_2 / || Yref[i,:] ||_2  <=  2e-2
+    max_i  || Ygpu[i,:] - Yref[i,:] ||_2 / || Yref[i,:] ||_2                   <=  2e-2
+    max_ij | Ygpu[i,j] - Yref[i,j] | / ( || Yref[i,:] ||_2 / sqrt(columns) )   <=  3e-2
 
 bf16 operands, fp32 accumulation; the oracle sees the same bf16-rounded inputs.
 """
@@ -10,6 +11,7 @@ import pytest
 import torch
 
 import bb_inputs
+import bb_parity
 import paper_2505_07829_amd as bb
 from oracle import oracle as orc
 
@@ -22,16 +24,15 @@ def dev(ts):
 
 
 def row_rel_err(Y_gpu, Y_ref):
-    y = Y_gpu.float().cpu().numpy().astype(np.float64)
-    num = np.linalg.norm(y - Y_ref, axis=1)
-    den = np.linalg.norm(Y_ref, axis=1)
-    assert np.all(np.isfinite(y))
-    assert np.all(den > 0)
-    return float((num / den).max())
+    """the row figure; the element-wise gate is asserted on the way (every comparison in this file passes here)"""
+    row, elem = bb_parity.errors(Y_gpu, Y_ref)
+    assert elem <= bb_parity.TOL_ELEM, f"element error {elem:.3e} > {bb_parity.TOL_ELEM} (row error {row:.3e})"
+    return row
 
 
-def sample_rows(M, tile=256, extra=6, seed=0):
-    """first/last row of every row tile plus a few random rows"""
+def sample_rows(M, tile=128, extra=6, seed=0):
+    """first/last row of every row tile of the kernels (128 rows: every 256-row tile's edges are among them)
+    plus a few random rows"""
     rows = set()
     for t0 in range(0, M, tile):
         rows.add(t0); rows.add(min(M, t0 + tile) - 1)
@@ -254,7 +255,7 @@ def test_c3_prefill_sampled_rows():
 def test_c4_large_sampled_rows():
     c = bb_inputs.CONFIGS["c4"]
     cpu = bb_inputs.make_config("c4")
-    rows = sample_rows(c.M, tile=1024, extra=2)
+    rows = sample_rows(c.M, extra=2)
     err = ffn_case(cpu, c.eps, rows=rows)
     print("c4 rel err", err, "rows", len(rows))
     assert err <= TOL
@@ -263,7 +264,7 @@ def test_c4_large_sampled_rows():
 def test_c5_ln_sampled_rows():
     c = bb_inputs.CONFIGS["c5"]
     cpu = bb_inputs.make_config("c5")
-    rows = sample_rows(c.M, tile=1024, extra=4)
+    rows = sample_rows(c.M, extra=4)
     Y = bb.bb_layernorm_matmul(*dev(cpu), c.eps)
     torch.cuda.synchronize()
     ref = orc.layernorm_matmul(*cpu, c.eps, rows=rows)
@@ -383,7 +384,7 @@ def test_split_contraction_256_row_tiles(M, D, F):
     # tiles with the contraction split over workgroups (also through the transposed layout and
     # with the residual added by the reduce kernel)
     cpu = bb_inputs.make_ffn(M, D, F, seed=M + F)
-    rows = sample_rows(M, tile=256, extra=10, seed=1)
+    rows = sample_rows(M, extra=10, seed=1)
     X, g, W1, W3, W2 = cpu
     ref = orc.rmsnorm_swiglu_ffn(X, g, W1, W3, W2, 1e-6, rows=rows)
     d = dev(cpu)
