@@ -74,28 +74,34 @@ def roofline_block(kernel, bound, work, ms, traffic, step_work=None, step_ms=Non
 # read 0.59, 0.57, 0.53, 0.51, 0.50, 0.49 ms and then stay at 0.486 ms, i.e. the first ~30 ms of any burst of
 # work run up to 20 % slow.  Between two measurements of this script the GPU idles (inputs are generated on
 # the CPU, the oracle is timed), and `--warmup 5` is 3 ms of work.  So every timed region is preceded by
-# PRECONDITION_MS of a matrix-instruction loop (bb_calib_mfma_data: not a step of the workload, nothing of it is
-# cached or skipped) that brings the clocks to the state sustained work runs in; then the W warm-up steps,
-# then the K timed steps.
+# PRECONDITION_MS of a calibration kernel (not a step of the workload, nothing of it is cached or skipped) that
+# brings the clocks to the state sustained work runs in: a matrix-instruction loop (bb_calib_mfma_data) before
+# matrix-bound workloads, a streaming read of 1 GiB (bb_calib_read) before bandwidth-bound ones; then the W
+# warm-up steps, then the K timed steps.
 PRECONDITION_MS = 100.0
 _precond = {}
 
 
-def precondition(torch, bb):
+def precondition(torch, bb, kind="mfma"):
     if not _precond:
         g = torch.Generator(device="cpu"); g.manual_seed(1)
         _precond["ops"] = torch.randn(16384, generator=g).to(torch.bfloat16).cuda()
         _precond["sink"] = torch.zeros(4096, dtype=torch.float32, device="cuda")
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        bb.bb_calib_mfma_data(_precond["ops"], 1024, 500, _precond["sink"])
-        torch.cuda.synchronize()
-        e0.record()
-        bb.bb_calib_mfma_data(_precond["ops"], 1024, 500, _precond["sink"])
-        e1.record()
-        torch.cuda.synchronize()
-        _precond["reps"] = max(1, int(PRECONDITION_MS / max(e0.elapsed_time(e1), 1e-3)))
-    for _ in range(_precond["reps"]):
-        bb.bb_calib_mfma_data(_precond["ops"], 1024, 500, _precond["sink"])
+        _precond["buf"] = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+        fns = {"mfma": lambda: bb.bb_calib_mfma_data(_precond["ops"], 1024, 500, _precond["sink"]),
+               "hbm": lambda: bb.bb_calib_read(_precond["buf"], _precond["sink"])}
+        _precond["fn"] = fns
+        for k, fn in fns.items():
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            fn()
+            torch.cuda.synchronize()
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            _precond["reps_" + k] = max(1, int(PRECONDITION_MS / max(e0.elapsed_time(e1), 1e-3)))
+    for _ in range(_precond["reps_" + kind]):
+        _precond["fn"][kind]()
 
 
 def flops_of(cfg):
@@ -139,8 +145,10 @@ def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np, c
         else:
             bb.bb_layernorm_matmul(*d, cfg.eps, Y=out, unfused=unfused)
 
+    pkind = "hbm" if stream_variant else "mfma"
+
     def timed(unfused=False):
-        precondition(torch, bb)
+        precondition(torch, bb, pkind)
         for i in range(warmup):
             step(i, unfused)
         torch.cuda.synchronize()
@@ -162,7 +170,7 @@ def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np, c
 
     # per-kernel durations: HIP events recorded by the library on the launch stream around every kernel of
     # `steps` back-to-back calls (at most 64 are kept), read after the run
-    precondition(torch, bb)
+    precondition(torch, bb, pkind)
     bb.bb_profile_enable(True)
     per = {}
     for i in range(min(steps, 64)):
@@ -213,7 +221,7 @@ def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np, c
         tsets = [[d[0], d[1]] + [w.t().contiguous() for w in d[2:]] for d in dev_sets]
         def stept(i):
             bb.bb_rmsnorm_swiglu_ffn_t(*tsets[i % nsets], cfg.eps, Y=out)
-        precondition(torch, bb)
+        precondition(torch, bb, pkind)
         for i in range(warmup):
             stept(i)
         torch.cuda.synchronize()
@@ -242,7 +250,7 @@ def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np, c
         def stepr(i):
             d = dev_sets[i % nsets]
             bb.bb_rmsnorm_swiglu_ffn_residual(*d, d[0], cfg.eps, Y=out)
-        precondition(torch, bb)
+        precondition(torch, bb, pkind)
         for i in range(warmup):
             stepr(i)
         torch.cuda.synchronize()
@@ -375,7 +383,7 @@ def run_attention(steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np):
     cpu_d = bb_inputs.make_attn(wd["B"], 1, wd["N"], wd["d"], wd["dv"], seed=1)
     Qd, Kd, Vd = [t.cuda() for t in cpu_d]
     Od = torch.empty((wd["B"], 1, wd["dv"]), dtype=torch.bfloat16, device="cuda")
-    precondition(torch, bb)
+    precondition(torch, bb, "hbm")
     for _ in range(warmup):
         bb.bb_attention(Qd, Kd, Vd, Od)
     torch.cuda.synchronize()
@@ -529,8 +537,9 @@ def main():
         "ms_per_step": primary["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "precondition": f"{PRECONDITION_MS:.0f} ms of bb_calib_mfma_data before the warm-up steps of every timed region "
-                        "(the chip leaves its idle power state over the first ~30 ms of work)",
+        "precondition": f"{PRECONDITION_MS:.0f} ms of a calibration kernel (bb_calib_mfma_data; bb_calib_read before "
+                        "bandwidth-bound workloads) before the warm-up steps of every timed region (the chip leaves "
+                        "its idle power state over the first ~30 ms of work)",
         "config": {"workload": f"{args.workload}: {primary['op']} M={primary['M']} D={primary['D']} "
                                f"F_or_N={primary['F_or_N']} ({primary['variant']})"},
         "roofline": primary["roofline"],

@@ -42,7 +42,10 @@ typedef enum bb_status {
     BB_ERR_ARCH = -6,      /* the current device is not gfx950                    */
     BB_ERR_WORKSPACE = -7, /* workspace missing, too small or misaligned          */
     BB_ERR_HIP = -8,       /* a HIP call failed; see bb_last_hip_error()          */
-    BB_ERR_VARIANT = -9    /* unknown variant, or one that cannot run this shape  */
+    BB_ERR_VARIANT = -9,   /* unknown variant, or one that cannot run this shape  */
+    BB_ERR_TIMEOUT = -10   /* a weight-streaming kernel of an EARLIER launch gave
+                              up waiting for another workgroup: that launch's
+                              output is invalid (see bb_check_fault)              */
 } bb_status;
 
 /* Which fused block program of Example 3 a call of bb_rmsnorm_swiglu_ffn runs.
@@ -352,6 +355,32 @@ int bb_shutdown(void);
 const char* bb_status_string(int status);
 int bb_version(void);
 int bb_last_hip_error(void); /* raw hipError_t of the last BB_ERR_HIP, else 0 */
+
+/* ------------------------------------------------------------------------
+ * Failure of a weight-streaming launch (BB_VARIANT_STREAM kernels, both
+ * weight layouts).  Their workgroups wait for each other inside the kernel
+ * (Example 3's epilogue: the parallel K-map hands partial results from
+ * processor to processor), which needs every workgroup resident at once: the
+ * launch must have the WHOLE device (no other kernel running beside it, on any
+ * stream), and its synchronisation words in the workspace must not be
+ * overwritten while it runs.  Every such wait is bounded (about two seconds).
+ * A wait that gives up lets the kernel run to its end with an INVALID output
+ * and sets a flag in host memory.  The flag is reported once, as
+ * BB_ERR_TIMEOUT, by the next bb_rmsnorm_swiglu_ffn* call on that device (which
+ * then launches nothing) or by bb_check_fault; either clears it and has the
+ * synchronisation words zeroed again before the next launch.  The flag is set by
+ * the kernel when it gives up, so it is seen only after that launch has run:
+ * synchronise the stream before bb_check_fault to learn about the launches
+ * issued so far.
+ * bb_check_fault:          BB_OK, or BB_ERR_TIMEOUT once per failure.
+ * bb_debug_inject_fault:   sets the flag from the host (tests of the path above).
+ * bb_debug_set_spin_limit: polls after which a wait gives up (default 8000000;
+ *                          0 = every wait that is not satisfied at once gives
+ *                          up, for tests: every kernel still runs to its end).
+ */
+int bb_check_fault(void);
+int bb_debug_inject_fault(void);
+int bb_debug_set_spin_limit(unsigned polls);
 
 /* ------------------------------------------------------------------------
  * Per-kernel timing of the most recent operator calls, for roofline reports.

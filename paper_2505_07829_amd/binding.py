@@ -15,6 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libbb.so")
 
 BB_OK = 0
+BB_ERR_TIMEOUT = -10
 VARIANT_AUTO, VARIANT_STREAM, VARIANT_SNAPSHOT1, VARIANT_UNFUSED, VARIANT_PRESCALE = 0, 1, 2, 3, 4
 OP_FFN, OP_LN, OP_FFN_UNFUSED, OP_LN_UNFUSED = 0, 1, 2, 3
 
@@ -28,7 +29,7 @@ EXPORTS = [
     "bb_shutdown", "bb_status_string", "bb_version", "bb_last_hip_error",
     "bb_calib_copy", "bb_calib_read", "bb_calib_mfma", "bb_calib_mfma_data",
     "bb_profile_enable", "bb_profile_count", "bb_profile_get", "bb_profile_calls", "bb_profile_count_of",
-    "bb_profile_get_of",
+    "bb_profile_get_of", "bb_check_fault", "bb_debug_inject_fault", "bb_debug_set_spin_limit",
 ]
 
 _lib = None
@@ -313,6 +314,19 @@ def bb_calib_mfma(workgroups: int, iters: int, sink) -> None:
 def bb_calib_mfma_data(operands, workgroups: int, iters: int, sink) -> None:
     _check(load().bb_calib_mfma_data(_ptr(operands), int(workgroups), int(iters), _ptr(sink), _stream()),
            "bb_calib_mfma_data")
+
+
+def bb_check_fault() -> None:
+    """Raises BBError(BB_ERR_TIMEOUT) once if a streaming kernel of an earlier launch gave up a wait."""
+    _check(load().bb_check_fault(), "bb_check_fault")
+
+
+def bb_debug_inject_fault() -> None:
+    _check(load().bb_debug_inject_fault(), "bb_debug_inject_fault")
+
+
+def bb_debug_set_spin_limit(polls: int) -> None:
+    _check(load().bb_debug_set_spin_limit(ctypes.c_uint(int(polls))), "bb_debug_set_spin_limit")
 
 
 def bb_profile_enable(on: bool) -> None:

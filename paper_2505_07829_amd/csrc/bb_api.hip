@@ -62,7 +62,12 @@ struct DeviceInfo {
     bool known = false;
     bool gfx950 = false;
     int cus = 0;
+    // one word of pinned host memory the streaming kernels write when a bounded wait on another workgroup
+    // gives up (mapped into the device: the kernels store to fault_dev, the host reads *fault_host)
+    volatile unsigned* fault_host = nullptr;
+    unsigned* fault_dev = nullptr;
 } g_dev[64];
+unsigned g_spin_limit = 8000000u;      // polls after which a wait on another workgroup gives up (about two seconds)
 
 bool log_on() {
     if (g_log < 0) g_log = std::getenv("BB_LOG") ? 1 : 0;
@@ -93,6 +98,15 @@ int current_device_info(const DeviceInfo** out) {
         BB_HIP(hipGetDeviceProperties(&prop, dev));
         d.gfx950 = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0;
         d.cus = prop.multiProcessorCount;
+        if (d.gfx950 && d.fault_host == nullptr) {
+            void* h = nullptr;
+            void* dp = nullptr;
+            BB_HIP(hipHostMalloc(&h, 64, hipHostMallocMapped));
+            *reinterpret_cast<volatile unsigned*>(h) = 0u;
+            BB_HIP(hipHostGetDevicePointer(&dp, h, 0));
+            d.fault_host = reinterpret_cast<volatile unsigned*>(h);
+            d.fault_dev = reinterpret_cast<unsigned*>(dp);
+        }
         d.known = true;
     }
     *out = &d;
@@ -464,8 +478,22 @@ int prepare_barrier_zone(const StreamPlan& sp, hipStream_t st) {
     return BB_OK;
 }
 
+// A streaming kernel of an earlier launch on this device gave up a bounded wait on another workgroup (it
+// did not have the whole device, or its synchronisation words had been overwritten): that launch's output is
+// invalid.  Reported ONCE, by the first call that notices; the flag is cleared and the zone is zeroed again
+// before the next launch (the barrier words and the kernels' count of completed barriers start over).
+int check_fault(const DeviceInfo* dev) {
+    if (dev->fault_host == nullptr || *dev->fault_host == 0u) return BB_OK;
+    *dev->fault_host = 0u;
+    g_ws.clean = 0;
+    g_ws.attn_zone = 0;
+    if (log_on()) std::fprintf(stderr, "[bb] a streaming kernel gave up a wait on another workgroup\n");
+    return BB_ERR_TIMEOUT;
+}
+
 int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u16* W2, const u16* R, u16* Y, int M,
-               int D, int F, float eps, int cus, hipStream_t st) {
+               int D, int F, float eps, const DeviceInfo* dev, hipStream_t st) {
+    const int cus = dev->cus;
     static int resident = -1;      // workgroups of the streaming kernel one compute unit can hold
     if (resident < 0) {
         hipError_t e = hipSuccess;
@@ -489,6 +517,8 @@ int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u
     a.bar = (unsigned*)(base + sp.bar_off);
     a.zeros = (const u16*)(base + sp.zero_off);
     a.epoch = (unsigned*)(base + sp.epoch_off);
+    a.fault = dev->fault_dev;
+    a.spin_limit = g_spin_limit;
     a.M = M; a.D = D; a.F = F; a.Fp = sp.Fp; a.eps = eps;
     a.nkb1 = sp.nkb1; a.nfb = sp.nfb; a.items1 = sp.items1; a.per1 = sp.per1; a.S1 = sp.S1;
     a.nkb2 = sp.nkb2; a.nnb = sp.nnb; a.items2 = sp.items2; a.per2 = sp.per2; a.S2 = sp.S2;
@@ -531,7 +561,8 @@ StreamTPlan stream_t_plan(int64_t D, int64_t F, int G) {
 
 // BB_ERR_VARIANT: not applicable to this shape or device (the caller falls back to the tiled kernels)
 int run_stream_t(const u16* X, const u16* g, const u16* W1t, const u16* W3t, const u16* W2t, const u16* R, u16* Y,
-                 int M, int D, int F, float eps, int cus, hipStream_t st) {
+                 int M, int D, int F, float eps, const DeviceInfo* dev, hipStream_t st) {
+    const int cus = dev->cus;
     if (M < 1 || M > kStreamMaxM) return BB_ERR_VARIANT;       // (the kernel clamps row numbers to M - 1)
     const int G = std::min(cus, kPlanCUs);
     const StreamTPlan tp = stream_t_plan(D, F, G);
@@ -553,6 +584,8 @@ int run_stream_t(const u16* X, const u16* g, const u16* W1t, const u16* W3t, con
     a.bar = (unsigned*)(base + sp.bar_off);
     a.zeros = (const u16*)(base + sp.zero_off);
     a.epoch = (unsigned*)(base + sp.epoch_off);
+    a.fault = dev->fault_dev;
+    a.spin_limit = g_spin_limit;
     a.M = M; a.D = D; a.F = F; a.Fp = sp.Fp; a.eps = eps;
     a.upw = tp.upw; a.cpw = tp.cpw; a.kblk = tp.kblk; a.cq2 = tp.cq2;
     a.red_off = tp.red_off; a.stat_off = tp.stat_off;
@@ -588,6 +621,7 @@ const char* bb_status_string(int s) {
         case BB_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
         case BB_ERR_HIP: return "HIP call failed";
         case BB_ERR_VARIANT: return "bad variant";
+        case BB_ERR_TIMEOUT: return "a streaming kernel of an earlier launch gave up waiting for another workgroup";
         default: return "unknown status";
     }
 }
@@ -602,6 +636,27 @@ int bb_set_variant(int v) {
 int bb_get_variant(void) {
     std::lock_guard<std::mutex> lk(g_mu);
     return read_variant();
+}
+
+int bb_check_fault(void) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    const DeviceInfo* dev = nullptr;
+    if (int rc = current_device_info(&dev)) return rc;
+    return check_fault(dev);
+}
+
+int bb_debug_inject_fault(void) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    const DeviceInfo* dev = nullptr;
+    if (int rc = current_device_info(&dev)) return rc;
+    *dev->fault_host = 1u;
+    return BB_OK;
+}
+
+int bb_debug_set_spin_limit(unsigned polls) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_spin_limit = polls;
+    return BB_OK;
 }
 
 size_t bb_workspace_bytes(int op, int64_t M, int64_t D, int64_t F) {
@@ -664,13 +719,14 @@ int ffn_locked(int variant, const void* X, const void* g, const void* W1, const 
     if (variant == BB_VARIANT_PRESCALE && M <= kStreamMaxM) return BB_ERR_VARIANT;   // (no room is planned for so few rows)
     const DeviceInfo* dev = nullptr;
     if (int rc = current_device_info(&dev)) return rc;
+    if (int rc = check_fault(dev)) return rc;
     const size_t zone = zone_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F);
     if (int rc = ensure_workspace(zone + scratch_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F))) return rc;
     hipStream_t st = as_stream(stream);
     const u16 *x = (const u16*)X, *gg = (const u16*)g, *w1 = (const u16*)W1, *w3 = (const u16*)W3,
               *w2 = (const u16*)W2;
     if (variant == BB_VARIANT_STREAM)
-        return run_stream(x, gg, w1, w3, w2, (const u16*)R, (u16*)Y, (int)M, (int)D, (int)F, eps, dev->cus, st);
+        return run_stream(x, gg, w1, w3, w2, (const u16*)R, (u16*)Y, (int)M, (int)D, (int)F, eps, dev, st);
     // first snapshot: hidden written once (bf16), then contracted with W2
     u16* H = (u16*)((char*)g_ws.ptr + zone);
     void* split = (char*)H + align_up((size_t)M * F * 2);
@@ -703,6 +759,7 @@ int ffn_t_locked(const void* X, const void* g, const void* W1t, const void* W3t,
                  int64_t M, int64_t D, int64_t F, float eps, void* stream, const void* R) {
     const DeviceInfo* dev = nullptr;
     if (int rc = current_device_info(&dev)) return rc;
+    if (int rc = check_fault(dev)) return rc;
     const size_t zone = zone_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F);
     if (int rc = ensure_workspace(zone + scratch_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F))) return rc;
     hipStream_t st = as_stream(stream);
@@ -710,7 +767,7 @@ int ffn_t_locked(const void* X, const void* g, const void* W1t, const void* W3t,
     const int variant = read_variant();
     if (M <= kStreamMaxM && (variant == BB_VARIANT_AUTO || variant == BB_VARIANT_STREAM)) {
         const int rc = run_stream_t((const u16*)X, (const u16*)g, (const u16*)W1t, (const u16*)W3t, (const u16*)W2t,
-                                    (const u16*)R, (u16*)Y, (int)M, (int)D, (int)F, eps, dev->cus, st);
+                                    (const u16*)R, (u16*)Y, (int)M, (int)D, (int)F, eps, dev, st);
         if (rc != BB_ERR_VARIANT) return rc;
     }
     u16* H = (u16*)((char*)g_ws.ptr + zone);

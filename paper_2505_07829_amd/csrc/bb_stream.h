@@ -30,6 +30,16 @@
 // into matrix-instruction operands without touching LDS.  The grid barrier is
 // a monotonically increasing counter in the workspace; its wait is bounded, so
 // the kernel always terminates.
+//
+// Contracts this file relies on (both checked by tests, neither a language
+// guarantee): (1) data handed from one workgroup to another is written with
+// agent-scope stores, the writer waits for their acknowledgement
+// (s_waitcnt vmcnt(0)) before its relaxed agent-scope atomic on the barrier
+// word, and the reader polls the flag with agent-scope loads before it reads the
+// data with agent-scope loads; (2) the weight stream is requested ahead with
+// inline-asm loads whose destination registers the compiler must not touch
+// before the matching s_waitcnt - check_inflight.py verifies that on the
+// compiled code.
 #pragma once
 #include "bb_common.h"
 
@@ -60,6 +70,8 @@ struct StreamArgs {
     const u16* zeros;  // 16 zero bytes in global memory: what a lane outside the matrices loads in phase 1
     unsigned* bar;     // BAR_WORDS barrier words (see grid_arrive), zero before the first call
     unsigned* epoch;   // one word next to them: grid barriers completed by earlier launches (kept by the kernels)
+    unsigned* fault;   // one word of host memory mapped into the device: set when a barrier's bounded wait gives up
+    unsigned spin_limit;   // polls after which it gives up
     int M, D, F, Fp;
     int nkb1, nfb, items1, per1, S1;   // phase 1: D/32 blocks, F/128 blocks, items, items per workgroup, slots
     int nkb2, nnb, items2, per2, S2;   // phase 2: F/32 blocks, D/128 blocks, ...
@@ -112,13 +124,20 @@ __device__ __forceinline__ f32x4 sum4(const float* red0, int stride, int i4) {
 // counting level on top of the groups cost another atomic round trip, about
 // 1 us per barrier).  Every word sits in its own 256-byte block.  All words only
 // ever increase (the kernels keep the number of completed barriers next to
-// them), so nothing needs resetting; the wait gives up after about two seconds.
-// Only thread 0 signals, after the whole workgroup's stores have been
-// acknowledged.
+// them), so nothing needs resetting; the wait gives up after `spin_limit` polls
+// (about two seconds by default) and then sets a word in host memory that the
+// library looks at when it is called next: the launch runs to its end with an
+// invalid output.  Only thread 0 signals, after the whole workgroup's stores have
+// been acknowledged.
 constexpr int BAR_GROUPS = 16;
 constexpr int BAR_STRIDE = 64;                 // words between barrier words (256 bytes)
 constexpr int BAR_WORDS = (2 * BAR_GROUPS + 2) * BAR_STRIDE;
-// word layout: group arrival g -> g, (16 unused), flag g -> 17 + g, timeout marker -> 33 (times BAR_STRIDE)
+// word layout: group arrival g -> g, (16 unused), flag g -> 17 + g (times BAR_STRIDE)
+
+// a bounded wait has given up: tell the host (system-scope store to mapped host memory)
+__device__ __forceinline__ void report_fault(unsigned* fault) {
+    __hip_atomic_store(fault, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
 
 // thread-level half: count this workgroup's arrival at barrier number k (>= 1)
 __device__ __forceinline__ void bar_signal(unsigned* bar, unsigned k) {
@@ -129,7 +148,7 @@ __device__ __forceinline__ void bar_signal(unsigned* bar, unsigned k) {
         __hip_atomic_store(bar + (BAR_GROUPS + 1 + g) * BAR_STRIDE, k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 // wavefront-level half (all 64 lanes call it): wait until every group has published barrier number k (bounded)
-__device__ __forceinline__ void bar_poll_wave(unsigned* bar, unsigned k) {
+__device__ __forceinline__ void bar_poll_wave(unsigned* bar, unsigned k, unsigned spin_limit, unsigned* fault) {
     const unsigned G = gridDim.x, ngroups = G < BAR_GROUPS ? G : BAR_GROUPS;
     const unsigned l = threadIdx.x & 63;
     unsigned spins = 0;
@@ -138,9 +157,8 @@ __device__ __forceinline__ void bar_poll_wave(unsigned* bar, unsigned k) {
         if (l < ngroups)
             v = __hip_atomic_load(bar + (BAR_GROUPS + 1 + l) * BAR_STRIDE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (__all((int)(v - k) >= 0)) break;
-        if (++spins > 8000000u) {
-            if (l == 0)
-                __hip_atomic_store(bar + (2 * BAR_GROUPS + 1) * BAR_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (++spins > spin_limit) {
+            if (l == 0) report_fault(fault);
             break;
         }
         __builtin_amdgcn_s_sleep(2);
@@ -339,7 +357,7 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
         prefetch2();
     } else {
         BB_STREAM_TRACE(3);
-        bar_poll_wave(p.bar, bar_base + 1u);
+        bar_poll_wave(p.bar, bar_base + 1u, p.spin_limit, p.fault);
         BB_STREAM_TRACE(4);
         // =====================  phase 1b: hidden block  =====================
         const int groups_per_row = p.Fp / 8;                   // tasks: (row, 8 consecutive hidden units)
@@ -417,7 +435,7 @@ __global__ __launch_bounds__(STREAM_THREADS) void ffn_stream_kernel(const Stream
                 sm.segbase[lane] = __hip_atomic_load(p.cnt + nb_first + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (lane == 0) bar_signal(p.bar, bar_base + 2u);
-        bar_poll_wave(p.bar, bar_base + 2u);
+        bar_poll_wave(p.bar, bar_base + 2u, p.spin_limit, p.fault);
         if (lane == 0 && b == 0)       // (every workgroup read the count before its first arrival)
             __hip_atomic_store(p.epoch, bar_base + 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }

@@ -90,7 +90,10 @@ struct StreamTArgs {
                        // of a global variable the compiler would know that it can be read ahead of time, and turn
                        // the loads back into branches around the real ones.)
     unsigned* bar;     // barrier words (see grid_arrive), shared with the row-major streaming kernel
-    unsigned* epoch;   // grid barriers completed by earlier launches (see ffn_stream_kernel)
+    unsigned* epoch;   // grid barriers completed by earlier launches: the barrier words only ever increase, the count
+                       // lives in device memory (workgroup 0 advances it), so the host keeps no state per launch
+    unsigned* fault;   // one word of host memory mapped into the device: set when the barrier's bounded wait gives up
+    unsigned spin_limit;   // polls after which it gives up
     int M, D, F, Fp;
     int upw, cpw;      // hidden units / output columns per workgroup
     int kblk;          // model channels whose bf16(x g) LDS holds at a time: a multiple of 512
@@ -381,7 +384,7 @@ __global__ __launch_bounds__(STREAMT_THREADS) void ffn_stream_t_kernel(const Str
         for (int u = 0; u < STREAMT_NPF2; ++u) issue_w(it[u]);
         BB_STREAM_TRACE(3);
         if (w == 0) {
-            bar_poll_wave(p.bar, bar_base + 1u);
+            bar_poll_wave(p.bar, bar_base + 1u, p.spin_limit, p.fault);
             if (lane == 0 && b == 0)
                 __hip_atomic_store(p.epoch, bar_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }

@@ -80,10 +80,11 @@ def transfer(state, block, report=None):
             continue
         is_vmem = re.match(r'(global_load|global_store|global_atomic|buffer_|flat_|scratch_)', s) is not None
         if in_asm:
-            m = re.match(r'global_load_dwordx4 v\[(\d+):(\d+)\]', s)
+            m = re.match(r'global_load_dword(?:x[234])?\s+(?:v\[(\d+):(\d+)\]|v(\d+))', s)
             if m:
                 st = {r: y + 1 for r, y in st.items()}
-                for r in range(int(m.group(1)), int(m.group(2)) + 1):
+                lo, hi = (int(m.group(1)), int(m.group(2))) if m.group(1) else (int(m.group(3)), int(m.group(3)))
+                for r in range(lo, hi + 1):
                     st[r] = 0
             continue
         hit = regs(s) & set(st)
