@@ -43,9 +43,11 @@ typedef enum bb_status {
     BB_ERR_WORKSPACE = -7, /* workspace missing, too small or misaligned          */
     BB_ERR_HIP = -8,       /* a HIP call failed; see bb_last_hip_error()          */
     BB_ERR_VARIANT = -9,   /* unknown variant, or one that cannot run this shape  */
-    BB_ERR_TIMEOUT = -10   /* a weight-streaming kernel of an EARLIER launch gave
+    BB_ERR_TIMEOUT = -10,  /* a weight-streaming kernel of an EARLIER launch gave
                               up waiting for another workgroup: that launch's
                               output is invalid (see bb_check_fault)              */
+    BB_ERR_INIT = -11      /* bb_rmsnorm_swiglu_ffn_static before bb_init (or any
+                              other call of this library) on the current device   */
 } bb_status;
 
 /* Which fused block program of Example 3 a call of bb_rmsnorm_swiglu_ffn runs.
@@ -348,6 +350,43 @@ int bb_set_workspace(void* dptr, size_t bytes);
 int bb_set_variant(int variant);
 int bb_get_variant(void);
 int bb_shutdown(void);
+
+/* ------------------------------------------------------------------------
+ * For callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.
+ *
+ * bb_init: sets the CURRENT device up (device properties, the 64-byte pinned
+ *   host word of bb_check_fault, the address of this device's copy of the
+ *   static scratch array).  The only call of this section that allocates
+ *   (that host word, once per device).  Every other entry point of the library
+ *   does the same on its first call on a device.  BB_OK, BB_ERR_ARCH, BB_ERR_HIP.
+ * bb_rmsnorm_swiglu_ffn_static: bb_rmsnorm_swiglu_ffn (same arguments, same
+ *   kernels, same variant choice, bit-identical output) with its scratch (the
+ *   hidden H, partial results of split contractions, the streaming kernels'
+ *   partial sums and synchronisation words) in a static device array of
+ *   BB_STATIC_SCRATCH_BYTES that each device holds from the loading of the
+ *   library to the end of the process.  Calls no hipMalloc, hipFree, event or
+ *   stream creation; what must start at zero is cleared by a kernel on
+ *   `stream` (no memset node), so the call can be captured into a HIP graph.
+ *   Neither reads nor changes the workspace of bb_set_workspace.
+ *   Errors: those of bb_rmsnorm_swiglu_ffn, and
+ *     BB_ERR_INIT       the current device has not been set up (bb_init);
+ *     BB_ERR_WORKSPACE  bb_workspace_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F)
+ *                       exceeds BB_STATIC_SCRATCH_BYTES: nothing is launched
+ *                       (M=64 D=512 F=1408 needs 2 MiB, M=16 D=4096 F=11008
+ *                       13 MiB, M=300 D=2048 F=5632 28 MiB; M=4096 D=4096
+ *                       F=11008 needs 118 MiB and is rejected);
+ *     BB_ERR_VARIANT    BB_VARIANT_UNFUSED is set (that program has its own,
+ *                       larger scratch).
+ *   All calls on one device share that device's array: calls that overlap in
+ *   time on one device (different streams, or threads) race; order them.
+ */
+#define BB_STATIC_SCRATCH_BYTES (32u << 20)
+int bb_init(void);
+int bb_rmsnorm_swiglu_ffn_static(const void* X, const void* g, const void* W1,
+                                 const void* W3, const void* W2, void* Y,
+                                 int64_t M, int64_t D, int64_t F, float eps,
+                                 void* stream);
 
 /* ------------------------------------------------------------------------
  * Diagnostics.

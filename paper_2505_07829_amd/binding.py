@@ -15,7 +15,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libbb.so")
 
 BB_OK = 0
+BB_ERR_WORKSPACE = -7
+BB_ERR_VARIANT = -9
 BB_ERR_TIMEOUT = -10
+BB_ERR_INIT = -11
+STATIC_SCRATCH_BYTES = 32 << 20
 VARIANT_AUTO, VARIANT_STREAM, VARIANT_SNAPSHOT1, VARIANT_UNFUSED, VARIANT_PRESCALE = 0, 1, 2, 3, 4
 OP_FFN, OP_LN, OP_FFN_UNFUSED, OP_LN_UNFUSED = 0, 1, 2, 3
 
@@ -30,6 +34,7 @@ EXPORTS = [
     "bb_calib_copy", "bb_calib_read", "bb_calib_mfma", "bb_calib_mfma_data",
     "bb_profile_enable", "bb_profile_count", "bb_profile_get", "bb_profile_calls", "bb_profile_count_of",
     "bb_profile_get_of", "bb_check_fault", "bb_debug_inject_fault", "bb_debug_set_spin_limit",
+    "bb_init", "bb_rmsnorm_swiglu_ffn_static",
 ]
 
 _lib = None
@@ -57,6 +62,7 @@ def load() -> ctypes.CDLL:
     vp, i64, f32, sz, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t, ctypes.c_int
     lib.bb_rmsnorm_swiglu_ffn.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
     lib.bb_rmsnorm_swiglu_ffn_unfused.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
+    lib.bb_rmsnorm_swiglu_ffn_static.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
     lib.bb_rmsnorm_swiglu_ffn_t.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
     lib.bb_layernorm_matmul_t.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
     lib.bb_layernorm_matmul.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
@@ -132,6 +138,24 @@ def bb_rmsnorm_swiglu_ffn(X, g, W1, W3, W2, eps: float, Y=None, unfused: bool = 
     fn = lib.bb_rmsnorm_swiglu_ffn_unfused if unfused else lib.bb_rmsnorm_swiglu_ffn
     _check(fn(_ptr(X), _ptr(g), _ptr(W1), _ptr(W3), _ptr(W2), _ptr(Y), M, D, F, float(eps), _stream()),
            "bb_rmsnorm_swiglu_ffn" + ("_unfused" if unfused else ""))
+    return Y
+
+
+def bb_init() -> None:
+    """Sets the current device up (the one call of the no-allocation path that may allocate)."""
+    _check(load().bb_init(), "bb_init")
+
+
+def bb_rmsnorm_swiglu_ffn_static(X, g, W1, W3, W2, eps: float, Y):
+    """bb_rmsnorm_swiglu_ffn with the library's static scratch array; allocates nothing, so Y is required."""
+    lib = load()
+    M, D = X.shape
+    F = W1.shape[1]
+    _require(X, (M, D), "X"); _require(g, (D,), "g")
+    _require(W1, (D, F), "W1"); _require(W3, (D, F), "W3"); _require(W2, (F, D), "W2")
+    _require(Y, (M, D), "Y")
+    _check(lib.bb_rmsnorm_swiglu_ffn_static(_ptr(X), _ptr(g), _ptr(W1), _ptr(W3), _ptr(W2), _ptr(Y), M, D, F,
+                                            float(eps), _stream()), "bb_rmsnorm_swiglu_ffn_static")
     return Y
 
 

@@ -66,7 +66,15 @@ struct DeviceInfo {
     // gives up (mapped into the device: the kernels store to fault_dev, the host reads *fault_host)
     volatile unsigned* fault_host = nullptr;
     unsigned* fault_dev = nullptr;
+    // this device's copy of the static scratch array (bb_rmsnorm_swiglu_ffn_static) and what is known of its contents
+    void* static_ptr = nullptr;
+    size_t static_clean = 0;
 } g_dev[64];
+
+// Scratch of bb_rmsnorm_swiglu_ffn_static, the entry point for callers that must not allocate.  Every
+// device the library is loaded on holds its own copy until the process ends.  In host code this name is a
+// stand-in, not an address: the device address comes from hipGetSymbolAddress (current_device_info).
+__device__ __align__(256) unsigned char scratch[BB_STATIC_SCRATCH_BYTES];
 unsigned g_spin_limit = 8000000u;      // polls after which a wait on another workgroup gives up (about two seconds)
 
 bool log_on() {
@@ -106,6 +114,13 @@ int current_device_info(const DeviceInfo** out) {
             BB_HIP(hipHostGetDevicePointer(&dp, h, 0));
             d.fault_host = reinterpret_cast<volatile unsigned*>(h);
             d.fault_dev = reinterpret_cast<unsigned*>(dp);
+        }
+        if (d.gfx950 && d.static_ptr == nullptr) {
+            void* sp = nullptr;
+            BB_HIP(hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)));
+            if (sp == nullptr || ((uintptr_t)sp & (kAlign - 1))) return BB_ERR_WORKSPACE;
+            d.static_ptr = sp;
+            d.static_clean = 0;        // (zero when the code object was loaded; cleared anyway before the first use)
         }
         d.known = true;
     }
@@ -487,6 +502,7 @@ int check_fault(const DeviceInfo* dev) {
     *dev->fault_host = 0u;
     g_ws.clean = 0;
     g_ws.attn_zone = 0;
+    g_dev[dev - g_dev].static_clean = 0;
     if (log_on()) std::fprintf(stderr, "[bb] a streaming kernel gave up a wait on another workgroup\n");
     return BB_ERR_TIMEOUT;
 }
@@ -621,6 +637,7 @@ const char* bb_status_string(int s) {
         case BB_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
         case BB_ERR_HIP: return "HIP call failed";
         case BB_ERR_VARIANT: return "bad variant";
+        case BB_ERR_INIT: return "bb_init has not been called on the current device";
         case BB_ERR_TIMEOUT: return "a streaming kernel of an earlier launch gave up waiting for another workgroup";
         default: return "unknown status";
     }
@@ -636,6 +653,57 @@ int bb_set_variant(int v) {
 int bb_get_variant(void) {
     std::lock_guard<std::mutex> lk(g_mu);
     return read_variant();
+}
+
+int bb_init(void) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    const DeviceInfo* dev = nullptr;
+    return current_device_info(&dev);
+}
+
+int bb_rmsnorm_swiglu_ffn_static(const void* X, const void* g, const void* W1, const void* W3, const void* W2,
+                                 void* Y, int64_t M, int64_t D, int64_t F, float eps, void* stream) {
+    if (int rc = validate_ffn(X, g, W1, W3, W2, Y, M, D, F, eps)) return rc;
+    if (M == 0) return BB_OK;
+    std::lock_guard<std::mutex> lk(g_mu);
+    int devno = 0;
+    BB_HIP(hipGetDevice(&devno));
+    if (devno < 0 || devno >= 64) return BB_ERR_ARCH;
+    DeviceInfo& d = g_dev[devno];
+    if (!d.known) return BB_ERR_INIT;                      // (setting a device up allocates its fault word)
+    if (!d.gfx950) return BB_ERR_ARCH;
+    int variant = read_variant();
+    if (variant == BB_VARIANT_UNFUSED) return BB_ERR_VARIANT;
+    if (variant == BB_VARIANT_STREAM && M > kStreamMaxM) return BB_ERR_VARIANT;
+    if (variant == BB_VARIANT_AUTO) variant = auto_variant(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F);
+    if (variant == BB_VARIANT_UNFUSED) variant = BB_VARIANT_SNAPSHOT1;
+    if (zone_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F) + scratch_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F) >
+        (size_t)BB_STATIC_SCRATCH_BYTES) {
+        if (log_on())
+            std::fprintf(stderr, "[bb] bb_rmsnorm_swiglu_ffn_static: M %lld D %lld F %lld needs %zu bytes of scratch, the static array has %zu\n",
+                         (long long)M, (long long)D, (long long)F,
+                         zone_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F) + scratch_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F),
+                         (size_t)BB_STATIC_SCRATCH_BYTES);
+        return BB_ERR_WORKSPACE;
+    }
+    // The operator runs as in bb_rmsnorm_swiglu_ffn with the static array in the place of the workspace: a
+    // caller-owned workspace is never grown or freed (ensure_workspace), the zone is cleared by a fill
+    // kernel, and per-kernel profiling (which creates events) is off for the duration of the call.
+    if (int rc = check_fault(&d)) return rc;               // (marks the zones of both workspaces for clearing)
+    const Workspace saved = g_ws;
+    const bool prof_was_on = g_prof.on;
+    g_ws = Workspace();
+    g_ws.ptr = d.static_ptr;
+    g_ws.bytes = (size_t)BB_STATIC_SCRATCH_BYTES;
+    g_ws.user = true;
+    g_ws.clean = d.static_clean;
+    g_ws.device = devno;
+    g_prof.on = false;
+    const int rc = ffn_locked(variant, X, g, W1, W3, W2, Y, M, D, F, eps, stream);
+    d.static_clean = g_ws.clean;
+    g_prof.on = prof_was_on;
+    g_ws = saved;
+    return rc;
 }
 
 int bb_check_fault(void) {
