@@ -94,6 +94,21 @@ typedef enum bb_status {
  *                       standard deviations (two passes over the row), the
  *                       product keeps the epilogue r (P - mu c) + b.  A
  *                       candidate of the measured selection below.
+ * BB_VARIANT_NEST      (FFN with D <= 512) the LAST snapshot of Example 3, the
+ *                       fully fused nest of the listing after Step 26, with one
+ *                       block of output columns (N = 1: the case of the
+ *                       Epilogue in which the extended maps replicate no work).
+ *                       ONE launch, a workgroup per block of 16 rows: statistics
+ *                       loop, then a serial loop over blocks of 128 hidden units
+ *                       (both products over the whole model dimension, inverse
+ *                       norm after the dots, Swish, gate, the block contracted
+ *                       with its rows of W2) with the 16 x D block of outputs in
+ *                       registers throughout.  The hidden never leaves the
+ *                       compute unit; no workspace is touched.  BB_ERR_VARIANT
+ *                       when D > 512 (the output block no longer fits).  A
+ *                       candidate of the measured selection below, never the
+ *                       rule of thumb's choice: one compute unit per 16 rows
+ *                       reads all three weight matrices alone.
  * BB_VARIANT_AUTO      the measured selection for exactly this shape if
  *                       bb_*_tune has recorded one, else STREAM for M <= 16,
  *                       SNAPSHOT1 up to 255 rows and PRESCALE from 256 rows on
@@ -106,7 +121,8 @@ typedef enum bb_variant {
     BB_VARIANT_STREAM = 1,
     BB_VARIANT_SNAPSHOT1 = 2,
     BB_VARIANT_UNFUSED = 3,
-    BB_VARIANT_PRESCALE = 4
+    BB_VARIANT_PRESCALE = 4,
+    BB_VARIANT_NEST = 5
 } bb_variant;
 
 typedef enum bb_op {
@@ -308,7 +324,7 @@ size_t bb_attention_workspace_bytes(int64_t B, int64_t M, int64_t N, int64_t d,
  * bb_layernorm_matmul with that shape run it.  Y holds the result of the last
  * candidate run (all candidates compute the same operator).
  *   chosen (host, may be NULL): the recorded variant.
- *   ms (host, 5 floats, may be NULL): ms[v] = mean milliseconds of variant v,
+ *   ms (host, 6 floats, may be NULL): ms[v] = mean milliseconds of variant v,
  *     -1 where v is not a candidate; ms[0] = the fastest.
  * A candidate that does not fit a caller-provided workspace is skipped.
  * bb_set_workspace and bb_tune_clear empty the table.  bb_tuned_variant returns

@@ -20,7 +20,7 @@ BB_ERR_VARIANT = -9
 BB_ERR_TIMEOUT = -10
 BB_ERR_INIT = -11
 STATIC_SCRATCH_BYTES = 32 << 20
-VARIANT_AUTO, VARIANT_STREAM, VARIANT_SNAPSHOT1, VARIANT_UNFUSED, VARIANT_PRESCALE = 0, 1, 2, 3, 4
+VARIANT_AUTO, VARIANT_STREAM, VARIANT_SNAPSHOT1, VARIANT_UNFUSED, VARIANT_PRESCALE, VARIANT_NEST = 0, 1, 2, 3, 4, 5
 OP_FFN, OP_LN, OP_FFN_UNFUSED, OP_LN_UNFUSED = 0, 1, 2, 3
 
 EXPORTS = [
@@ -206,11 +206,11 @@ def bb_rmsnorm_swiglu_ffn_tune(X, g, W1, W3, W2, eps: float, reps: int = 5, Y=No
     if Y is None:
         Y = torch.empty((M, D), dtype=torch.bfloat16, device=X.device)
     _require(Y, (M, D), "Y")
-    chosen, ms = ctypes.c_int(0), (ctypes.c_float * 5)()
+    chosen, ms = ctypes.c_int(0), (ctypes.c_float * 6)()
     _check(lib.bb_rmsnorm_swiglu_ffn_tune(_ptr(X), _ptr(g), _ptr(W1), _ptr(W3), _ptr(W2), _ptr(Y), M, D, F,
                                           float(eps), _stream(), int(reps), ctypes.byref(chosen), ms),
            "bb_rmsnorm_swiglu_ffn_tune")
-    return chosen.value, {v: float(ms[v]) for v in (1, 2, 3, 4) if ms[v] >= 0}
+    return chosen.value, {v: float(ms[v]) for v in (1, 2, 3, 4, 5) if ms[v] >= 0}
 
 
 def bb_layernorm_matmul_tune(X, gamma, beta, W, eps: float, reps: int = 5, Y=None):
@@ -225,11 +225,11 @@ def bb_layernorm_matmul_tune(X, gamma, beta, W, eps: float, reps: int = 5, Y=Non
     if Y is None:
         Y = torch.empty((M, N), dtype=torch.bfloat16, device=X.device)
     _require(Y, (M, N), "Y")
-    chosen, ms = ctypes.c_int(0), (ctypes.c_float * 5)()
+    chosen, ms = ctypes.c_int(0), (ctypes.c_float * 6)()
     _check(lib.bb_layernorm_matmul_tune(_ptr(X), _ptr(gamma), _ptr(beta), _ptr(W), _ptr(Y), M, D, N, float(eps),
                                         _stream(), int(reps), ctypes.byref(chosen), ms),
            "bb_layernorm_matmul_tune")
-    return chosen.value, {v: float(ms[v]) for v in (1, 2, 3, 4) if ms[v] >= 0}
+    return chosen.value, {v: float(ms[v]) for v in (1, 2, 3, 4, 5) if ms[v] >= 0}
 
 
 def bb_tuned_variant(op: int, M: int, D: int, F_or_N: int) -> int:

@@ -18,6 +18,7 @@
 #include "bb_misc.h"
 #include "bb_stream.h"
 #include "bb_stream_t.h"
+#include "bb_nest.h"
 
 namespace {
 
@@ -136,6 +137,7 @@ int read_variant() {
             else if (!std::strcmp(e, "snapshot1")) g_variant = BB_VARIANT_SNAPSHOT1;
             else if (!std::strcmp(e, "unfused")) g_variant = BB_VARIANT_UNFUSED;
             else if (!std::strcmp(e, "prescale")) g_variant = BB_VARIANT_PRESCALE;
+            else if (!std::strcmp(e, "nest")) g_variant = BB_VARIANT_NEST;
         }
     }
     return g_variant;
@@ -163,9 +165,12 @@ int auto_variant(int op, int64_t M, int64_t D, int64_t FN) {
     if (it != g_tuned.end()) return it->second;
     // (measured on D = 4096, F = 11008: from 256 rows on the separate statistics pass beats the
     // statistics inside the product loop by 7-9 %; below, the split contraction needs the fused form)
-    if (op == BB_OP_RMSNORM_SWIGLU_FFN)
-        return (M <= kStreamMaxM && stream_fits(D)) ? BB_VARIANT_STREAM
-                                                    : (M >= kPrescaleMinM ? BB_VARIANT_PRESCALE : BB_VARIANT_SNAPSHOT1);
+    if (op == BB_OP_RMSNORM_SWIGLU_FFN) {
+        if (M <= kStreamMaxM && stream_fits(D)) return BB_VARIANT_STREAM;
+        // (the fully fused nest, BB_VARIANT_NEST, is no rule-of-thumb choice: a block of 16 rows is served by one
+        // compute unit, which reads all three weight matrices alone; measured 28 us against 24 us on 64 x 256 x 704)
+        return M >= kPrescaleMinM ? BB_VARIANT_PRESCALE : BB_VARIANT_SNAPSHOT1;
+    }
     return M >= kPrescaleMinM ? BB_VARIANT_PRESCALE : BB_VARIANT_SNAPSHOT1;
 }
 
@@ -644,7 +649,7 @@ const char* bb_status_string(int s) {
 }
 
 int bb_set_variant(int v) {
-    if (v < BB_VARIANT_AUTO || v > BB_VARIANT_PRESCALE) return BB_ERR_VARIANT;
+    if (v < BB_VARIANT_AUTO || v > BB_VARIANT_NEST) return BB_ERR_VARIANT;
     std::lock_guard<std::mutex> lk(g_mu);
     g_variant = v;
     return BB_OK;
@@ -785,9 +790,22 @@ int ffn_locked(int variant, const void* X, const void* g, const void* W1, const 
         return ffn_unfused_locked(X, g, W1, W3, W2, Y, M, D, F, eps, stream);
     if (variant == BB_VARIANT_UNFUSED) variant = BB_VARIANT_SNAPSHOT1;
     if (variant == BB_VARIANT_PRESCALE && M <= kStreamMaxM) return BB_ERR_VARIANT;   // (no room is planned for so few rows)
+    if (variant == BB_VARIANT_NEST && D > NEST_MAXD) return BB_ERR_VARIANT;          // (the block of outputs no longer fits the registers)
     const DeviceInfo* dev = nullptr;
     if (int rc = current_device_info(&dev)) return rc;
     if (int rc = check_fault(dev)) return rc;
+    if (variant == BB_VARIANT_NEST) {
+        // last snapshot (one block of output columns): one launch, no workspace
+        NestArgs a;
+        a.X = (const u16*)X; a.g = (const u16*)g; a.W1 = (const u16*)W1; a.W3 = (const u16*)W3; a.W2 = (const u16*)W2;
+        a.Y = (u16*)Y; a.R = (const u16*)R; a.M = (int)M; a.D = (int)D; a.F = (int)F; a.eps = eps;
+        hipStream_t nst = as_stream(stream);
+        prof_begin(nst);
+        nest_launch((int)((D + 127) / 128), (int)((M + NEST_ROWS - 1) / NEST_ROWS), nst, a);
+        BB_HIP(hipGetLastError());
+        prof_mark("ffn_nest", nst);
+        return BB_OK;
+    }
     const size_t zone = zone_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F);
     if (int rc = ensure_workspace(zone + scratch_bytes(BB_OP_RMSNORM_SWIGLU_FFN, M, D, F))) return rc;
     hipStream_t st = as_stream(stream);
@@ -910,7 +928,8 @@ int bb_layernorm_matmul(const void* X, const void* gamma, const void* beta, cons
     if (M == 0) return BB_OK;
     std::lock_guard<std::mutex> lk(g_mu);
     int variant = read_variant();
-    if (variant == BB_VARIANT_AUTO || variant == BB_VARIANT_STREAM) variant = auto_variant(BB_OP_LAYERNORM_MATMUL, M, D, N);
+    if (variant == BB_VARIANT_AUTO || variant == BB_VARIANT_STREAM || variant == BB_VARIANT_NEST)
+        variant = auto_variant(BB_OP_LAYERNORM_MATMUL, M, D, N);
     return ln_locked(variant, X, gamma, beta, W, Y, M, D, N, eps, stream);
 }
 
@@ -1194,9 +1213,10 @@ int tune_locked(int op, int64_t M, int64_t D, int64_t FN, int reps, hipStream_t 
     int best = 0;
     float best_ms = 0.f;
     int rc = BB_OK;
-    for (int v = BB_VARIANT_STREAM; v <= BB_VARIANT_PRESCALE && rc == BB_OK; ++v) {
+    for (int v = BB_VARIANT_STREAM; v <= BB_VARIANT_NEST && rc == BB_OK; ++v) {
         if (ms_out) ms_out[v] = -1.f;
-        if (op == BB_OP_LAYERNORM_MATMUL && v == BB_VARIANT_STREAM) continue;
+        if (op == BB_OP_LAYERNORM_MATMUL && (v == BB_VARIANT_STREAM || v == BB_VARIANT_NEST)) continue;
+        if (v == BB_VARIANT_NEST && D > NEST_MAXD) continue;
         if (v == BB_VARIANT_STREAM && M > kStreamMaxM) continue;
         if (op == BB_OP_RMSNORM_SWIGLU_FFN && v == BB_VARIANT_PRESCALE && M <= kStreamMaxM) continue;
         float ms = 0.f;

@@ -12,6 +12,7 @@ struct GemmArgs;
 struct StreamArgs;
 struct StreamTArgs;
 struct AttnArgs;
+struct NestArgs;
 
 // gemm_kernel<MODE, bm, full, odd, split, bt> on `grid` workgroups (defined per MODE and per weight
 // layout in bb_gemm_inst_*.hip); split launches exist for MODE_PLAIN and MODE_GATEUP only
@@ -28,6 +29,9 @@ int stream_resident(hipError_t* err);
 void stream_launch(int G, hipStream_t st, const StreamArgs& a);
 int stream_t_resident(int lds_bytes, hipError_t* err);
 void stream_t_launch(int G, int lds_bytes, hipStream_t st, const StreamTArgs& a);
+
+// fully fused nest for small model dimensions: ffn_nest_kernel<nd>, nd = blocks of 128 model channels (2 or 4)
+void nest_launch(int nd, int grid, hipStream_t st, const NestArgs& a);
 
 // attention: tiled kernel (ksplit > 1: split keys + combine kernel), one-query streaming kernel
 // (defined per pair of head dimensions in bb_attn_inst_*.hip)

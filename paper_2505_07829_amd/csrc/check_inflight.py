@@ -7,7 +7,7 @@ register it reuses too early is overwritten when the load returns).
     check_inflight.py <device assembly (.s)> <kernel symbol> [...]
 
 Forward data-flow analysis over the kernel's control-flow graph.  State: for every vector
-register that an asm load has been issued to, the least number of vector-memory instructions
+register (vector or accumulation) that an asm load has been issued to, the least number of vector-memory instructions
 issued after that load on any path ("younger").  Loads of a wavefront return in order, so
 "s_waitcnt vmcnt(N)" completes every load with at least N younger ones; states of joining paths
 are merged register by register with the minimum.  Any instruction outside the asm blocks that
@@ -19,12 +19,16 @@ import sys
 BIG = 1 << 20
 
 
+AGPR = 1000     # accumulation register aN is tracked as register number AGPR + N
+
+
 def regs(text):
     out = set()
-    for m in re.finditer(r'\bv\[(\d+):(\d+)\]', text):
-        out.update(range(int(m.group(1)), int(m.group(2)) + 1))
-    for m in re.finditer(r'\bv(\d+)\b', text):
-        out.add(int(m.group(1)))
+    for m in re.finditer(r'\b([va])\[(\d+):(\d+)\]', text):
+        base = AGPR if m.group(1) == 'a' else 0
+        out.update(range(base + int(m.group(2)), base + int(m.group(3)) + 1))
+    for m in re.finditer(r'\b([va])(\d+)\b', text):
+        out.add((AGPR if m.group(1) == 'a' else 0) + int(m.group(2)))
     return out
 
 
@@ -80,11 +84,12 @@ def transfer(state, block, report=None):
             continue
         is_vmem = re.match(r'(global_load|global_store|global_atomic|buffer_|flat_|scratch_)', s) is not None
         if in_asm:
-            m = re.match(r'global_load_dword(?:x[234])?\s+(?:v\[(\d+):(\d+)\]|v(\d+))', s)
+            m = re.match(r'global_load_dword(?:x[234])?\s+([va])(?:\[(\d+):(\d+)\]|(\d+))', s)
             if m:
                 st = {r: y + 1 for r, y in st.items()}
-                lo, hi = (int(m.group(1)), int(m.group(2))) if m.group(1) else (int(m.group(3)), int(m.group(3)))
-                for r in range(lo, hi + 1):
+                base = AGPR if m.group(1) == 'a' else 0
+                lo, hi = (int(m.group(2)), int(m.group(3))) if m.group(2) else (int(m.group(4)), int(m.group(4)))
+                for r in range(base + lo, base + hi + 1):
                     st[r] = 0
             continue
         hit = regs(s) & set(st)
@@ -127,7 +132,8 @@ def check(path, kernel):
             continue
         seen.add(lineno)
         if len(seen) <= 12:
-            print("  line %d: %s   <- registers %s may be in flight" % (lineno, s[:72], hit[:4]))
+            names = ["a%d" % (r - AGPR) if r >= AGPR else "v%d" % r for r in hit[:4]]
+            print("  line %d: %s   <- registers %s may be in flight" % (lineno, s[:72], names))
     print("%s: %d suspicious instruction(s)" % (kernel, len(seen)))
     return len(seen)
 

@@ -153,7 +153,9 @@ def test_variant_and_workspace_queries(lib):
     assert bb.bb_get_variant() in (0, 1, 2)
     old = bb.bb_get_variant()
     with pytest.raises(bb.BBError):
-        bb.bb_set_variant(5)
+        bb.bb_set_variant(6)
+    bb.bb_set_variant(bb.VARIANT_NEST)
+    assert bb.bb_get_variant() == bb.VARIANT_NEST
     bb.bb_set_variant(bb.VARIANT_UNFUSED)
     assert bb.bb_get_variant() == bb.VARIANT_UNFUSED
     bb.bb_set_variant(bb.VARIANT_PRESCALE)

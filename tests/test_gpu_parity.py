@@ -62,7 +62,7 @@ def _lib():
 
 
 # ---------------------------------------------------------------- small shapes
-@pytest.mark.parametrize("variant", [bb.VARIANT_SNAPSHOT1, bb.VARIANT_AUTO])
+@pytest.mark.parametrize("variant", [bb.VARIANT_SNAPSHOT1, bb.VARIANT_NEST, bb.VARIANT_AUTO])
 def test_c1_full(variant):
     c = bb_inputs.CONFIGS["c1"]
     err = ffn_case(bb_inputs.make_config("c1"), c.eps, variant=variant)
@@ -81,6 +81,40 @@ def test_ragged_shapes_snapshot1(M, D, F):
 def test_ragged_shapes_stream(M, D, F):
     err = ffn_case(bb_inputs.make_ffn(M, D, F, seed=M + F), 1e-6, variant=bb.VARIANT_STREAM)
     assert err <= TOL
+
+
+# the fully fused nest (last snapshot of Example 3 with one block of output columns): one launch, D <= 512
+@pytest.mark.parametrize("M,D,F", [(1, 64, 64), (16, 256, 704), (17, 72, 136), (64, 256, 704), (130, 264, 712),
+                                   (300, 512, 1032), (33, 392, 200), (250, 512, 2816)])
+def test_ragged_shapes_nest(M, D, F):
+    err = ffn_case(bb_inputs.make_ffn(M, D, F, seed=M + D + 1), 1e-6, variant=bb.VARIANT_NEST)
+    assert err <= TOL
+
+
+def test_nest_is_one_launch_on_c1():
+    c = bb_inputs.CONFIGS["c1"]
+    cpu = bb_inputs.make_config("c1")
+    bb.bb_set_variant(bb.VARIANT_NEST)
+    bb.bb_profile_enable(True)
+    try:
+        Y = bb.bb_rmsnorm_swiglu_ffn(*dev(cpu), c.eps)
+        names = [k for k, _ in bb.bb_profile_last()]
+    finally:
+        bb.bb_profile_enable(False)
+        bb.bb_set_variant(bb.VARIANT_AUTO)
+    assert names == ["ffn_nest"]
+    assert row_rel_err(Y, orc.rmsnorm_swiglu_ffn(*cpu, c.eps)) <= TOL
+
+
+def test_nest_refuses_a_model_dimension_whose_output_block_does_not_fit():
+    cpu = bb_inputs.make_ffn(32, 520, 256, seed=2)
+    bb.bb_set_variant(bb.VARIANT_NEST)
+    try:
+        with pytest.raises(bb.BBError) as e:
+            bb.bb_rmsnorm_swiglu_ffn(*dev(cpu), 1e-6)
+        assert e.value.status == bb.BB_ERR_VARIANT
+    finally:
+        bb.bb_set_variant(bb.VARIANT_AUTO)
 
 
 def test_stream_repeated_calls_keep_scratch_clean():
@@ -119,7 +153,7 @@ def test_variant_switching_shares_workspace():
 
 
 @pytest.mark.parametrize("which", [1, 2, 3, 4])
-@pytest.mark.parametrize("variant", [bb.VARIANT_STREAM, bb.VARIANT_SNAPSHOT1])
+@pytest.mark.parametrize("variant", [bb.VARIANT_STREAM, bb.VARIANT_SNAPSHOT1, bb.VARIANT_NEST])
 def test_zero_operand_gives_exact_zero(which, variant):
     cpu = list(bb_inputs.make_ffn(16, 128, 256, seed=6))
     cpu[which] = torch.zeros_like(cpu[which])           # g, W1, W3 or W2
@@ -137,7 +171,7 @@ def test_eps_matters_when_rows_are_tiny():
     # drops eps or puts it outside the root would miss by tens of percent
     cpu = list(bb_inputs.make_ffn(16, 256, 512, seed=8))
     cpu[0] = (cpu[0].float() * 1e-3).to(torch.bfloat16)
-    for v in (bb.VARIANT_STREAM, bb.VARIANT_SNAPSHOT1):
+    for v in (bb.VARIANT_STREAM, bb.VARIANT_SNAPSHOT1, bb.VARIANT_NEST):
         assert ffn_case(cpu, 1e-6, variant=v) <= TOL
 
 
@@ -281,7 +315,8 @@ def test_tune_records_fastest_candidate_and_auto_follows():
     M, D, F = 96, 512, 1408
     assert bb.bb_tuned_variant(bb.OP_FFN, M, D, F) == bb.VARIANT_AUTO
     chosen, ms = bb.bb_rmsnorm_swiglu_ffn_tune(*d, 1e-6, reps=3)
-    assert set(ms) == {bb.VARIANT_SNAPSHOT1, bb.VARIANT_UNFUSED, bb.VARIANT_PRESCALE}   # STREAM is no candidate above 16 rows
+    # (STREAM is no candidate above 16 rows; the fully fused nest is one up to a model dimension of 512)
+    assert set(ms) == {bb.VARIANT_SNAPSHOT1, bb.VARIANT_UNFUSED, bb.VARIANT_PRESCALE, bb.VARIANT_NEST}
     assert chosen == min(ms, key=ms.get) and all(v > 0 for v in ms.values())
     assert bb.bb_tuned_variant(bb.OP_FFN, M, D, F) == chosen
     assert bb.bb_tuned_variant(bb.OP_FFN, M + 1, D, F) == bb.VARIANT_AUTO  # exact shapes only
@@ -292,6 +327,7 @@ def test_tune_records_fastest_candidate_and_auto_follows():
     bb.bb_profile_enable(False)
     assert ("rmsnorm_rows" in names) == (chosen == bb.VARIANT_UNFUSED)
     assert ("rms_gain_rows" in names) == (chosen == bb.VARIANT_PRESCALE)
+    assert ("ffn_nest" in names) == (chosen == bb.VARIANT_NEST)
     ref = orc.rmsnorm_swiglu_ffn(*cpu, 1e-6)
     assert row_rel_err(Y, ref) <= TOL
     bb.bb_tune_clear()
@@ -302,7 +338,7 @@ def test_tune_decode_shape_has_three_candidates():
     bb.bb_tune_clear()
     cpu = bb_inputs.make_ffn(8, 512, 1408, seed=5)
     chosen, ms = bb.bb_rmsnorm_swiglu_ffn_tune(*dev(cpu), 1e-6, reps=3)
-    assert set(ms) == {bb.VARIANT_STREAM, bb.VARIANT_SNAPSHOT1, bb.VARIANT_UNFUSED}
+    assert set(ms) == {bb.VARIANT_STREAM, bb.VARIANT_SNAPSHOT1, bb.VARIANT_UNFUSED, bb.VARIANT_NEST}
     Y = bb.bb_rmsnorm_swiglu_ffn(*dev(cpu), 1e-6)
     assert row_rel_err(Y, orc.rmsnorm_swiglu_ffn(*cpu, 1e-6)) <= TOL
     bb.bb_tune_clear()
@@ -347,6 +383,16 @@ def residual_case(M, D, F, seed, transposed=False, in_place=None):
                                    (256, 512, 1024), (512, 1024, 2816), (300, 520, 1032)])
 def test_residual_epilogue(M, D, F):
     assert residual_case(M, D, F, seed=M + F) <= TOL
+
+
+@pytest.mark.parametrize("M,D,F", [(17, 72, 136), (96, 512, 1408), (130, 264, 712)])
+def test_residual_epilogue_fully_fused_nest(M, D, F):
+    bb.bb_set_variant(bb.VARIANT_NEST)
+    try:
+        assert residual_case(M, D, F, seed=M + F) <= TOL
+        assert residual_case(M, D, F, seed=5, in_place="x") <= TOL
+    finally:
+        bb.bb_set_variant(bb.VARIANT_AUTO)
 
 
 @pytest.mark.parametrize("M,D,F", [(130, 264, 712), (512, 1024, 2816), (16, 256, 704)])
