@@ -194,18 +194,23 @@ __device__ __forceinline__ void quad_transpose_f32(float (&y)[4], bool upper, bo
 // of the paper's block programs (W^T) and of linear-layer checkpoints.  Its tile
 // then lies in LDS exactly like the A tile (rows of 8 contraction chunks, same
 // swizzle, same load-to-LDS role) and its fragments are plain 128-bit reads.
-template <int MODE, int BM, bool FULL, bool ODD, bool SPLIT = false, bool BT = false>
-__global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
+// NW: wavefronts per workgroup.  4 (one per SIMD, a 128 x 128 wavefront tile in 256 accumulator registers), or,
+// for the modes without prologue on 256-row tiles, 8 (two per SIMD, 128 x 64 each in 128 accumulator registers:
+// while one wavefront's LDS reads and load-to-LDS instructions issue, the other's matrix instructions do).
+template <int MODE, int BM, bool FULL, bool ODD, bool SPLIT = false, bool BT = false, int NW = 4>
+__global__ __launch_bounds__(64 * NW) void gemm_kernel(const GemmArgs p) {
+    static_assert(NW == 4 || (NW == 8 && BM == 256 && MODE != MODE_GATEUP && MODE != MODE_LN), "8 wavefronts: 256-row tiles, no prologue");
     // (2 x 2 wherever the A fragments need no prologue: least LDS read traffic)
     constexpr int WM = (MODE == MODE_PLAIN || MODE == MODE_GATEUP_PRE || MODE == MODE_LN_PRE) ? 2 : 4;   // wavefronts along the rows
-    constexpr int WN = 4 / WM;                          // and along the columns
+    constexpr int WN = NW / WM;                         // and along the columns
     constexpr int WR = BM / WM, WC = 256 / WN;          // wavefront tile
     constexpr int MT = WR / 32, NT = WC / 32;           // 32x32 subtiles per wavefront
     constexpr bool DUAL = MODE == MODE_GATEUP || MODE == MODE_GATEUP_PRE;   // two products per tile, SwiGLU epilogue
     constexpr bool COOK = MODE == MODE_GATEUP || MODE == MODE_LN;           // norm prologue on the A fragments
     constexpr bool LNE = MODE == MODE_LN || MODE == MODE_LN_PRE;            // epilogue r (P - mu c) + b
     constexpr int NCOL = DUAL ? 128 : 256;                   // output columns per tile
-    constexpr int ADMA = BM / 32;   // A load-to-LDS instructions per wavefront and step
+    constexpr int ADMA = BM / (8 * NW);   // A load-to-LDS instructions per wavefront and step
+    constexpr int BDMA = 32 / NW;         // B load-to-LDS instructions per wavefront and step
     // (the B arrays come first: the many transposing reads of a step then reach
     // their addresses with the 16-bit displacement of the LDS instructions)
     __shared__ u32x4 sB0[64 * 32], sB1[64 * 32];     // [contraction row][32 chunks], swizzled
@@ -288,8 +293,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     const bool colB_ok = FULL || colB < p.N;
     const u32 laneB = (u32)(rowBl * p.ldb + (colB_ok ? 8 * chunkB : 0));
     // BT: like the A tile.  256 tile rows (= output columns; GATEUP: 128 rows of
-    // W1^T, then the same 128 of W3^T), 8 instructions per wavefront, each 8 rows.
-    const int rowT = 64 * w + (lane >> 3);                       // + 8 j for instruction j
+    // W1^T, then the same 128 of W3^T), BDMA instructions per wavefront, each 8 rows.
+    const int rowT = 8 * BDMA * w + (lane >> 3);                 // + 8 j for instruction j
     int kcT[2];
     u32 laneT[2];
 #pragma unroll
@@ -322,25 +327,26 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
         }
     }
 
-    // Quarter `part` (0..3) of the load-to-LDS instructions of B tile kt (8 per
+    // Quarter `part` (0..3) of the load-to-LDS instructions of B tile kt (BDMA per
     // wavefront and tile) into LDS array dB
     auto dma_b = [&](int kt, u32x4* dB, int part) {
         const int k0 = (kt0 + kt) * GEMM_BK;
 #pragma unroll
-        for (int qq = 0; qq < 2; ++qq) {
-            const int q = 2 * part + qq;
+        for (int qq = 0; qq < BDMA / 4; ++qq) {
+            const int q = (BDMA / 4) * part + qq;
             if (BT) {
-                const int r0 = 64 * w + 8 * q;                       // first tile row of the instruction
-                const bool second = HALF && w >= 2;
+                const int r0 = 8 * BDMA * w + 8 * q;                 // first tile row of the instruction
+                const bool second = HALF && r0 >= 128;
                 const int nrow = HALF ? n0 + (r0 & 127) : n0 + r0;   // first matrix row (output column)
                 copy16(second ? p.B1 : p.B0, second ? rsB1 : rsB0, (size_t)nrow * p.ldb + k0, laneT[q & 1],
-                       k0 + 8 * kcT[q & 1] < p.K && nrow + (lane >> 3) < p.N, dB + (8 * w + q) * 64);
+                       k0 + 8 * kcT[q & 1] < p.K && nrow + (lane >> 3) < p.N, dB + (BDMA * w + q) * 64);
             } else if (HALF) {
-                const int rg = 4 * (q & 3) + w;                      // four-row group of the half tile
-                copy16((q >> 2) ? p.B1 : p.B0, (q >> 2) ? rsB1 : rsB0, (size_t)(k0 + 4 * rg) * p.ldb + n0, laneB,
-                       colB_ok && k0 + 4 * rg + rowBl < p.K, dB + (q >> 2) * 1024 + rg * 64);
+                const int idx = NW * q + w;                          // four-row group of the two half tiles
+                const int hf = idx >> 4, rg = idx & 15;
+                copy16(hf ? p.B1 : p.B0, hf ? rsB1 : rsB0, (size_t)(k0 + 4 * rg) * p.ldb + n0, laneB,
+                       colB_ok && k0 + 4 * rg + rowBl < p.K, dB + hf * 1024 + rg * 64);
             } else {
-                const int rp = w + 4 * q;                            // row pair of the tile
+                const int rp = w + NW * q;                           // row pair of the tile
                 copy16(p.B0, rsB0, (size_t)(k0 + 2 * rp) * p.ldb + n0, laneB, colB_ok && k0 + 2 * rp + rowBl < p.K,
                        dB + rp * 64);
             }
@@ -609,12 +615,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs p) {
     // ---- row statistics: add the two lanes that share a row (lane, lane ^ 32)
     if (MODE == MODE_GATEUP_PRE) {
         // the inverse norms were computed by the row kernel that applied the gain
-        for (int i = threadIdx.x; i < BM; i += GEMM_THREADS) stat0[i] = (m0 + i < p.M) ? p.colc[m0 + i] : 0.f;
+        for (int i = threadIdx.x; i < BM; i += 64 * NW) stat0[i] = (m0 + i < p.M) ? p.colc[m0 + i] : 0.f;
         __syncthreads();
     }
     if (MODE == MODE_LN_PRE) {
         // row statistics from the row kernel: rowstat[2 m] = inverse standard deviation, [2 m + 1] = mean
-        for (int i = threadIdx.x; i < BM; i += GEMM_THREADS) {
+        for (int i = threadIdx.x; i < BM; i += 64 * NW) {
             const bool ok = m0 + i < p.M;
             stat0[i] = ok ? p.rowstat[2 * (size_t)(m0 + i)] : 0.f;
             stat1[i] = ok ? p.rowstat[2 * (size_t)(m0 + i) + 1] : 0.f;
