@@ -65,14 +65,15 @@ typedef enum bb_status {
  *                      workgroups per tile, whose fp32 partial results a small
  *                      kernel adds in fixed order before the epilogue (Rule 3's
  *                      parallel reduction without atomics): up to four launches.
- * BB_VARIANT_STREAM    bandwidth-bound form for M <= 16 rows.  One persistent
+ * BB_VARIANT_STREAM    bandwidth-bound form for M <= 32 rows (transposed-weight
+ *                      entry points: M <= 16).  One persistent
  *                      kernel (one workgroup per compute unit, all resident)
  *                      streams W1, W3 and then W2 exactly once; both
  *                      reductions (over the model dimension and over the
  *                      hidden dimension) run in parallel over all workgroups
  *                      (Rule 3; Example 3's epilogue proposes it for the
  *                      K-map) through per-workgroup partial-sum slots that a
- *                      short phase adds up.  The hidden block (16 x F) passes
+ *                      short phase adds up.  The hidden block (M x F) passes
  *                      through a cache-resident scratch between the phases.
  *                      The kernel synchronises its workgroups through counters
  *                      in the workspace that only the kernels touch: a launch
@@ -110,7 +111,7 @@ typedef enum bb_status {
  *                       rule of thumb's choice: one compute unit per 16 rows
  *                       reads all three weight matrices alone.
  * BB_VARIANT_AUTO      the measured selection for exactly this shape if
- *                       bb_*_tune has recorded one, else STREAM for M <= 16,
+ *                       bb_*_tune has recorded one, else STREAM for M <= 32,
  *                       SNAPSHOT1 up to 255 rows and PRESCALE from 256 rows on
  *                       (the table measured on an MI355X for D = 4096,
  *                       F = 11008); LN -> matmul: SNAPSHOT1 up to 255 rows,
@@ -316,7 +317,7 @@ size_t bb_attention_workspace_bytes(int64_t B, int64_t M, int64_t N, int64_t d,
  * keeps the one that runs fastest; Example 3's epilogue lists the forms).
  *
  * bb_*_tune run every candidate program of the operator on the caller's
- * operands (same arguments as the operator): STREAM (FFN, M <= 16 only),
+ * operands (same arguments as the operator): STREAM (FFN, M <= 32 only),
  * SNAPSHOT1, UNFUSED, PRESCALE (for the FFN M > 16 only); each once untimed and then `reps` (1..1000) times between
  * two events on `stream`, which the call waits for.  The fastest is recorded
  * for exactly this (operator, M, D, F or N) in a process-wide table that

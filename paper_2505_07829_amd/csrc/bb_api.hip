@@ -24,7 +24,9 @@ namespace {
 
 using namespace bb;
 
-constexpr int64_t kStreamMaxM = 16;   // rows the weight-streaming kernel handles
+constexpr int64_t kStreamMaxM = 16 * STREAM_MAXMT;   // rows the weight-streaming kernel handles (row-major weights)
+constexpr int64_t kStreamTMaxM = 16;  // rows the weight-streaming kernel for transposed weights handles
+constexpr int64_t kPrescaleFloorM = 16; // up to this many rows no room is planned for BB_VARIANT_PRESCALE's gain-scaled copy of X
 constexpr int64_t kPrescaleMinM = 256; // rows from which AUTO runs the statistics loop as a kernel of its own
 constexpr size_t kAlign = 256;
 
@@ -153,11 +155,6 @@ struct TuneKey {
 };
 std::map<TuneKey, int> g_tuned;
 
-// The streaming kernel keeps per-workgroup state for at most 64 blocks of 128 output columns
-// (a workgroup's share of the second phase spans at most D / 128 / workgroups + 2 of them; the rule of
-// thumb assumes no fewer than 64 workgroups, run_stream checks the real number).
-bool stream_fits(int64_t D) { return (D + 127) / 128 / 64 + 2 <= 64; }
-
 // AUTO: a measured selection for exactly this shape if there is one, else the rule of thumb
 // (weight-streaming kernel up to kStreamMaxM rows, tiled kernels beyond; LN always fused)
 int auto_variant(int op, int64_t M, int64_t D, int64_t FN) {
@@ -166,7 +163,7 @@ int auto_variant(int op, int64_t M, int64_t D, int64_t FN) {
     // (measured on D = 4096, F = 11008: from 256 rows on the separate statistics pass beats the
     // statistics inside the product loop by 7-9 %; below, the split contraction needs the fused form)
     if (op == BB_OP_RMSNORM_SWIGLU_FFN) {
-        if (M <= kStreamMaxM && stream_fits(D)) return BB_VARIANT_STREAM;
+        if (M <= kStreamMaxM) return BB_VARIANT_STREAM;
         // (the fully fused nest, BB_VARIANT_NEST, is no rule-of-thumb choice: a block of 16 rows is served by one
         // compute unit, which reads all three weight matrices alone; measured 28 us against 24 us on 64 x 256 x 704)
         return M >= kPrescaleMinM ? BB_VARIANT_PRESCALE : BB_VARIANT_SNAPSHOT1;
@@ -270,37 +267,42 @@ int validate_ln(const void* X, const void* gamma, const void* beta, const void* 
 
 // ------------------------------------------------------------ workspace plan
 struct StreamPlan {
-    size_t bar_off, zero_off, epoch_off, ppart_off, spart_off, h_off, ypart_off, cnt_off, zone_bytes, total_bytes;
-    int Fp, nkb1, nfb, items1, per1, S1, nkb2, nnb, items2, per2, S2;
+    size_t bar_off, zero_off, epoch_off, cnt_off, zone_bytes, ppart_off, spart_off, h_off, ypart_off, total_bytes;
+    int MT, Fp, nkb1, nfb, items1, per1, S1, nkb2, nnb, items2, per2, S2;
 };
 
-// Layout of the streaming kernels' scratch for G workgroups.  Only the "zone"
-// (barrier words, a block of zeros that nothing ever writes, and the kernels' count
-// of completed grid barriers) has to be zero before the first call; the barrier
-// words and the count only ever increase, and only the kernels touch them.
-StreamPlan stream_plan(int64_t D, int64_t F, int G) {
+// groups of 16 rows the streaming kernel is instantiated for
+int stream_mt(int64_t M) { return M <= 16 ? 1 : 2; }
+
+// Layout of the streaming kernels' scratch for G workgroups and M rows.  Only the "zone"
+// (barrier words, a block of zeros that nothing ever writes, the kernels' count of completed grid
+// barriers, and the arrival counters of the output blocks) has to be zero before the first call: the
+// barrier words and the count only ever increase, a counter is put back to zero by the workgroup that
+// sees it complete, and only the kernels touch them.
+StreamPlan stream_plan(int64_t M, int64_t D, int64_t F, int G) {
     StreamPlan s;
+    s.MT = stream_mt(M);
     s.Fp = (int)((F + 127) / 128 * 128);
     s.nkb1 = (int)((D + 31) / 32);
     s.nfb = (int)((F + 127) / 128);
     s.items1 = s.nkb1 * s.nfb;
-    s.per1 = (s.items1 + G - 1) / G;
+    s.per1 = std::max((s.items1 + G - 1) / G, 1);
     s.S1 = (s.nkb1 - 1) / s.per1 + 2;
     s.nkb2 = (int)((F + 31) / 32);
     s.nnb = (int)((D + 127) / 128);
     s.items2 = s.nkb2 * s.nnb;
-    s.per2 = (s.items2 + G - 1) / G;
+    s.per2 = std::max((s.items2 + G - 1) / G, 1);
     s.S2 = (s.nkb2 - 1) / s.per2 + 2;
     s.bar_off = 0;
     s.zero_off = align_up((size_t)BAR_WORDS * 4);               // 256 bytes that stay zero
     s.epoch_off = s.zero_off + kAlign;                          // the kernels' count of completed grid barriers
-    s.zone_bytes = s.epoch_off + kAlign;
+    s.cnt_off = s.epoch_off + kAlign;
+    s.zone_bytes = s.cnt_off + align_up((size_t)s.nnb * 4);
     s.ppart_off = s.zone_bytes;
-    s.spart_off = s.ppart_off + align_up((size_t)s.nfb * s.S1 * 4096 * 4);
-    s.h_off = s.spart_off + align_up((size_t)s.S1 * 16 * 4);
-    s.ypart_off = s.h_off + align_up((size_t)16 * s.Fp * 2);
-    s.cnt_off = s.ypart_off + align_up((size_t)s.nnb * s.S2 * 2048 * 4);
-    s.total_bytes = s.cnt_off + align_up((size_t)s.nnb * 4);
+    s.spart_off = s.ppart_off + align_up((size_t)s.nfb * s.S1 * s.MT * 4096 * 4);
+    s.h_off = s.spart_off + align_up((size_t)s.S1 * 16 * s.MT * 4);
+    s.ypart_off = s.h_off + align_up((size_t)16 * s.MT * s.Fp * 2);
+    s.total_bytes = s.ypart_off + align_up((size_t)s.nnb * s.S2 * s.MT * 2048 * 4);
     return s;
 }
 
@@ -369,7 +371,7 @@ int attn_key_splits(int64_t wgs, int64_t nt, int cus) {
 }
 
 size_t zone_bytes(int op, int64_t M, int64_t D, int64_t F) {
-    if (op == BB_OP_RMSNORM_SWIGLU_FFN && M <= kStreamMaxM) return stream_plan(D, F, kPlanCUs).total_bytes;
+    if (op == BB_OP_RMSNORM_SWIGLU_FFN && M <= kStreamMaxM) return stream_plan(M, D, F, kPlanCUs).total_bytes;
     return 0;
 }
 
@@ -379,7 +381,7 @@ size_t scratch_bytes(int op, int64_t M, int64_t D, int64_t F) {
         case BB_OP_RMSNORM_SWIGLU_FFN:      // hidden | partial results of a split | gain-scaled X and inverse norms (PRESCALE)
             return align_up((size_t)M * F * 2) +
                    std::max(split_bytes(MODE_GATEUP, M, F, D, kPlanCUs), split_bytes(MODE_PLAIN, M, D, F, kPlanCUs)) +
-                   (M > kStreamMaxM ? align_up((size_t)M * D * 2) + align_up((size_t)M * 4) : 0);
+                   (M > kPrescaleFloorM ? align_up((size_t)M * D * 2) + align_up((size_t)M * 4) : 0);
         case BB_OP_LAYERNORM_MATMUL:        // column vectors and their partial sums | gamma-scaled X and row statistics (PRESCALE)
             return (2 + 2 * COLVEC_SPLITS) * align_up((size_t)F * 4) + align_up((size_t)M * D * 2) +
                    align_up((size_t)M * 8);
@@ -515,17 +517,16 @@ int check_fault(const DeviceInfo* dev) {
 int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u16* W2, const u16* R, u16* Y, int M,
                int D, int F, float eps, const DeviceInfo* dev, hipStream_t st) {
     const int cus = dev->cus;
-    static int resident = -1;      // workgroups of the streaming kernel one compute unit can hold
-    if (resident < 0) {
-        hipError_t e = hipSuccess;
-        const int n = stream_resident(&e);
-        BB_HIP(e);
-        resident = n;
-    }
-    if (resident < 1) return BB_ERR_VARIANT;   // the grid barrier needs every workgroup resident
     const int G = std::min(cus, kPlanCUs);
-    const StreamPlan sp = stream_plan(D, F, G);
-    if ((sp.per2 - 1) / sp.nkb2 + 2 > 64) return BB_ERR_VARIANT;   // (see stream_fits)
+    const StreamPlan sp = stream_plan(M, D, F, G);
+    static int resident[STREAM_MAXMT + 1] = {-1, -1, -1};   // workgroups of the kernel one compute unit can hold
+    if (resident[sp.MT] < 0) {
+        hipError_t e = hipSuccess;
+        const int n = stream_resident(sp.MT, &e);
+        BB_HIP(e);
+        resident[sp.MT] = n;
+    }
+    if (resident[sp.MT] < 1) return BB_ERR_VARIANT;   // the grid barrier needs every workgroup resident
     char* base = (char*)g_ws.ptr;
     if (int rc = prepare_barrier_zone(sp, st)) return rc;
     StreamArgs a;
@@ -544,10 +545,10 @@ int run_stream(const u16* X, const u16* g, const u16* W1, const u16* W3, const u
     a.nkb1 = sp.nkb1; a.nfb = sp.nfb; a.items1 = sp.items1; a.per1 = sp.per1; a.S1 = sp.S1;
     a.nkb2 = sp.nkb2; a.nnb = sp.nnb; a.items2 = sp.items2; a.per2 = sp.per2; a.S2 = sp.S2;
     if (log_on())
-        std::fprintf(stderr, "[bb] stream M %d D %d F %d items %d/%d per wg %d/%d slots %d/%d\n", M, D, F,
-                     a.items1, a.items2, a.per1, a.per2, a.S1, a.S2);
-    prof_begin(st);   // (a refill of the barrier word above, if any, is not part of the kernel's time)
-    stream_launch(G, st, a);
+        std::fprintf(stderr, "[bb] stream M %d (%d x 16 rows) D %d F %d items %d/%d per wg %d/%d slots %d/%d\n", M, sp.MT, D,
+                     F, a.items1, a.items2, a.per1, a.per2, a.S1, a.S2);
+    prof_begin(st);   // (a refill of the zone above, if any, is not part of the kernel's time)
+    stream_launch(sp.MT, G, st, a);
     BB_HIP(hipGetLastError());
     prof_mark("ffn_stream", st);
     return BB_OK;
@@ -584,7 +585,7 @@ StreamTPlan stream_t_plan(int64_t D, int64_t F, int G) {
 int run_stream_t(const u16* X, const u16* g, const u16* W1t, const u16* W3t, const u16* W2t, const u16* R, u16* Y,
                  int M, int D, int F, float eps, const DeviceInfo* dev, hipStream_t st) {
     const int cus = dev->cus;
-    if (M < 1 || M > kStreamMaxM) return BB_ERR_VARIANT;       // (the kernel clamps row numbers to M - 1)
+    if (M < 1 || M > kStreamTMaxM) return BB_ERR_VARIANT;      // (the kernel clamps row numbers to M - 1)
     const int G = std::min(cus, kPlanCUs);
     const StreamTPlan tp = stream_t_plan(D, F, G);
     if (!tp.ok) return BB_ERR_VARIANT;
@@ -596,7 +597,7 @@ int run_stream_t(const u16* X, const u16* g, const u16* W1t, const u16* W3t, con
         resident = nres;
     }
     if (resident < 1) return BB_ERR_VARIANT;    // the grid barrier needs every workgroup resident
-    const StreamPlan sp = stream_plan(D, F, G);        // (barrier words and hidden block: the same places)
+    const StreamPlan sp = stream_plan(M, D, F, G);     // (barrier words and hidden block: the same places)
     char* base = (char*)g_ws.ptr;
     if (int rc = prepare_barrier_zone(sp, st)) return rc;
     StreamTArgs a;
@@ -789,7 +790,7 @@ int ffn_locked(int variant, const void* X, const void* g, const void* W1, const 
     if (variant == BB_VARIANT_UNFUSED && R == nullptr)
         return ffn_unfused_locked(X, g, W1, W3, W2, Y, M, D, F, eps, stream);
     if (variant == BB_VARIANT_UNFUSED) variant = BB_VARIANT_SNAPSHOT1;
-    if (variant == BB_VARIANT_PRESCALE && M <= kStreamMaxM) return BB_ERR_VARIANT;   // (no room is planned for so few rows)
+    if (variant == BB_VARIANT_PRESCALE && M <= kPrescaleFloorM) return BB_ERR_VARIANT;   // (no room is planned for so few rows)
     if (variant == BB_VARIANT_NEST && D > NEST_MAXD) return BB_ERR_VARIANT;          // (the block of outputs no longer fits the registers)
     const DeviceInfo* dev = nullptr;
     if (int rc = current_device_info(&dev)) return rc;
@@ -851,7 +852,7 @@ int ffn_t_locked(const void* X, const void* g, const void* W1t, const void* W3t,
     hipStream_t st = as_stream(stream);
     // few rows: the weight-streaming kernel for this layout (unless a tiled variant is forced)
     const int variant = read_variant();
-    if (M <= kStreamMaxM && (variant == BB_VARIANT_AUTO || variant == BB_VARIANT_STREAM)) {
+    if (M <= kStreamTMaxM && (variant == BB_VARIANT_AUTO || variant == BB_VARIANT_STREAM)) {
         const int rc = run_stream_t((const u16*)X, (const u16*)g, (const u16*)W1t, (const u16*)W3t, (const u16*)W2t,
                                     (const u16*)R, (u16*)Y, (int)M, (int)D, (int)F, eps, dev, st);
         if (rc != BB_ERR_VARIANT) return rc;
@@ -1218,7 +1219,7 @@ int tune_locked(int op, int64_t M, int64_t D, int64_t FN, int reps, hipStream_t 
         if (op == BB_OP_LAYERNORM_MATMUL && (v == BB_VARIANT_STREAM || v == BB_VARIANT_NEST)) continue;
         if (v == BB_VARIANT_NEST && D > NEST_MAXD) continue;
         if (v == BB_VARIANT_STREAM && M > kStreamMaxM) continue;
-        if (op == BB_OP_RMSNORM_SWIGLU_FFN && v == BB_VARIANT_PRESCALE && M <= kStreamMaxM) continue;
+        if (op == BB_OP_RMSNORM_SWIGLU_FFN && v == BB_VARIANT_PRESCALE && M <= kPrescaleFloorM) continue;
         float ms = 0.f;
         rc = time_candidate([&]() { return run(v); }, reps, st, &ms);
         if (rc == BB_ERR_WORKSPACE && g_ws.user) {      // does not fit the caller's workspace: not a candidate

@@ -25,8 +25,9 @@ void splitk_reduce_dispatch(int mode, const float* part, const float* ssqpart, u
                             hipStream_t st);
 
 // streaming kernels: workgroups of the kernel one compute unit can hold (hipError_t in *err), launch
-int stream_resident(hipError_t* err);
-void stream_launch(int G, hipStream_t st, const StreamArgs& a);
+// (row-major weights: ffn_stream_kernel<mt>, mt = 1 or 2 groups of 16 rows)
+int stream_resident(int mt, hipError_t* err);
+void stream_launch(int mt, int G, hipStream_t st, const StreamArgs& a);
 int stream_t_resident(int lds_bytes, hipError_t* err);
 void stream_t_launch(int G, int lds_bytes, hipStream_t st, const StreamTArgs& a);
 

@@ -7,13 +7,16 @@
 
 namespace bb {
 
-int stream_resident(hipError_t* err) {
+template <int MT>
+static int stream_resident_mt(hipError_t* err) {
     int n = 0;
-    *err = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, ffn_stream_kernel, STREAM_THREADS, 0);
+    *err = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, ffn_stream_kernel<MT>, STREAM_THREADS, 0);
     return n;
 }
-void stream_launch(int G, hipStream_t st, const StreamArgs& a) {
-    hipLaunchKernelGGL(ffn_stream_kernel, dim3(G), dim3(STREAM_THREADS), 0, st, a);
+int stream_resident(int mt, hipError_t* err) { return mt == 1 ? stream_resident_mt<1>(err) : stream_resident_mt<2>(err); }
+void stream_launch(int mt, int G, hipStream_t st, const StreamArgs& a) {
+    if (mt == 1) hipLaunchKernelGGL(ffn_stream_kernel<1>, dim3(G), dim3(STREAM_THREADS), 0, st, a);
+    else hipLaunchKernelGGL(ffn_stream_kernel<2>, dim3(G), dim3(STREAM_THREADS), 0, st, a);
 }
 int stream_t_resident(int lds_bytes, hipError_t* err) {
     *err = hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_stream_t_kernel),

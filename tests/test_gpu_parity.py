@@ -77,7 +77,9 @@ def test_ragged_shapes_snapshot1(M, D, F):
     assert err <= TOL
 
 
-@pytest.mark.parametrize("M,D,F", [(1, 64, 64), (5, 264, 712), (16, 256, 704), (9, 72, 136), (16, 520, 1032)])
+@pytest.mark.parametrize("M,D,F", [(1, 64, 64), (5, 264, 712), (16, 256, 704), (9, 72, 136), (16, 520, 1032),
+                                   # two groups of 16 rows
+                                   (17, 72, 136), (32, 520, 1032), (25, 264, 712), (31, 1032, 2056)])
 def test_ragged_shapes_stream(M, D, F):
     err = ffn_case(bb_inputs.make_ffn(M, D, F, seed=M + F), 1e-6, variant=bb.VARIANT_STREAM)
     assert err <= TOL
