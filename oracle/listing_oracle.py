@@ -72,131 +72,123 @@ def bf16_bits_to_f64(a) -> np.ndarray:
     return a.astype(np.float64)
 
 
-def fused_rmsnorm_swiglu_ffn(X, g, W1, W3, W2, eps, nM=1, nN=1, nK=1, nD=1):
-    """Example 3, final fused nest, with block counts (nM, nN, nK, nD) for the
-    row, output-column, hidden and model dimensions."""
+# --- building blocks of the fused nests (each is one stage of a nest, evaluated block by block) ----------
+def _prepared_ffn(X, g, W1, W3, W2):
+    """fp64 operands; the gain is folded into the transposed up-projections: (X diag(g)) W = X (diag(g) W)"""
     X, g, W1, W3, W2 = (bf16_bits_to_f64(t) for t in (X, g, W1, W3, W2))
+    return X, (g[:, None] * W1).T, (g[:, None] * W3).T, W2.T       # X [M,D], WT, VT [F,D], UT [D,F]
+
+
+def _sum_of_squares(X, m, dblocks):
+    """row sums of squares of the row block, accumulated over the model-dimension blocks"""
+    return sum(row_sum(X[m, d] ** 2) for d in dblocks)
+
+
+def _products(X, WT, VT, m, k, dblocks):
+    """the two contractions of row block m with the transposed weight blocks of hidden block k,
+    accumulated over the model-dimension blocks (one pass over X[m, :] serves both)"""
+    p = sum(dot(X[m, d], WT[k, d]) for d in dblocks)
+    q = sum(dot(X[m, d], VT[k, d]) for d in dblocks)
+    return p, q
+
+
+def _hidden_block(p, q, r):
+    """inverse norm applied to the finished products (Rule 4), Swish on one, Hadamard product with the other"""
+    ps, qs = row_scale(p, r), row_scale(q, r)
+    return mul(ps / (1.0 + np.exp(-ps)), qs)
+
+
+def fused_rmsnorm_swiglu_ffn(X, g, W1, W3, W2, eps, nM=1, nN=1, nK=1, nD=1):
+    """Example 3, final fused nest, with block counts (nM, nN, nK, nD) for the row, output-column,
+    hidden and model dimensions.  Everything lives under the (m, n) maps: for every hidden block the
+    statistics and both products are recomputed from X (the replicated work of the extended maps),
+    and the output block accumulates the hidden blocks' contributions one after the other."""
+    X, WT, VT, UT = _prepared_ffn(X, g, W1, W3, W2)
     M, D = X.shape
-    F = W1.shape[1]
-    WT = (g[:, None] * W1).T              # [F, D]  gain folded: (X diag(g)) W
-    VT = (g[:, None] * W3).T              # [F, D]
-    UT = W2.T                             # [D_out, F]
+    F = WT.shape[0]
+    dblocks = _splits(D, nD)
     O = np.zeros((M, D))
-    for m in _splits(M, nM):                       # forall m
-        for n in _splits(D, nN):                   # forall n
-            acc_o = 0.0
-            for k in _splits(F, nK):               # for k (serial reduction)
-                ssq = 0.0
-                p = 0.0
-                q = 0.0
-                for d in _splits(D, nD):           # for d (serial reduction)
-                    x = X[m, d]
-                    ssq = ssq + row_sum(x ** 2)
-                    p = p + dot(x, WT[k, d])
-                    q = q + dot(x, VT[k, d])
-                r = 1.0 / np.sqrt(ssq / D + eps)
-                ps = row_scale(p, r)
-                sw = ps / (1.0 + np.exp(-ps))
-                qs = row_scale(q, r)
-                h = mul(sw, qs)
-                acc_o = acc_o + dot(h, UT[n, k])
-            O[m, n] = acc_o
+    for m in _splits(M, nM):
+        for n in _splits(D, nN):
+            out = 0.0
+            for k in _splits(F, nK):
+                # (in the nest the statistics ride along in the products' loop over d: same sums)
+                r = 1.0 / np.sqrt(_sum_of_squares(X, m, dblocks) / D + eps)
+                h = _hidden_block(*_products(X, WT, VT, m, k, dblocks), r)
+                out = out + dot(h, UT[n, k])
+            O[m, n] = out
     return O
 
 
 def snapshot1_rmsnorm_swiglu_ffn(X, g, W1, W3, W2, eps, nM=1, nN=1, nK=1, nD=1):
-    """Example 3, first snapshot (before the N-map is extended): statistics
-    once per row block, a K-map that writes the hidden blocks to a global
-    buffer, then an N-map that reduces over them."""
-    X, g, W1, W3, W2 = (bf16_bits_to_f64(t) for t in (X, g, W1, W3, W2))
+    """Example 3, first snapshot (before the N-map is extended): statistics once per row block, a
+    K-map that writes the hidden blocks to a list in global memory, then an N-map that reduces over it."""
+    X, WT, VT, UT = _prepared_ffn(X, g, W1, W3, W2)
     M, D = X.shape
-    F = W1.shape[1]
-    WT = (g[:, None] * W1).T
-    VT = (g[:, None] * W3).T
-    UT = W2.T
+    F = WT.shape[0]
+    dblocks, kblocks = _splits(D, nD), _splits(F, nK)
     O = np.zeros((M, D))
     for m in _splits(M, nM):
-        ssq = 0.0
-        for d in _splits(D, nD):
-            ssq = ssq + row_sum(X[m, d] ** 2)
-        r = 1.0 / np.sqrt(ssq / D + eps)
-        hidden = {}                                 # the buffered edge I1[m, k]
-        for ki, k in enumerate(_splits(F, nK)):
-            p = 0.0
-            q = 0.0
-            for d in _splits(D, nD):
-                x = X[m, d]
-                p = p + dot(x, WT[k, d])
-                q = q + dot(x, VT[k, d])
-            ps = row_scale(p, r)
-            hidden[ki] = mul(ps / (1.0 + np.exp(-ps)), row_scale(q, r))
+        r = 1.0 / np.sqrt(_sum_of_squares(X, m, dblocks) / D + eps)
+        hidden = [_hidden_block(*_products(X, WT, VT, m, k, dblocks), r) for k in kblocks]   # the buffered list
         for n in _splits(D, nN):
-            acc = 0.0
-            for ki, k in enumerate(_splits(F, nK)):
-                acc = acc + dot(hidden[ki], UT[n, k])
-            O[m, n] = acc
+            O[m, n] = sum(dot(h, UT[n, k]) for h, k in zip(hidden, kblocks))
     return O
 
 
 def fused_layernorm_matmul(X, gamma, beta, W, eps, nM=1, nN=1, nK=1):
-    """Example 2, final fused nest, with block counts (nM, nN, nK) for rows,
-    output columns and the contraction dimension."""
+    """Example 2, final fused nest, with block counts (nM, nN, nK) for rows, output columns and the
+    contraction dimension: under the (m, n) maps ONE loop over k gathers the row sums and row sums of
+    squares of X, the column sums of the gain-scaled and of the bias-scaled weight block, and the
+    product; mean and deviation are applied to the finished product (Rules 5 and 4)."""
     X, gamma, beta, W = (bf16_bits_to_f64(t) for t in (X, gamma, beta, W))
     M, KK = X.shape
     N = W.shape[1]
     YT = (gamma[:, None] * W).T          # [N, KK]  gain folded into the weights
-    BT = (beta[:, None] * W).T           # [N, KK]  bias row: beta^T W after row_sum
+    BT = (beta[:, None] * W).T           # [N, KK]  its column sums are the bias row beta^T W
+    kblocks = _splits(KK, nK)
     Z = np.zeros((M, N))
     for m in _splits(M, nM):
         for n in _splits(N, nN):
-            s1 = 0.0
-            s2 = 0.0
-            col = 0.0
-            bia = 0.0
-            acc = 0.0
-            for k in _splits(KK, nK):
-                x = X[m, k]
-                s1 = s1 + row_sum(x)
-                s2 = s2 + row_sum(x ** 2)
-                yt = YT[n, k]
-                col = col + row_sum(yt)
-                bia = bia + row_sum(BT[n, k])
-                acc = acc + dot(x, yt)
-            negmu = -s1 / KK
-            rstd = (s2 / KK - negmu ** 2 + eps) ** (-0.5)
-            t = add(outer(negmu, col), acc)
-            t = row_scale(t, rstd)
-            Z[m, n] = t + bia[None, :]
+            sums = {"x": 0.0, "xx": 0.0, "colw": 0.0, "colb": 0.0, "xw": 0.0}
+            for k in kblocks:
+                x, yt = X[m, k], YT[n, k]
+                for name, term in (("x", row_sum(x)), ("xx", row_sum(x ** 2)), ("colw", row_sum(yt)),
+                                   ("colb", row_sum(BT[n, k])), ("xw", dot(x, yt))):
+                    sums[name] = sums[name] + term
+            mean = sums["x"] / KK
+            rstd = (sums["xx"] / KK - mean ** 2 + eps) ** (-0.5)
+            centred = add(outer(-mean, sums["colw"]), sums["xw"])      # (x - mean) gamma W without forming x - mean
+            Z[m, n] = row_scale(centred, rstd) + sums["colb"][None, :]
     return Z
 
 
 # ============================================================ Example 1
 def fused_attention(Q, K, V, nM=1, nN=1, nD=1, nL=1):
-    """Example 1's final fused nest (the "unsafe" Flash Attention the fusion
-    algorithm ends with): per (m, l) output block a serial loop over key blocks
-    n; inside it a serial loop over feature blocks d accumulates the dot of the
-    query block with the key block; the scaled scores are exponentiated block by
-    block, their row sums and the dot with the transposed value block are
-    accumulated, and the rows are divided by the accumulated row sums at the
-    end.  No stabilisation: plain exp.  Q [M,d], K [N,d], V [N,L] float64."""
+    """Example 1's final fused nest (the "unsafe" Flash Attention the fusion algorithm ends with):
+    under the (m, l) maps a serial loop over key blocks; the score block of a key block is a
+    contraction over the feature blocks, its plain exponential (no stabilisation) feeds both running
+    sums - the row sums and the product with the transposed value block - and the rows are divided
+    by the row sums at the very end.  Q [M,d], K [N,d], V [N,L] float64."""
     Mt, dt = Q.shape
     Nt, Lt = V.shape
-    mb, nb = np.array_split(np.arange(Mt), nM), np.array_split(np.arange(Nt), nN)
-    db, lb = np.array_split(np.arange(dt), nD), np.array_split(np.arange(Lt), nL)
-    O = np.empty((Mt, Lt))
+    rows, keys = np.array_split(np.arange(Mt), nM), np.array_split(np.arange(Nt), nN)
+    feats, vals = np.array_split(np.arange(dt), nD), np.array_split(np.arange(Lt), nL)
     VT = V.T
-    for m in mb:
-        for l in lb:
-            t5 = np.zeros(len(m))
-            t7 = np.zeros((len(m), len(l)))
-            for n in nb:
-                t3 = np.zeros((len(m), len(n)))
-                for d in db:
-                    t3 = add(t3, dot(Q[np.ix_(m, d)], K[np.ix_(n, d)]))
-                t4 = np.exp(t3 * (dt ** -0.5))
-                t5 = add(t5, row_sum(t4))
-                t7 = add(t7, dot(t4, VT[np.ix_(l, n)]))
-            O[np.ix_(m, l)] = row_scale(t7, 1.0 / t5)
+    O = np.empty((Mt, Lt))
+
+    def exp_scores(m, n):
+        return np.exp(sum(dot(Q[np.ix_(m, d)], K[np.ix_(n, d)]) for d in feats) * (dt ** -0.5))
+
+    for m in rows:
+        for l in vals:
+            denominator = np.zeros(len(m))
+            numerator = np.zeros((len(m), len(l)))
+            for n in keys:
+                e = exp_scores(m, n)
+                denominator = add(denominator, row_sum(e))
+                numerator = add(numerator, dot(e, VT[np.ix_(l, n)]))
+            O[np.ix_(m, l)] = row_scale(numerator, 1.0 / denominator)
     return O
 
 

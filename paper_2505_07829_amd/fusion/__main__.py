@@ -29,19 +29,17 @@ def main() -> None:
         if args.steps:
             print(emit.listing(g), "\n")
 
-    def snapshot(k: int) -> None:
-        err = check.max_error(g, args.example)
-        print(f"\n# snapshot {k}: {emit.intermediate_buffers(g)} intermediate lists in global memory, "
-              f"max relative deviation from the array program on random blocks {err:.1e}")
-        print(emit.listing(g), "\n")
+    taken = [0]
 
-    algorithm.bfs_fuse_no_extend(g, after)
-    k = 1
-    snapshot(k)
-    while algorithm.bfs_extend(g, after) is not None:
-        algorithm.bfs_fuse_no_extend(g, after)
-        k += 1
-        snapshot(k)
+    def snapshot(cur) -> None:
+        taken[0] += 1
+        err = check.max_error(cur, args.example)
+        print(f"\n# snapshot {taken[0]}: {emit.intermediate_buffers(cur)} intermediate lists in global memory, "
+              f"loop nest {emit.nest(cur)}, "
+              f"max relative deviation from the array program on random blocks {err:.1e}")
+        print(emit.listing(cur), "\n")
+
+    algorithm.fuse_in_place(g, after, snapshot)
 
 
 if __name__ == "__main__":

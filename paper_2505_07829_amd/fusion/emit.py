@@ -8,7 +8,7 @@ global memory are I1, I2, ... in order of their first store.
 
 `listing(g)` returns the text; `skeleton(g)` the same program with the loads
 folded into the expressions that use them and no variable numbers on plain
-loads, one statement per line, which is what the tests compare.
+loads, one statement per line; `nest(g)` only the loop structure.
 """
 from __future__ import annotations
 
@@ -205,6 +205,36 @@ def listing(g: Graph) -> str:
 
 def skeleton(g: Graph) -> str:
     return "\n".join(str(l) for l in _emit(g, True).lines)
+
+
+def nest(g: Graph) -> str:
+    """The loop structure of the program without its statements: a parallel loop over dimension X
+    is written X(...), a serial one x(...), siblings are separated by blanks, an innermost loop has no parentheses; e.g. "M(n(d) L(n))"
+    is a parallel loop over M that holds a serial loop over N with a serial loop over D inside,
+    followed by a parallel loop over L with a serial loop over N inside."""
+    out: List[str] = []
+    depth_open: List[int] = []
+
+    def close_to(depth: int) -> None:
+        while depth_open and depth_open[-1] >= depth:
+            depth_open.pop()
+            out.append(")")
+
+    for line in _emit(g, True).lines:
+        text = str(line)
+        depth = len(text) - len(text.lstrip("\t"))
+        body = text.strip()
+        close_to(depth)
+        for kw, par in (("forall ", True), ("for ", False)):
+            if body.startswith(kw):
+                var = body[len(kw):].split(" ")[0]
+                if out and out[-1] != "(":
+                    out.append(" ")
+                out.append((var.upper() if par else var.lower()) + "(")
+                depth_open.append(depth)
+                break
+    close_to(0)
+    return "".join(out).replace("( ", "(").replace("()", "")
 
 
 def intermediate_buffers(g: Graph) -> int:
