@@ -171,9 +171,14 @@ int bb_rmsnorm_swiglu_ffn(const void* X, const void* g, const void* W1,
  *
  *   X [M, D] in   gamma [D] in   beta [D] in   W [D, N] in   Y [M, N] out
  *
- * D and N positive multiples of 8, M >= 0.  The one-pass variance
- * sum(x^2)/D - mean^2 is evaluated in fp32: rows whose |mean|/std exceeds a
- * few hundred lose accuracy.  Workspace: bb_workspace_bytes(
+ * D and N positive multiples of 8, M >= 0.  With the statistics inside the
+ * product loop (BB_VARIANT_SNAPSHOT1: AUTO's choice below 256 rows) the
+ * variance is the one-pass form sum(x^2)/D - mean^2 in fp32: rows whose
+ * |mean|/std exceeds a few hundred lose accuracy.  BB_VARIANT_PRESCALE (AUTO
+ * from 256 rows on) takes two passes over the row (mean, then the sum of
+ * squared deviations) and has no such limit, so the two sides of the row
+ * threshold differ on such inputs; a caller with large means selects
+ * BB_VARIANT_PRESCALE or BB_VARIANT_UNFUSED for every M.  Workspace: bb_workspace_bytes(
  * BB_OP_LAYERNORM_MATMUL, M, D, N) (fp32 column vectors of length N and their
  * partial sums).
  */
