@@ -29,16 +29,18 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this same script (profiles/hbm_traffic_c2_c3_attention.txt; FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 as
+# this same script (profiles/hbm_traffic_c1_c2_c3_ffn.txt, attention: profiles/hbm_traffic_c2_c3_attention.txt;
+# FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 as
 # calibrated against bb_calib_copy).  Counters cannot be read from inside a timed run, so the
 # figures are carried here (the line says so in "traffic_source"); workloads without a counter run report null.
-TRAFFIC_SOURCE = ("carried from profiles/hbm_traffic_c2_c3_attention.txt (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE "
+TRAFFIC_SOURCE = ("carried from profiles/hbm_traffic_c1_c2_c3_ffn.txt and hbm_traffic_c2_c3_attention.txt (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE "
                   "runs of this script, scaled by a copy of known size); not measured in this run")
 MEASURED_TRAFFIC_BYTES = {
+    ("c1", "ffn_nest"): 4.49e6 + 0.03e6,
     ("c2", "ffn_stream"): 280.4e6 + 16.2e6,
     ("c2", "ffn_stream_t"): 275.0e6 + 0.7e6,
-    ("c3", "gemm_gateup"): 621.5e6 + 45.2e6,
-    ("c3", "gemm_gateup_prescaled"): 624.2e6 + 45.1e6,
+    ("c3", "gemm_gateup"): 621.5e6 + 46.2e6,
+    ("c3", "gemm_gateup_prescaled"): 632.6e6 + 45.1e6,
     ("attention", "attention"): 100.9e6 + 33.6e6,
     ("attention", "attention_decode"): 67.6e6 + 0.3e6,
 }
