@@ -451,7 +451,13 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
     // that plan, and a plan for fewer units can ask for more splits than it has room for)
     const int nsplit = split ? plan_split(MODE, M, N, K, kPlanCUs, &nk_split, &split_bm) : 1;
     const bool do_split = nsplit >= 2;
-    const bool big = do_split ? split_bm == 256 : tiles256 >= cus;
+    // 256-row tiles or 128-row tiles: whichever needs less time for its rounds on `cus` compute units.  A 128-row
+    // tile costs about 0.75 of a 256-row tile (the same weight loads for half the flops, one wavefront per SIMD).
+    // E.g. 512 rows of c3's gate/up: 172 tiles of 256 rows in one round against 344 of 128 rows in two; 640 rows:
+    // 258 tiles of 256 rows would need a second round for two tiles, 430 of 128 rows take two short rounds
+    const int tiles128 = ((M + 127) / 128) * a.tiles_n;
+    const int rounds256 = (tiles256 + cus - 1) / cus, rounds128 = (tiles128 + cus - 1) / cus;
+    const bool big = do_split ? split_bm == 256 : (M >= 256 && 100 * rounds256 <= 75 * rounds128);
     const int BM = big ? 256 : 128;
     a.tiles_m = (M + BM - 1) / BM;
     const int tiles = a.tiles_m * a.tiles_n;
