@@ -431,6 +431,16 @@ void mark_dirty(size_t off) {
 }
 
 // ------------------------------------------------------------------- launches
+// Row tiles per group of the tile order (see gemm_kernel's tile coordinates).  The 32 workgroups that an XCD runs
+// together should need few distinct operand tiles: its L2 fetches each of them over the fabric once per step.  With
+// g row tiles and 32 / g column tiles that is g A tiles + 32 / g B tiles; measured (gate/up of 4096 x 8192 x 28672,
+// ms): g = 16 (the order by columns) 3.07, 8 2.81, 4 2.76, 2 2.85, 1 3.08; the product of 8192 x 4096 x 16384: 32
+// 0.946, 8 0.845, 4 0.830.  Four beats eight although both fetch 12 tiles: an A tile is 256 pieces of 128 bytes, a B
+// tile 64 pieces of 512.  128-row tiles have A tiles of half the size: eight.  BB_GROUP_M overrides (measurements).
+int gemm_group_m(int BM) {
+    static const int forced = [] { const char* e = std::getenv("BB_GROUP_M"); return e ? std::atoi(e) : 0; }();
+    return forced > 0 ? forced : (BM == 256 ? 4 : 8);
+}
 // `split`: device scratch of split_bytes(...) for this launch, or nullptr (never split).
 // BT: B0/B1 are given transposed ([N, K] row-major, ldb = K).
 template <int MODE, bool BT = false>
@@ -460,6 +470,7 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
     const bool big = do_split ? split_bm == 256 : (M >= 256 && 100 * rounds256 <= 75 * rounds128);
     const int BM = big ? 256 : 128;
     a.tiles_m = (M + BM - 1) / BM;
+    a.group_m = std::min(a.tiles_m, gemm_group_m(BM));
     const int tiles = a.tiles_m * a.tiles_n;
     if (do_split) {
         a.nsplit = nsplit;

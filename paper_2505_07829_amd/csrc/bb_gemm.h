@@ -86,6 +86,7 @@ struct GemmArgs {
     int M, N, K;
     int lda, ldb, ldc;
     int tiles_m, tiles_n, tiles_per_xcd;
+    int group_m;         // row tiles per group of the tile order (see the kernel's tile coordinates)
     float eps;
     // split contraction (SPLIT kernels): `nsplit` workgroups per tile, each with
     // `nk_split` contraction steps; fp32 partial results part[split][M][ldp]
@@ -220,14 +221,20 @@ __global__ __launch_bounds__(64 * NW) void gemm_kernel(const GemmArgs p) {
     __shared__ float stat1[BM];                      // mean (LN)
 
     // ---- tile coordinates: workgroup id -> XCD (id % 8) -> contiguous range
-    // of tiles per XCD, row tiles fastest, so the tiles resident on one XCD
-    // share B columns and A rows in that XCD's L2.
+    // of the tile order per XCD.  The order runs through groups of `group_m` row
+    // tiles, inside a group row tiles fastest: the 32 tiles that an XCD works
+    // on together are then a block of about 8 row tiles x 4 column tiles, the
+    // shape with the fewest distinct A and B tiles (12 against 18 for 16 x 2 and 33 for
+    // 32 x 1), which is what the XCD's L2 has to fetch over the fabric per step.
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
     const int lin = xcd * p.tiles_per_xcd + local;
     const int ntiles = p.tiles_m * p.tiles_n;
     if (local >= p.tiles_per_xcd || lin >= (SPLIT ? ntiles * p.nsplit : ntiles)) return;
     const int tile = SPLIT ? lin % ntiles : lin, split = SPLIT ? lin / ntiles : 0;
-    const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
+    const int per_group = p.group_m * p.tiles_n;
+    const int grp = tile / per_group, in_grp = tile - grp * per_group;
+    const int rows_grp = min(p.group_m, p.tiles_m - grp * p.group_m);      // (the last group may be shorter)
+    const int tm = grp * p.group_m + in_grp % rows_grp, tn = in_grp / rows_grp;
     const int kt0 = SPLIT ? split * p.nk_split : 0;           // first contraction step of this workgroup
     const int m0 = tm * BM, n0 = tn * NCOL;
 

@@ -444,6 +444,31 @@ def test_split_contraction_256_row_tiles(M, D, F):
     assert row_rel_err(Yr[rows], ref + X[rows].double().numpy()) <= TOL
 
 
+# ---------------------------------------------------------------- tile order
+# The tiles are walked in groups of row tiles (four 256-row tiles or eight 128-row tiles); shapes whose number of row
+# tiles is no multiple of the group: 6 = 4 + 2 tiles of 256 rows (the last one ragged), 11 = 8 + 3 tiles of 128 rows.
+@pytest.mark.parametrize("M,D,F", [(1300, 128, 3072), (1408, 128, 384), (1330, 72, 3080)])
+@pytest.mark.parametrize("variant", [bb.VARIANT_SNAPSHOT1, bb.VARIANT_PRESCALE])
+def test_tile_order_with_a_short_last_group_ffn(M, D, F, variant):
+    cpu = bb_inputs.make_ffn(M, D, F, seed=M + F)
+    assert ffn_case(cpu, 1e-6, variant=variant) <= TOL
+    assert ffn_case(cpu, 1e-6, unfused=True) <= TOL
+
+
+@pytest.mark.parametrize("M,D,N", [(1300, 128, 6144), (1408, 64, 768)])
+def test_tile_order_with_a_short_last_group_ln(M, D, N):
+    cpu = bb_inputs.make_ln(M, D, N, seed=M + N)
+    ref = orc.layernorm_matmul(*cpu, 1e-5)
+    for variant in (bb.VARIANT_PRESCALE, bb.VARIANT_SNAPSHOT1):
+        bb.bb_set_variant(variant)
+        try:
+            Y = bb.bb_layernorm_matmul(*dev(cpu), 1e-5)
+            torch.cuda.synchronize()
+        finally:
+            bb.bb_set_variant(bb.VARIANT_AUTO)
+        assert row_rel_err(Y, ref) <= TOL
+
+
 # ---------------------------------------------------------------- statistics loop as its own kernel
 @pytest.mark.parametrize("M,D,F", [(17, 72, 136), (130, 264, 712), (300, 520, 1032), (512, 1024, 2816),
                                    (2048, 1024, 2816)])
