@@ -291,7 +291,7 @@ def run_workload(name, steps, warmup, with_cpu, torch, bb, bb_inputs, orc, np, c
     dom_ms = ms_step_events if len(kernels_ms) == 1 else kernels_ms[dom]
     res = {
         "workload": name, "op": cfg.op, "M": cfg.M, "D": cfg.D, "F_or_N": cfg.F,
-        "variant": "stream" if stream_variant else (
+        "variant": "stream" if stream_variant else "nest" if dom == "ffn_nest" else (
             "prescale" if dom.endswith("_prescaled") else "snapshot1"),
         "ms_per_step": ms_step, "ms_per_step_events": ms_step_events,
         "tflops": flops_of(cfg) / (ms_step * 1e-3) / 1e12,

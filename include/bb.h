@@ -107,11 +107,14 @@ typedef enum bb_status {
  *                       registers throughout.  The hidden never leaves the
  *                       compute unit; no workspace is touched.  BB_ERR_VARIANT
  *                       when D > 512 (the output block no longer fits).  A
- *                       candidate of the measured selection below, never the
- *                       rule of thumb's choice: one compute unit per 16 rows
- *                       reads all three weight matrices alone.
+ *                       candidate of the measured selection below and the
+ *                       rule of thumb's choice for small weight matrices (one
+ *                       compute unit per 16 rows reads all three of them
+ *                       alone: it wins where six pairs of wavefronts take all
+ *                       hidden blocks at once).
  * BB_VARIANT_AUTO      the measured selection for exactly this shape if
- *                       bb_*_tune has recorded one, else STREAM for M <= 32,
+ *                       bb_*_tune has recorded one, else NEST for D <= 256 and
+ *                       F <= 768, else STREAM for M <= 32,
  *                       SNAPSHOT1 up to 255 rows and PRESCALE from 256 rows on
  *                       (the table measured on an MI355X for D = 4096,
  *                       F = 11008); LN -> matmul: SNAPSHOT1 up to 255 rows,

@@ -27,6 +27,7 @@ using namespace bb;
 constexpr int64_t kStreamMaxM = 16 * STREAM_MAXMT;   // rows the weight-streaming kernel handles (row-major weights)
 constexpr int64_t kStreamTMaxM = 16;  // rows the weight-streaming kernel for transposed weights handles
 constexpr int64_t kPrescaleFloorM = 16; // up to this many rows no room is planned for BB_VARIANT_PRESCALE's gain-scaled copy of X
+constexpr int64_t kNestAutoMaxD = 256, kNestAutoMaxF = 768;   // shapes on which AUTO runs the fully fused nest
 constexpr int64_t kPrescaleMinM = 256; // rows from which AUTO runs the statistics loop as a kernel of its own
 constexpr size_t kAlign = 256;
 
@@ -156,16 +157,21 @@ struct TuneKey {
 std::map<TuneKey, int> g_tuned;
 
 // AUTO: a measured selection for exactly this shape if there is one, else the rule of thumb
-// (weight-streaming kernel up to kStreamMaxM rows, tiled kernels beyond; LN always fused)
+// (the fully fused nest for small weight matrices, else the weight-streaming kernel up to kStreamMaxM rows and
+// the tiled kernels beyond; LN always fused)
 int auto_variant(int op, int64_t M, int64_t D, int64_t FN) {
     auto it = g_tuned.find(TuneKey{op, M, D, FN});
     if (it != g_tuned.end()) return it->second;
     // (measured on D = 4096, F = 11008: from 256 rows on the separate statistics pass beats the
     // statistics inside the product loop by 7-9 %; below, the split contraction needs the fused form)
     if (op == BB_OP_RMSNORM_SWIGLU_FFN) {
+        // The fully fused nest (one launch, a block of 16 rows per compute unit, which reads all three weight
+        // matrices alone) where its six wavefront pairs take all hidden blocks in one trip: measured 10-19 us against
+        // 15-35 us for the best other program on 16...4096 rows of 64 x 256, 128 x 768, 192 x 768, 256 x 704 and
+        // 256 x 768 (D x F).  With a second trip (F = 1024...1536) it wins only from some thousand rows on, with
+        // D > 256 (four pairs, twice the steps per block) nowhere: left to the measured selection.
+        if (D <= kNestAutoMaxD && FN <= kNestAutoMaxF) return BB_VARIANT_NEST;
         if (M <= kStreamMaxM) return BB_VARIANT_STREAM;
-        // (the fully fused nest, BB_VARIANT_NEST, is no rule-of-thumb choice: a block of 16 rows is served by one
-        // compute unit, which reads all three weight matrices alone; measured 28 us against 24 us on 64 x 256 x 704)
         return M >= kPrescaleMinM ? BB_VARIANT_PRESCALE : BB_VARIANT_SNAPSHOT1;
     }
     return M >= kPrescaleMinM ? BB_VARIANT_PRESCALE : BB_VARIANT_SNAPSHOT1;

@@ -108,6 +108,25 @@ def test_nest_is_one_launch_on_c1():
     assert row_rel_err(Y, orc.rmsnorm_swiglu_ffn(*cpu, c.eps)) <= TOL
 
 
+def launches_of_auto(M, D, F):
+    d = dev(bb_inputs.make_ffn(M, D, F, seed=3))
+    bb.bb_profile_enable(True)
+    try:
+        bb.bb_rmsnorm_swiglu_ffn(*d, 1e-6)
+        return [k for k, _ in bb.bb_profile_last()]
+    finally:
+        bb.bb_profile_enable(False)
+
+
+def test_auto_runs_the_nest_where_its_wavefront_pairs_take_all_hidden_blocks_at_once():
+    # D <= 256 and F <= 768, any number of rows (also those the streaming kernel would take)
+    for M, D, F in [(64, 256, 704), (8, 128, 768), (1500, 200, 696)]:
+        assert launches_of_auto(M, D, F) == ["ffn_nest"], (M, D, F)
+    # one more hidden block, or a wider model: the other programs
+    for M, D, F in [(64, 256, 776), (64, 264, 704), (8, 256, 1408)]:
+        assert "ffn_nest" not in launches_of_auto(M, D, F), (M, D, F)
+
+
 def test_nest_refuses_a_model_dimension_whose_output_block_does_not_fit():
     cpu = bb_inputs.make_ffn(32, 520, 256, seed=2)
     bb.bb_set_variant(bb.VARIANT_NEST)
