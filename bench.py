@@ -36,11 +36,11 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
 TRAFFIC_SOURCE = ("carried from profiles/hbm_traffic_c1_c2_c3_ffn.txt and hbm_traffic_c2_c3_attention.txt (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE "
                   "runs of this script, scaled by a copy of known size); not measured in this run")
 MEASURED_TRAFFIC_BYTES = {
-    ("c1", "ffn_nest"): 4.49e6 + 0.03e6,
+    ("c1", "ffn_nest"): 4.45e6 + 0.03e6,
     ("c2", "ffn_stream"): 280.4e6 + 16.2e6,
     ("c2", "ffn_stream_t"): 275.0e6 + 0.7e6,
-    ("c3", "gemm_gateup"): 621.5e6 + 46.2e6,
-    ("c3", "gemm_gateup_prescaled"): 632.6e6 + 45.1e6,
+    ("c3", "gemm_gateup"): 588.0e6 + 45.1e6,
+    ("c3", "gemm_gateup_prescaled"): 587.6e6 + 45.1e6,
     ("attention", "attention"): 100.9e6 + 33.6e6,
     ("attention", "attention_decode"): 67.6e6 + 0.3e6,
 }
