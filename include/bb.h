@@ -113,8 +113,8 @@ typedef enum bb_status {
  *                       alone: it wins where six pairs of wavefronts take all
  *                       hidden blocks at once).
  * BB_VARIANT_AUTO      the measured selection for exactly this shape if
- *                       bb_*_tune has recorded one, else NEST for D <= 256 and
- *                       F <= 768, else STREAM for M <= 32,
+ *                       bb_*_tune has recorded one, else NEST for D <= 256,
+ *                       F <= 768 and M <= 4096, else STREAM for M <= 32,
  *                       SNAPSHOT1 up to 255 rows and PRESCALE from 256 rows on
  *                       (the table measured on an MI355X for D = 4096,
  *                       F = 11008); LN -> matmul: SNAPSHOT1 up to 255 rows,

@@ -27,7 +27,7 @@ using namespace bb;
 constexpr int64_t kStreamMaxM = 16 * STREAM_MAXMT;   // rows the weight-streaming kernel handles (row-major weights)
 constexpr int64_t kStreamTMaxM = 16;  // rows the weight-streaming kernel for transposed weights handles
 constexpr int64_t kPrescaleFloorM = 16; // up to this many rows no room is planned for BB_VARIANT_PRESCALE's gain-scaled copy of X
-constexpr int64_t kNestAutoMaxD = 256, kNestAutoMaxF = 768;   // shapes on which AUTO runs the fully fused nest
+constexpr int64_t kNestAutoMaxD = 256, kNestAutoMaxF = 768, kNestAutoMaxM = 16 * 256;   // shapes on which AUTO runs the fully fused nest
 constexpr int64_t kPrescaleMinM = 256; // rows from which AUTO runs the statistics loop as a kernel of its own
 constexpr size_t kAlign = 256;
 
@@ -169,8 +169,9 @@ int auto_variant(int op, int64_t M, int64_t D, int64_t FN) {
         // matrices alone) where its six wavefront pairs take all hidden blocks in one trip: measured 10-19 us against
         // 15-35 us for the best other program on 16...4096 rows of 64 x 256, 128 x 768, 192 x 768, 256 x 704 and
         // 256 x 768 (D x F).  With a second trip (F = 1024...1536) it wins only from some thousand rows on, with
-        // D > 256 (four pairs, twice the steps per block) nowhere: left to the measured selection.
-        if (D <= kNestAutoMaxD && FN <= kNestAutoMaxF) return BB_VARIANT_NEST;
+        // D > 256 (four pairs, twice the steps per block) nowhere: left to the measured selection.  Beyond 4096 rows
+        // (more blocks of 16 rows than compute units: a second round) the tiled kernels win again.
+        if (D <= kNestAutoMaxD && FN <= kNestAutoMaxF && M <= kNestAutoMaxM) return BB_VARIANT_NEST;
         if (M <= kStreamMaxM) return BB_VARIANT_STREAM;
         return M >= kPrescaleMinM ? BB_VARIANT_PRESCALE : BB_VARIANT_SNAPSHOT1;
     }

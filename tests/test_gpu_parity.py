@@ -122,8 +122,8 @@ def test_auto_runs_the_nest_where_its_wavefront_pairs_take_all_hidden_blocks_at_
     # D <= 256 and F <= 768, any number of rows (also those the streaming kernel would take)
     for M, D, F in [(64, 256, 704), (8, 128, 768), (1500, 200, 696)]:
         assert launches_of_auto(M, D, F) == ["ffn_nest"], (M, D, F)
-    # one more hidden block, or a wider model: the other programs
-    for M, D, F in [(64, 256, 776), (64, 264, 704), (8, 256, 1408)]:
+    # one more hidden block, a wider model, or more blocks of 16 rows than compute units: the other programs
+    for M, D, F in [(64, 256, 776), (64, 264, 704), (8, 256, 1408), (4112, 64, 128)]:
         assert "ffn_nest" not in launches_of_auto(M, D, F), (M, D, F)
 
 
