@@ -28,12 +28,12 @@
 // C [M,N] row-major, all bf16.  fp32 accumulation in 32x32x16 matrix
 // instructions.
 //
-// Tiling: 256 threads = 4 wavefronts, workgroup tile BM x 256 columns (GATEUP:
+// Tiling: 4 or 8 wavefronts, workgroup tile BM x 256 columns (GATEUP:
 // 128 hidden units = 128 columns of W1 + the same 128 of W3), contraction step
-// 64, LDS double buffered with one barrier per step.  PLAIN and GATEUP_PRE
-// arrange the wavefronts 2x2 (least LDS read traffic; in GATEUP_PRE a
-// wavefront takes 64 columns of W1 and the same 64 of W3); GATEUP and LN
-// arrange them 4x1, so that every wavefront owns its rows of A alone (see
+// 64, LDS double buffered with one barrier per step.  PLAIN, GATEUP_PRE and LN_PRE
+// arrange the wavefronts 2x2 or 2x4 (least LDS read traffic; in GATEUP_PRE a
+// wavefront takes columns of W1 and the same ones of W3); GATEUP and LN
+// arrange them 4x1 or 8x1, so that every wavefront owns its rows of A alone (see
 // "A operand").
 //
 // Both operand tiles go from global memory straight into LDS with load-to-LDS
@@ -195,14 +195,15 @@ __device__ __forceinline__ void quad_transpose_f32(float (&y)[4], bool upper, bo
 // of the paper's block programs (W^T) and of linear-layer checkpoints.  Its tile
 // then lies in LDS exactly like the A tile (rows of 8 contraction chunks, same
 // swizzle, same load-to-LDS role) and its fragments are plain 128-bit reads.
-// NW: wavefronts per workgroup.  4 (one per SIMD, a 128 x 128 wavefront tile in 256 accumulator registers), or,
-// for the modes without prologue on 256-row tiles, 8 (two per SIMD, 128 x 64 each in 128 accumulator registers:
-// while one wavefront's LDS reads and load-to-LDS instructions issue, the other's matrix instructions do).
+// NW: wavefronts per workgroup.  4 (one per SIMD, a 128 x 128 or 64 x 256 wavefront tile in 256 accumulator registers),
+// or, on 256-row tiles, 8 (two per SIMD, 128 x 64 or 32 x 256 each in 128 accumulator registers: while one wavefront's
+// LDS reads, load-to-LDS instructions and prologue arithmetic issue, the other's matrix instructions do).
 template <int MODE, int BM, bool FULL, bool ODD, bool SPLIT = false, bool BT = false, int NW = 4>
 __global__ __launch_bounds__(64 * NW) void gemm_kernel(const GemmArgs p) {
-    static_assert(NW == 4 || (NW == 8 && BM == 256 && MODE != MODE_GATEUP && MODE != MODE_LN), "8 wavefronts: 256-row tiles, no prologue");
+    static_assert(NW == 4 || (NW == 8 && BM == 256), "8 wavefronts: 256-row tiles");
     // (2 x 2 wherever the A fragments need no prologue: least LDS read traffic)
-    constexpr int WM = (MODE == MODE_PLAIN || MODE == MODE_GATEUP_PRE || MODE == MODE_LN_PRE) ? 2 : 4;   // wavefronts along the rows
+    // wavefronts along the rows (with a prologue: all of them, so that no A fragment is prepared twice)
+    constexpr int WM = (MODE == MODE_PLAIN || MODE == MODE_GATEUP_PRE || MODE == MODE_LN_PRE) ? 2 : NW;
     constexpr int WN = NW / WM;                         // and along the columns
     constexpr int WR = BM / WM, WC = 256 / WN;          // wavefront tile
     constexpr int MT = WR / 32, NT = WC / 32;           // 32x32 subtiles per wavefront

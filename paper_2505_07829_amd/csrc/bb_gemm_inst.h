@@ -14,11 +14,13 @@ template <int MODE, bool BT>
 void gemm_dispatch(int bm, bool full, bool odd, bool split, dim3 grid, hipStream_t st, const GemmArgs& a) {
     using T = std::true_type;
     using F_ = std::false_type;
-    // Complete 256-row tiles of the modes without a prologue run with eight wavefronts (two per SIMD, 128 x 64
-    // accumulators each): one wavefront's fragment reads and load-to-LDS instructions issue under the other's
-    // matrix instructions (86 % instead of 78 % of the cycles of a step are matrix cycles; the chip's clock
-    // gives most of that back: 2 % less time per launch).
-    constexpr bool WIDE = (MODE == MODE_PLAIN || MODE == MODE_GATEUP_PRE || MODE == MODE_LN_PRE) && !BT;
+    // Complete 256-row tiles of row-major weights run with eight wavefronts (two per SIMD): one wavefront's
+    // fragment reads, load-to-LDS instructions and prologue arithmetic issue under the other's matrix instructions.
+    // Without a prologue the wavefronts lie 2 x 4 over the tile (128 x 64 accumulators each; 86 % instead of 78 %
+    // of the cycles of a step are matrix cycles, and the chip's clock gives most of that back); with the norm
+    // prologue 8 x 1 (32 x 256 each), so that no A fragment is prepared twice (c3's gate/up with the statistics in
+    // the loop 0.35 -> 0.33 ms, c5's LN product 1.10 -> 0.92 ms).
+    constexpr bool WIDE = !BT;
     auto go = [&](auto BMc, auto FULLc, auto ODDc, auto SPLITc) {
         constexpr int BM = decltype(BMc)::value;
         constexpr bool FULL = decltype(FULLc)::value;
