@@ -19,7 +19,7 @@ void gemm_dispatch(int bm, bool full, bool odd, bool split, dim3 grid, hipStream
     // Without a prologue the wavefronts lie 2 x 4 over the tile (128 x 64 accumulators each; 86 % instead of 78 %
     // of the cycles of a step are matrix cycles, and the chip's clock gives most of that back); with the norm
     // prologue 8 x 1 (32 x 256 each), so that no A fragment is prepared twice (c3's gate/up with the statistics in
-    // the loop 0.35 -> 0.33 ms, c5's LN product 1.10 -> 0.92 ms).
+    // the loop 362 -> 336 us, c5's LN product 1035-1100 -> 991 us).
     constexpr bool WIDE = !BT;
     auto go = [&](auto BMc, auto FULLc, auto ODDc, auto SPLITc) {
         constexpr int BM = decltype(BMc)::value;
