@@ -14,17 +14,17 @@ template <int MODE, bool BT>
 void gemm_dispatch(int bm, bool full, bool odd, bool split, dim3 grid, hipStream_t st, const GemmArgs& a) {
     using T = std::true_type;
     using F_ = std::false_type;
-    // Complete 256-row tiles of row-major weights run with eight wavefronts (two per SIMD): one wavefront's
-    // fragment reads, load-to-LDS instructions and prologue arithmetic issue under the other's matrix instructions.
-    // Without a prologue the wavefronts lie 2 x 4 over the tile (128 x 64 accumulators each; 86 % instead of 78 %
-    // of the cycles of a step are matrix cycles, and the chip's clock gives most of that back); with the norm
-    // prologue 8 x 1 (32 x 256 each), so that no A fragment is prepared twice (c3's gate/up with the statistics in
-    // the loop 362 -> 336 us, c5's LN product 1035-1100 -> 991 us).
-    constexpr bool WIDE = !BT;
+    // Complete 256-row tiles run with eight wavefronts (two per SIMD): one wavefront's fragment reads, load-to-LDS
+    // instructions and prologue arithmetic issue under the other's matrix instructions.  Without a prologue the
+    // wavefronts lie 2 x 4 over the tile (128 x 64 accumulators each; 86 % instead of 78 % of the cycles of a step
+    // are matrix cycles, and the chip's clock gives most of that back); with the norm prologue 8 x 1 (32 x 256
+    // each), so that no A fragment is prepared twice (kernel traces: c3's gate/up with the statistics in the loop
+    // 362 -> 336 us, c5's LN product 1035-1100 -> 991 us).  Transposed weights: c3's gate/up 295 -> 287 us, c5's
+    // product 861 -> 827 us (relative to the row-major kernels of the same runs).
     auto go = [&](auto BMc, auto FULLc, auto ODDc, auto SPLITc) {
         constexpr int BM = decltype(BMc)::value;
         constexpr bool FULL = decltype(FULLc)::value;
-        constexpr int NW = (WIDE && BM == 256 && FULL) ? 8 : 4;
+        constexpr int NW = (BM == 256 && FULL) ? 8 : 4;
         hipLaunchKernelGGL((gemm_kernel<MODE, BM, FULL, decltype(ODDc)::value, decltype(SPLITc)::value, BT, NW>), grid,
                            dim3(64 * NW), 0, st, a);
     };
