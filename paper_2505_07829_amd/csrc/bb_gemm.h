@@ -277,6 +277,20 @@ __global__ __launch_bounds__(64 * NW) void gemm_kernel(const GemmArgs p) {
         kcA[o] = (lane & 7) ^ (((rowA + 8 * o) >> 1) & 7);
         laneA[o] = (u32)((lane >> 3) * p.lda + 8 * kcA[o]);
     }
+    // FULL kernels take any number of rows: a lane whose row lies past the last one reads the last row instead (the
+    // row tile computes rows that the epilogue does not store).  Per instruction j the wavefront-uniform row base is
+    // clamped too, so that the lane part stays non-negative; in every tile but a ragged last one these are the
+    // values above.
+    int ubaseA[ADMA];
+    u32 laneAc[ADMA];
+    if (FULL) {
+#pragma unroll
+        for (int j = 0; j < ADMA; ++j) {
+            const int rb = m0 + 8 * ADMA * w + 8 * j;
+            ubaseA[j] = min(rb, p.M - 1);
+            laneAc[j] = (u32)((min(rb + (lane >> 3), p.M - 1) - ubaseA[j]) * p.lda + 8 * kcA[j & 1]);
+        }
+    }
 
     // ---- B: load-to-LDS role.
     // PLAIN, LN: the LDS tile is [64 rows][32 chunks]; one instruction fills two
@@ -368,8 +382,11 @@ __global__ __launch_bounds__(64 * NW) void gemm_kernel(const GemmArgs p) {
 #pragma unroll
         for (int jj = 0; jj < ADMA / 4; ++jj) {
             const int j = (ADMA / 4) * part + jj;
-            copy16(p.A, rsA, (size_t)(m0 + 8 * ADMA * w + 8 * j) * p.lda + k0, laneA[j & 1],
-                   k0 + 8 * kcA[j & 1] < p.K && m0 + rowA + 8 * j < p.M, dA + (ADMA * w + j) * 64);
+            if (FULL)
+                copy16(p.A, rsA, (size_t)ubaseA[j] * p.lda + k0, laneAc[j], true, dA + (ADMA * w + j) * 64);
+            else
+                copy16(p.A, rsA, (size_t)(m0 + 8 * ADMA * w + 8 * j) * p.lda + k0, laneA[j & 1],
+                       k0 + 8 * kcA[j & 1] < p.K && m0 + rowA + 8 * j < p.M, dA + (ADMA * w + j) * 64);
         }
         if (COOK && part == 3) {
             copy16(p.gain, rsG, (size_t)k0, (u32)(8 * (lane & 7)), k0 + 8 * (lane & 7) < p.K, dG);
@@ -686,7 +703,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_kernel(const GemmArgs p) {
                     u32 d0 = pack_bf16(h[0], h[1]), d1 = pack_bf16(h[2], h[3]);
                     quad_transpose(d0, d1, tup, tsel);
                     const int m = m0 + rl + eq, col = fcol + 32 * u;
-                    if ((FULL || m < p.M) && (FULL || col < p.N)) {
+                    if (m < p.M && (FULL || col < p.N)) {
                         u32x2 o = {d0, d1};
                         *reinterpret_cast<u32x2*>(p.C + (size_t)m * p.ldc + col) = o;
                     }
@@ -724,7 +741,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_kernel(const GemmArgs p) {
                         if (LNE) y[i] = fmaf(r[i], y[i] - mu[i] * cc[tt], cb[tt]);
                     }
                     const int m = m0 + rl + eq, col = scol + 32 * tt;
-                    const bool inside = (FULL || m < p.M) && (FULL || col < p.N);
+                    const bool inside = m < p.M && (FULL || col < p.N);
                     if (MODE == MODE_PLAIN && p.res != nullptr) {
                         // residual epilogue: transpose in fp32, add the residual's four values, round once
                         quad_transpose_f32(y, tup, (eq & 1) != 0);

@@ -488,6 +488,44 @@ def test_tile_order_with_a_short_last_group_ln(M, D, N):
         assert row_rel_err(Y, ref) <= TOL
 
 
+# Any number of rows runs through the kernels without bounds checks as long as the columns and the contraction
+# are complete tiles: the ragged last row tile reads its last valid row in place of the missing ones and stores
+# only the valid ones.  (In place over the residual a stored row past M would be visible as a changed R.)
+@pytest.mark.parametrize("M,D,F", [(1, 64, 128), (257, 128, 256), (300, 256, 512), (1000, 512, 1024), (2047, 1024, 2816)])
+def test_ragged_rows_on_complete_columns_ffn(M, D, F):
+    cpu = bb_inputs.make_ffn(M, D, F, seed=M + F)
+    for variant in (bb.VARIANT_SNAPSHOT1, bb.VARIANT_PRESCALE):
+        if variant == bb.VARIANT_PRESCALE and M <= 16:
+            continue
+        assert ffn_case(cpu, 1e-6, variant=variant) <= TOL
+    assert ffn_case(cpu, 1e-6, unfused=True) <= TOL
+    bb.bb_set_variant(bb.VARIANT_SNAPSHOT1)
+    try:
+        assert residual_case(M, D, F, seed=M) <= TOL
+        assert residual_case(M, D, F, seed=M, in_place="x") <= TOL
+        assert residual_case(M, D, F, seed=M, transposed=True) <= TOL
+    finally:
+        bb.bb_set_variant(bb.VARIANT_AUTO)
+
+
+@pytest.mark.parametrize("M,D,N", [(1, 64, 256), (300, 256, 512), (1000, 512, 1024), (2047, 1024, 2048)])
+def test_ragged_rows_on_complete_columns_ln(M, D, N):
+    cpu = bb_inputs.make_ln(M, D, N, seed=M + N)
+    ref = orc.layernorm_matmul(*cpu, 1e-5)
+    for variant in (bb.VARIANT_PRESCALE, bb.VARIANT_SNAPSHOT1, bb.VARIANT_UNFUSED):
+        bb.bb_set_variant(variant)
+        try:
+            Y = bb.bb_layernorm_matmul(*dev(cpu), 1e-5)
+            torch.cuda.synchronize()
+        finally:
+            bb.bb_set_variant(bb.VARIANT_AUTO)
+        assert row_rel_err(Y, ref) <= TOL
+    d = dev(cpu)
+    Yt = bb.bb_layernorm_matmul_t(d[0], d[1], d[2], d[3].t().contiguous(), 1e-5)
+    torch.cuda.synchronize()
+    assert row_rel_err(Yt, ref) <= TOL
+
+
 # ---------------------------------------------------------------- statistics loop as its own kernel
 @pytest.mark.parametrize("M,D,F", [(17, 72, 136), (130, 264, 712), (300, 520, 1032), (512, 1024, 2816),
                                    (2048, 1024, 2816)])
