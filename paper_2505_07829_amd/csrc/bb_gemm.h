@@ -178,9 +178,10 @@ __device__ __forceinline__ void quad_transpose_f32(float (&y)[4], bool upper, bo
     y[3] = odd ? z1 : q1;
 }
 
-// FULL: every tile is complete (M % BM == 0, N % columns-per-tile == 0,
+// FULL: every tile is complete in the columns and the contraction (N % columns-per-tile == 0,
 // K % 64 == 0) and A and B are smaller than 4 GiB each, so the main loop has no
-// bounds checks and addresses its loads with 32-bit offsets.
+// bounds checks and addresses its loads with 32-bit offsets.  The number of rows is free: lanes of
+// a ragged last row tile read the last valid row, the epilogue stores only valid rows.
 // ODD: the number of contraction steps of a workgroup is odd.
 // SPLIT (PLAIN, GATEUP; for shapes with fewer tiles than half the compute
 // units, i.e. few rows): nsplit workgroups share a tile, each contracts
