@@ -492,12 +492,12 @@ int launch_gemm(const u16* A, int lda, const u16* B0, const u16* B1, int ldb, u1
         std::fprintf(stderr, "[bb] gemm mode %d%s BM %d M %d N %d K %d tiles %dx%d split %d x %d steps\n", MODE,
                      BT ? " (B transposed)" : "", BM, M, N, K, a.tiles_m, a.tiles_n, a.nsplit,
                      do_split ? nk_split : (K + GEMM_BK - 1) / GEMM_BK);
-    // tiles complete in the columns and the contraction (any number of rows: a ragged last row tile reads its last
-    // valid row in place of the missing ones and stores only the valid ones), and operands small enough for the
-    // kernels' 32-bit byte offsets
+    // tiles complete in the contraction (any number of rows and columns: a ragged last tile reads its last valid row
+    // or chunk of columns in place of the missing ones and stores only the valid elements), and operands small
+    // enough for the kernels' 32-bit byte offsets
     const size_t bbytes = BT ? (size_t)N * ldb * 2 : (size_t)K * ldb * 2;
     const bool small = (size_t)M * lda * 2 < (1ull << 32) && bbytes < (1ull << 32);
-    const bool full = (N % ncol == 0) && (K % GEMM_BK == 0) && small;
+    const bool full = (K % GEMM_BK == 0) && small;
     const bool odd = ((do_split ? nk_split : (K + GEMM_BK - 1) / GEMM_BK) & 1) != 0;
     if (do_split) {
         constexpr int SM = (MODE == MODE_PLAIN || MODE == MODE_GATEUP) ? MODE : MODE_PLAIN;   // (the others are never split)

@@ -178,10 +178,10 @@ __device__ __forceinline__ void quad_transpose_f32(float (&y)[4], bool upper, bo
     y[3] = odd ? z1 : q1;
 }
 
-// FULL: every tile is complete in the columns and the contraction (N % columns-per-tile == 0,
-// K % 64 == 0) and A and B are smaller than 4 GiB each, so the main loop has no
-// bounds checks and addresses its loads with 32-bit offsets.  The number of rows is free: lanes of
-// a ragged last row tile read the last valid row, the epilogue stores only valid rows.
+// FULL: every tile is complete in the contraction (K % 64 == 0) and A and B are smaller than 4 GiB
+// each, so the main loop has no bounds checks and addresses its loads with 32-bit offsets.  The numbers
+// of rows and of columns are free: lanes of a ragged last row (column) tile read the last valid row
+// (chunk of columns), the epilogue stores only valid elements.
 // ODD: the number of contraction steps of a workgroup is odd.
 // SPLIT (PLAIN, GATEUP; for shapes with fewer tiles than half the compute
 // units, i.e. few rows): nsplit workgroups share a tile, each contracts
@@ -314,7 +314,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_kernel(const GemmArgs p) {
     const int chunkB = HALF ? ((lane & 15) ^ ((lane >> 4) << 2)) : (l32 ^ (((2 * w + lhi) & 3) << 2));
     const int colB = n0 + 8 * chunkB;
     const bool colB_ok = FULL || colB < p.N;
-    const u32 laneB = (u32)(rowBl * p.ldb + (colB_ok ? 8 * chunkB : 0));
+    // (FULL kernels take any number of columns: a lane whose chunk of columns lies past the last one reads the last
+    // chunk instead; the ragged last column tile computes columns that the epilogue does not store)
+    const u32 laneB = (u32)(rowBl * p.ldb + (FULL ? min(8 * chunkB, p.N - 8 - n0) : (colB_ok ? 8 * chunkB : 0)));
     // BT: like the A tile.  256 tile rows (= output columns; GATEUP: 128 rows of
     // W1^T, then the same 128 of W3^T), BDMA instructions per wavefront, each 8 rows.
     const int rowT = 8 * BDMA * w + (lane >> 3);                 // + 8 j for instruction j
@@ -324,6 +326,18 @@ __global__ __launch_bounds__(64 * NW) void gemm_kernel(const GemmArgs p) {
     for (int o = 0; o < 2; ++o) {
         kcT[o] = (lane & 7) ^ (((rowT + 8 * o) >> 1) & 7);
         laneT[o] = (u32)((lane >> 3) * p.ldb + 8 * kcT[o]);
+    }
+    // (FULL, transposed weights: the rows of B are output columns; clamped like the rows of A)
+    int ubaseT[BDMA];
+    u32 laneTc[BDMA];
+    if (FULL && BT) {
+#pragma unroll
+        for (int q = 0; q < BDMA; ++q) {
+            const int r0 = 8 * BDMA * w + 8 * q;
+            const int nrow = HALF ? n0 + (r0 & 127) : n0 + r0;
+            ubaseT[q] = min(nrow, p.N - 1);
+            laneTc[q] = (u32)((min(nrow + (lane >> 3), p.N - 1) - ubaseT[q]) * p.ldb + 8 * kcT[q & 1]);
+        }
     }
 
     // ---- B: fragment-read role.  Group b = lane / 16 of a transposing read
@@ -361,8 +375,12 @@ __global__ __launch_bounds__(64 * NW) void gemm_kernel(const GemmArgs p) {
                 const int r0 = 8 * BDMA * w + 8 * q;                 // first tile row of the instruction
                 const bool second = HALF && r0 >= 128;
                 const int nrow = HALF ? n0 + (r0 & 127) : n0 + r0;   // first matrix row (output column)
-                copy16(second ? p.B1 : p.B0, second ? rsB1 : rsB0, (size_t)nrow * p.ldb + k0, laneT[q & 1],
-                       k0 + 8 * kcT[q & 1] < p.K && nrow + (lane >> 3) < p.N, dB + (BDMA * w + q) * 64);
+                if (FULL)
+                    copy16(second ? p.B1 : p.B0, second ? rsB1 : rsB0, (size_t)ubaseT[q] * p.ldb + k0, laneTc[q], true,
+                           dB + (BDMA * w + q) * 64);
+                else
+                    copy16(second ? p.B1 : p.B0, second ? rsB1 : rsB0, (size_t)nrow * p.ldb + k0, laneT[q & 1],
+                           k0 + 8 * kcT[q & 1] < p.K && nrow + (lane >> 3) < p.N, dB + (BDMA * w + q) * 64);
             } else if (HALF) {
                 const int idx = NW * q + w;                          // four-row group of the two half tiles
                 const int hf = idx >> 4, rg = idx & 15;
@@ -704,7 +722,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_kernel(const GemmArgs p) {
                     u32 d0 = pack_bf16(h[0], h[1]), d1 = pack_bf16(h[2], h[3]);
                     quad_transpose(d0, d1, tup, tsel);
                     const int m = m0 + rl + eq, col = fcol + 32 * u;
-                    if (m < p.M && (FULL || col < p.N)) {
+                    if (m < p.M && col < p.N) {
                         u32x2 o = {d0, d1};
                         *reinterpret_cast<u32x2*>(p.C + (size_t)m * p.ldc + col) = o;
                     }
@@ -718,7 +736,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_kernel(const GemmArgs p) {
         if (LNE) {
 #pragma unroll
             for (int tt = 0; tt < NT; ++tt) {
-                const bool ok = FULL || ncol + 32 * tt < p.N;
+                const bool ok = ncol + 32 * tt < p.N;
                 cc[tt] = ok ? p.colc[ncol + 32 * tt] : 0.f;
                 cb[tt] = ok ? p.colb[ncol + 32 * tt] : 0.f;
             }
@@ -742,7 +760,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_kernel(const GemmArgs p) {
                         if (LNE) y[i] = fmaf(r[i], y[i] - mu[i] * cc[tt], cb[tt]);
                     }
                     const int m = m0 + rl + eq, col = scol + 32 * tt;
-                    const bool inside = m < p.M && (FULL || col < p.N);
+                    const bool inside = m < p.M && col < p.N;
                     if (MODE == MODE_PLAIN && p.res != nullptr) {
                         // residual epilogue: transpose in fp32, add the residual's four values, round once
                         quad_transpose_f32(y, tup, (eq & 1) != 0);

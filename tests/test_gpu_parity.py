@@ -508,6 +508,48 @@ def test_ragged_rows_on_complete_columns_ffn(M, D, F):
         bb.bb_set_variant(bb.VARIANT_AUTO)
 
 
+# ... and any number of columns: a ragged last column tile reads its last valid chunk of columns in place of the
+# missing ones.  Gate/up with 712 = 5 x 128 + 72 hidden units, down projections with 320 = 256 + 64 and
+# 896 = 3 x 256 + 128 columns (contractions of 768 and 4864: complete steps), ragged rows on top.
+@pytest.mark.parametrize("M,D,F", [(300, 256, 712), (300, 320, 768), (1000, 320, 1352), (700, 896, 4864)])
+def test_ragged_columns_on_complete_contractions_ffn(M, D, F):
+    cpu = bb_inputs.make_ffn(M, D, F, seed=M + F)
+    rows = sample_rows(M, extra=10, seed=2)
+    for variant in (bb.VARIANT_SNAPSHOT1, bb.VARIANT_PRESCALE):
+        assert ffn_case(cpu, 1e-6, rows=rows, variant=variant) <= TOL
+    assert ffn_case(cpu, 1e-6, rows=rows, unfused=True) <= TOL
+    X, g, W1, W3, W2 = cpu
+    ref = orc.rmsnorm_swiglu_ffn(X, g, W1, W3, W2, 1e-6, rows=rows)
+    d = dev(cpu)
+    bb.bb_set_variant(bb.VARIANT_SNAPSHOT1)
+    try:
+        Yt = bb.bb_rmsnorm_swiglu_ffn_t(d[0], d[1], *[w.t().contiguous() for w in d[2:]], 1e-6)
+        Yr = bb.bb_rmsnorm_swiglu_ffn_residual(*d, d[0], 1e-6)
+        torch.cuda.synchronize()
+    finally:
+        bb.bb_set_variant(bb.VARIANT_AUTO)
+    assert row_rel_err(Yt[rows], ref) <= TOL
+    assert row_rel_err(Yr[rows], ref + X[rows].double().numpy()) <= TOL
+
+
+@pytest.mark.parametrize("M,D,N", [(300, 256, 712), (1000, 320, 1352), (2047, 1024, 2056)])
+def test_ragged_columns_on_complete_contractions_ln(M, D, N):
+    cpu = bb_inputs.make_ln(M, D, N, seed=M + N)
+    ref = orc.layernorm_matmul(*cpu, 1e-5)
+    for variant in (bb.VARIANT_PRESCALE, bb.VARIANT_SNAPSHOT1, bb.VARIANT_UNFUSED):
+        bb.bb_set_variant(variant)
+        try:
+            Y = bb.bb_layernorm_matmul(*dev(cpu), 1e-5)
+            torch.cuda.synchronize()
+        finally:
+            bb.bb_set_variant(bb.VARIANT_AUTO)
+        assert row_rel_err(Y, ref) <= TOL
+    d = dev(cpu)
+    Yt = bb.bb_layernorm_matmul_t(d[0], d[1], d[2], d[3].t().contiguous(), 1e-5)
+    torch.cuda.synchronize()
+    assert row_rel_err(Yt, ref) <= TOL
+
+
 @pytest.mark.parametrize("M,D,N", [(1, 64, 256), (300, 256, 512), (1000, 512, 1024), (2047, 1024, 2048)])
 def test_ragged_rows_on_complete_columns_ln(M, D, N):
     cpu = bb_inputs.make_ln(M, D, N, seed=M + N)
